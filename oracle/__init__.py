@@ -1,0 +1,21 @@
+"""CPU oracle for the Bamboo stage hot path (arXiv 2204.12013).
+
+TEST INFRASTRUCTURE ONLY.  Nothing in the product package may import this
+package; only the tests, the smoke check and the benchmark's cpu_baseline leg
+do.  It shares no code with the HIP path: plain numpy float64, one function per
+mathematical step, no blocking or fusion.
+
+Modules
+  layer     transformer layer forward/backward (the computation that FNC/BNC
+            and FRC/BRC of Section 5.1 both denote)
+  schedule  1F1B program, slot timeline, FRC insertion, failover merge
+            (Sections 2, 5.2)
+  stage     a stage executing an instruction list with simulated neighbours
+            (Sections 5.1, 5.2: eager FRC, lazy BRC, recovery)
+
+Pins (see tests/test_oracle_*.py): finite differences, an independent autograd
+implementation, closed forms for the timeline, the paper's worked values, brute
+force over tiny pipelines.  Input distributions for biases/LayerNorm parameters
+and the upstream-gradient scale are not fixed by the paper: parity unpinned for
+those choices (they are inputs, not arithmetic).
+"""

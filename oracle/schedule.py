@@ -1,0 +1,217 @@
+"""Reference slot schedule of one Bamboo stage (oracle; test infrastructure).
+
+Integers only.  Follows the paper's description in prose (its figures are not
+available): the 1F1B schedule of Section 2, instruction groups and the static
+per-stage schedule of Sections 4 and 5.2, eager FRC placed before the stage
+talks to its successor (Section 5.2 "Scheduling"), and the four merge rules of
+the failover schedule (Section 5.2 "Lazy BRC and Recovery").
+
+An instruction is a tuple (op, lane, mb, arg):
+  op    one of the codes below
+  lane  0 = main stream, 1 = FRC stream
+  mb    micro-batch id, -1 when the instruction has none
+  arg   FWD/BWD: own stash slot (mb mod C_own); FRC/BRC: shadow stash slot (mb);
+        comm ops: id of the peer stage; BUBBLE: ticks; JOIN: last FRC waited for
+        (-1: all); otherwise 0
+"""
+
+RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, FWD, BWD, FRC, BRC, BUBBLE, JOIN, ALLREDUCE, APPLY = range(12)
+OP_NAMES = ("RECV_ACT", "SEND_ACT", "RECV_GRAD", "SEND_GRAD", "FWD", "BWD",
+            "FRC", "BRC", "BUBBLE", "JOIN", "ALLREDUCE", "APPLY")
+
+
+def warmup_depth(P, s, M):
+    """Forwards a 1F1B stage runs before its first backward, minus one."""
+    return min(P - 1 - s, M)
+
+
+def own_slots(P, s, M):
+    """Peak number of in-flight micro-batches of stage s (Section 5.2: with four
+    stages, the second stage holds 3 and the third holds 2)."""
+    return min(P - s, M)
+
+
+def compute_order(P, s, M):
+    """1F1B compute sequence of stage s as a list of ('F'|'B', k)."""
+    w = warmup_depth(P, s, M)
+    seq = [("F", k) for k in range(w)]
+    for i in range(M - w):
+        seq.append(("F", w + i))
+        seq.append(("B", i))
+    seq += [("B", k) for k in range(M - w, M)]
+    return seq
+
+
+def timeline(P, M, tick_F, tick_B):
+    """Simulate all P stages with zero communication latency.
+
+    tick_F / tick_B: int or per-stage sequences.  Returns (start, end, makespan)
+    where start[s][j], end[s][j] are the times of the j-th compute instruction of
+    stage s.  A forward waits for the same micro-batch's forward on the previous
+    stage; a backward waits for its backward on the next stage; instructions of a
+    stage run in program order.
+    """
+    tf = [tick_F] * P if isinstance(tick_F, int) else list(tick_F)
+    tb = [tick_B] * P if isinstance(tick_B, int) else list(tick_B)
+    seqs = [compute_order(P, s, M) for s in range(P)]
+    start = [[None] * len(q) for q in seqs]
+    end = [[None] * len(q) for q in seqs]
+    done = {}                      # (kind, stage, k) -> end time
+    pos = [0] * P
+    clock = [0] * P
+    progressed = True
+    while progressed:
+        progressed = False
+        for s in range(P):
+            while pos[s] < len(seqs[s]):
+                kind, k = seqs[s][pos[s]]
+                if kind == "F":
+                    dep = done.get(("F", s - 1, k)) if s > 0 else 0
+                    dur = tf[s]
+                else:
+                    dep = done.get(("B", s + 1, k)) if s < P - 1 else 0
+                    dur = tb[s]
+                if dep is None:
+                    break
+                t0 = max(clock[s], dep)
+                start[s][pos[s]] = t0
+                end[s][pos[s]] = t0 + dur
+                clock[s] = t0 + dur
+                done[(kind, s, k)] = t0 + dur
+                pos[s] += 1
+                progressed = True
+    assert all(pos[s] == len(seqs[s]) for s in range(P)), "1F1B deadlock"
+    return start, end, max(clock)
+
+
+def _head_comm(prev, cur, P, s):
+    """Communication instructions at the head of cur's group: first the send of
+    what the previous compute produced, then the receive cur needs."""
+    out = []
+    if prev is not None:
+        kind, k = prev
+        if kind == "F" and s < P - 1:
+            out.append((SEND_ACT, 0, k, s + 1))
+        if kind == "B" and s > 0:
+            out.append((SEND_GRAD, 0, k, s - 1))
+    if cur is not None:
+        kind, k = cur
+        if kind == "F" and s > 0:
+            out.append((RECV_ACT, 0, k, s - 1))
+        if kind == "B" and s < P - 1:
+            out.append((RECV_GRAD, 0, k, s + 1))
+    return out
+
+
+def stage_program(P, s, M, frc=True, tick_F=1, tick_B=2, bubbles=True):
+    """Instruction list of stage s for one iteration (no failure)."""
+    seq = compute_order(P, s, M)
+    C = own_slots(P, s, M)
+    start, end, makespan = timeline(P, M, tick_F, tick_B)
+    prog, prev, clock = [], None, 0
+    for j, cur in enumerate(seq):
+        gap = start[s][j] - clock
+        if bubbles and gap > 0:
+            prog.append((BUBBLE, 0, -1, gap))
+        prog += _head_comm(prev, cur, P, s)
+        kind, k = cur
+        if kind == "F":
+            prog.append((FWD, 0, k, k % C))
+            if frc:
+                prog.append((FRC, 1, k, k))
+        else:
+            prog.append((BWD, 0, k, k % C))
+        clock = end[s][j]
+        prev = cur
+    tail = makespan - clock
+    prog += _head_comm(prev, None, P, s)
+    if bubbles and tail > 0:
+        prog.append((BUBBLE, 0, -1, tail))
+    prog += [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
+    return prog
+
+
+def lost_backwards(P, s, M, k_fail):
+    """Backwards stage s (and hence its successor) had completed when the send
+    of micro-batch k_fail's activation to the successor fails."""
+    seq = compute_order(P, s, M)
+    j = seq.index(("F", k_fail))
+    return sum(1 for kind, _ in seq[:j] if kind == "B")
+
+
+def prefix_until_failure(P, s, M, k_fail, frc=True, tick_F=1, tick_B=2, bubbles=True):
+    """The part of the normal program that ran before the failure was detected:
+    everything up to and including FWD(k_fail) and its FRC."""
+    prog = stage_program(P, s, M, frc, tick_F, tick_B, bubbles)
+    last = max(i for i, ins in enumerate(prog)
+               if ins[2] == k_fail and ins[0] in (FWD, FRC))
+    return prog[:last + 1]
+
+
+def failover_program(P, s, M, k_fail):
+    """Failover schedule of shadow stage s after its successor s+1 is lost while
+    stage s tries to send it the activation of micro-batch k_fail.
+
+    (i)   wait for the FRC stream up to FRC(k_fail);
+    (ii)  replay: BRC over the micro-batches whose successor-side backward had
+          already run (their weight-gradient contributions died with the victim);
+    (iii) the rest of stage s's 1F1B program with the victim's groups merged in:
+          communication first, victim<->shadow traffic removed, the victim's
+          external traffic before the shadow's, backward work before forward work.
+    """
+    assert 0 <= s < P - 1 and 0 <= k_fail < M
+    seq = compute_order(P, s, M)
+    C = own_slots(P, s, M)
+    has_far = s + 2 < P                     # the victim had a successor of its own
+    b = lost_backwards(P, s, M, k_fail)
+    prog = [(JOIN, 0, -1, k_fail)]
+    for k in range(b):
+        if has_far:
+            prog.append((RECV_GRAD, 0, k, s + 2))
+        prog.append((BRC, 0, k, k))
+    rest = seq[seq.index(("F", k_fail)) + 1:]
+    # groups: a backward starts a new group; a forward joins the group of the
+    # backward just before it (backward work is ordered first inside a group)
+    groups = []
+    for item in rest:
+        if item[0] == "B" or not groups or groups[-1][-1][0] == "F":
+            groups.append([item])
+        else:
+            groups[-1].append(item)
+    unsent_act = [k_fail]                   # FRC outputs the far stage has not got
+    unsent_grad = []                        # own input-gradients not yet sent back
+    for grp in groups + [[]]:
+        # victim's external communication first
+        if has_far:
+            prog += [(SEND_ACT, 0, k, s + 2) for k in unsent_act]
+        unsent_act = []
+        for kind, k in grp:
+            if kind == "B" and has_far:
+                prog.append((RECV_GRAD, 0, k, s + 2))
+        # then the shadow's own
+        if s > 0:
+            prog += [(SEND_GRAD, 0, k, s - 1) for k in unsent_grad]
+        unsent_grad = []
+        for kind, k in grp:
+            if kind == "F" and s > 0:
+                prog.append((RECV_ACT, 0, k, s - 1))
+        # compute: backward (victim's then own), then forward (own then victim's)
+        for kind, k in grp:
+            if kind == "B":
+                prog.append((BRC, 0, k, k))
+                prog.append((BWD, 0, k, k % C))
+                unsent_grad.append(k)
+        for kind, k in grp:
+            if kind == "F":
+                prog.append((FWD, 0, k, k % C))
+                prog.append((FRC, 0, k, k))
+                unsent_act.append(k)
+    prog += [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
+    return prog
+
+
+def fmt(prog):
+    return " ".join(
+        OP_NAMES[op] + ("" if mb < 0 else "(%d)" % mb) +
+        ("[%d]" % arg if op in (BUBBLE,) else "") + ("@1" if lane else "")
+        for op, lane, mb, arg in prog)

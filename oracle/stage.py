@@ -1,0 +1,123 @@
+"""One Bamboo stage executing an instruction list (oracle; test infrastructure).
+
+Section 5.1: node s runs normal computation (FNC/BNC) over its own layers and
+redundant computation (FRC/BRC) over a replica of its successor's layers.
+Section 5.2: FRC is eager and its intermediates are kept until a preemption;
+BRC is lazy and recomputes the gradients lost with the victim.
+
+Neighbours are simulated in the same process:
+  stage s-1  = a table of inputs x_k
+  stage s+1  = the same layer code over the shadow parameter values, with its own
+               caches and its own gradient accumulator (lost on preemption)
+  stage s+2  = a table of upstream gradients g_z_k
+"""
+import numpy as np
+
+from . import layer as L
+from . import schedule as S
+
+
+def stash_record_index(slot, layer, n_layers):
+    """Index of the record (slot, layer) inside a stash arena, in records."""
+    return slot * n_layers + layer
+
+
+def _acc(dst, grads):
+    """dst += grads, layer by layer, tensor by tensor."""
+    for d, g in zip(dst, grads):
+        for name in L.PARAM_NAMES:
+            d[name] = d[name] + g[name]
+
+
+def _zeros_like_params(layers):
+    return [{n: np.zeros_like(p[n]) for n in L.PARAM_NAMES} for p in layers]
+
+
+class StageSim:
+    def __init__(self, arch, own_layers, shadow_layers, B, S_len, n_h, P, s, M,
+                 x_table, gz_table, eps=1e-5):
+        self.arch, self.B, self.S, self.n_h, self.eps = arch, B, S_len, n_h, eps
+        self.own, self.shadow = own_layers, shadow_layers
+        self.P, self.s, self.M = P, s, M
+        self.x, self.gz = x_table, gz_table
+        self.C_own = S.own_slots(P, s, M)
+        self.own_stash = {}        # slot -> (k, caches)
+        self.shadow_stash = {}     # slot -> (k, caches)
+        self.G_own = _zeros_like_params(own_layers)
+        self.G_shadow = _zeros_like_params(shadow_layers)
+        # simulated successor
+        self.succ_alive = True
+        self.succ_cache = {}
+        self.G_succ = _zeros_like_params(shadow_layers)
+        self.succ_bwd_done = []
+        self.y, self.z_frc, self.z_succ, self.gy, self.gx = {}, {}, {}, {}, {}
+        self.bwd_done = set()
+        self.trace = []
+
+    # ---- the successor's own work (only while it is alive)
+    def _succ_backward(self, k):
+        if k not in self.succ_cache:
+            self.z_succ[k], self.succ_cache[k] = L.stack_fwd(
+                self.arch, self.shadow, self.y[k], self.B, self.S, self.n_h, self.eps)
+        gy, grads = L.stack_bwd(self.arch, self.shadow, self.succ_cache.pop(k), self.gz[k])
+        _acc(self.G_succ, grads)
+        self.succ_bwd_done.append(k)
+        return gy
+
+    def preempt_successor(self):
+        """The successor disappears: its caches and accumulated gradients are gone."""
+        self.succ_alive = False
+        self.succ_cache = {}
+        self.G_succ = None
+
+    # ---- interpreter
+    def run(self, prog):
+        for op, lane, k, arg in prog:
+            self.trace.append((op, k))
+            if op == S.FWD:
+                assert arg == k % self.C_own
+                assert arg not in self.own_stash, "own stash slot %d still live" % arg
+                self.y[k], caches = L.stack_fwd(self.arch, self.own, self.x[k],
+                                                self.B, self.S, self.n_h, self.eps)
+                self.own_stash[arg] = (k, caches)
+            elif op == S.FRC:
+                assert arg == k and k in self.y
+                assert arg not in self.shadow_stash
+                self.z_frc[k], caches = L.stack_fwd(self.arch, self.shadow, self.y[k],
+                                                    self.B, self.S, self.n_h, self.eps)
+                self.shadow_stash[arg] = (k, caches)
+            elif op == S.RECV_GRAD:
+                if arg == self.s + 1:          # from the live successor
+                    assert self.succ_alive
+                    self.gy[k] = self._succ_backward(k)
+                # from s+2 (after failover): g_z_k is read from the table by BRC
+            elif op == S.BWD:
+                kk, caches = self.own_stash.pop(arg)
+                assert kk == k
+                self.gx[k], grads = L.stack_bwd(self.arch, self.own, caches, self.gy[k])
+                _acc(self.G_own, grads)
+                self.bwd_done.add(k)
+            elif op == S.BRC:
+                kk, caches = self.shadow_stash.pop(arg)
+                assert kk == k
+                gy, grads = L.stack_bwd(self.arch, self.shadow, caches, self.gz[k])
+                _acc(self.G_shadow, grads)
+                if k not in self.bwd_done:     # replayed micro-batches already have theirs
+                    self.gy[k] = gy
+                else:
+                    self.gy_replay = getattr(self, "gy_replay", {})
+                    self.gy_replay[k] = gy
+            # SEND_*, RECV_ACT, BUBBLE, JOIN, ALLREDUCE, APPLY: no arithmetic
+        return self
+
+
+def run_no_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, frc=True, eps=1e-5):
+    sim = StageSim(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, eps)
+    return sim.run(S.stage_program(P, s, M, frc=frc))
+
+
+def run_with_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, k_fail, eps=1e-5):
+    sim = StageSim(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, eps)
+    sim.run(S.prefix_until_failure(P, s, M, k_fail))
+    sim.preempt_successor()
+    return sim.run(S.failover_program(P, s, M, k_fail))

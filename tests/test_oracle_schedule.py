@@ -1,0 +1,189 @@
+"""Pins for oracle/schedule.py (integers only; no HIP path involved)."""
+import itertools
+import os
+
+import pytest
+
+from oracle import schedule as S
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_in_flight_counts_of_the_four_stage_example():
+    """Section 5.2: in the 4-stage 1F1B figure the second stage holds 3 active
+    micro-batches and the third holds 2."""
+    assert S.own_slots(4, 1, 8) == 3 and S.own_slots(4, 2, 8) == 2
+    # and the program really reaches, and never exceeds, that many
+    for P, M in itertools.product(range(1, 6), range(1, 9)):
+        for s in range(P):
+            live = peak = 0
+            for kind, _ in S.compute_order(P, s, M):
+                live += 1 if kind == "F" else -1
+                peak = max(peak, live)
+                assert live >= 0
+            assert live == 0 and peak == S.own_slots(P, s, M)
+
+
+def test_every_microbatch_forward_then_backward_once():
+    for P, M in itertools.product(range(1, 6), range(1, 9)):
+        for s in range(P):
+            seq = S.compute_order(P, s, M)
+            assert sorted(seq) == sorted([("F", k) for k in range(M)] + [("B", k) for k in range(M)])
+            for k in range(M):
+                assert seq.index(("F", k)) < seq.index(("B", k))
+            # one-forward-one-backward: after warm-up, kinds alternate
+            w = S.warmup_depth(P, s, M)
+            steady = seq[w:w + 2 * (M - w)]
+            assert all(steady[i][0] == "FB"[i % 2] for i in range(len(steady)))
+
+
+def test_uniform_pipeline_closed_form():
+    """Equal stages: makespan (M+P-1)(tF+tB); each stage idles (P-1)(tF+tB),
+    i.e. the textbook bubble fraction (P-1)/(M+P-1)."""
+    for P, M, tf, tb in [(4, 8, 1, 2), (2, 3, 1, 1), (8, 16, 1, 2), (3, 3, 5, 7), (5, 2, 1, 2)]:
+        start, end, makespan = S.timeline(P, M, tf, tb)
+        assert makespan == (M + P - 1) * (tf + tb)
+        for s in range(P):
+            busy = sum(e - b for b, e in zip(start[s], end[s]))
+            assert busy == M * (tf + tb)
+            assert makespan - busy == (P - 1) * (tf + tb)
+
+
+def test_bubble_of_the_unequal_pair_example():
+    """Section 5.2 / Figure 9: a stage whose forward takes t next to a successor
+    1.2x slower in both passes waits 0.6t at the barrier (t = 10 ticks, backward
+    = 2 x forward)."""
+    M = 6
+    start, end, _ = S.timeline(2, M, [10, 12], [20, 24])
+    seq = S.compute_order(2, 0, M)
+    gaps = []
+    for j in range(1, len(seq)):
+        gaps.append((seq[j], start[0][j] - end[0][j - 1]))
+    steady = [g for (kind, k), g in gaps if kind == "B" and 1 <= k <= M - 2]
+    assert steady and all(g == 6 for g in steady), gaps
+
+
+def test_hand_derived_timeline_of_the_bert_stage():
+    rows = []
+    makespan = None
+    for line in open(os.path.join(GOLDEN, "cfg_bert_stage1_timeline.txt")):
+        if line.startswith("# makespan"):
+            makespan = int(line.split()[-1])
+        if line.startswith("#") or not line.strip():
+            continue
+        kind, k, a, b = line.split()
+        rows.append(((kind, int(k)), int(a), int(b)))
+    start, end, mk = S.timeline(4, 8, 1, 2)
+    seq = S.compute_order(4, 1, 8)
+    assert mk == makespan == 33
+    assert [(seq[j], start[1][j], end[1][j]) for j in range(len(seq))] == rows
+    prog = S.stage_program(4, 1, 8, frc=True)
+    bubbles = [a for op, _, _, a in prog if op == S.BUBBLE]
+    assert bubbles == [1, 4, 1, 1, 2] and sum(bubbles) == 9
+    # the bubbles after the first forward hold exactly the 8 ticks that 8 FRCs
+    # of one tick each need
+    assert sum(bubbles[1:]) == 8
+
+
+def test_program_structure():
+    for P, M in itertools.product(range(2, 6), range(1, 7)):
+        for s in range(P):
+            for frc in (False, True):
+                prog = S.stage_program(P, s, M, frc=frc)
+                ops = [i[0] for i in prog]
+                assert ops[-3:] == [S.JOIN, S.ALLREDUCE, S.APPLY]
+                C = S.own_slots(P, s, M)
+                for j, (op, lane, k, arg) in enumerate(prog):
+                    if op in (S.FWD, S.BWD):
+                        assert lane == 0 and arg == k % C
+                    if op == S.FRC:
+                        assert lane == 1 and arg == k and prog[j - 1][:3] == (S.FWD, 0, k)
+                    if op == S.SEND_ACT:
+                        assert arg == s + 1 and s < P - 1
+                    if op == S.RECV_ACT:
+                        assert arg == s - 1 and s > 0
+                assert ops.count(S.FRC) == (M if frc else 0)
+                assert ops.count(S.FWD) == ops.count(S.BWD) == M
+                assert ops.count(S.SEND_ACT) == ops.count(S.RECV_GRAD) == (M if s < P - 1 else 0)
+                assert ops.count(S.RECV_ACT) == ops.count(S.SEND_GRAD) == (M if s > 0 else 0)
+                # FRC(k) sits between FWD(k) and the send to the successor
+                if frc and s < P - 1:
+                    for k in range(M):
+                        i_frc = prog.index((S.FRC, 1, k, k))
+                        i_send = prog.index((S.SEND_ACT, 0, k, s + 1))
+                        assert i_frc < i_send
+                # total bubble time + busy time = makespan
+                _, _, mk = S.timeline(P, M, 1, 2)
+                assert sum(a for op, _, _, a in prog if op == S.BUBBLE) + 3 * M == mk
+
+
+def _groups(prog):
+    """Split at every comm->compute->comm change: a group = comm*, compute*."""
+    comm = {S.RECV_ACT, S.SEND_ACT, S.RECV_GRAD, S.SEND_GRAD}
+    comp = {S.FWD, S.BWD, S.FRC, S.BRC}
+    groups, cur, seen_compute = [], [], False
+    for ins in prog:
+        if ins[0] in comm and seen_compute:
+            groups.append(cur)
+            cur, seen_compute = [], False
+        if ins[0] in comp:
+            seen_compute = True
+        if ins[0] in comm or ins[0] in comp:
+            cur.append(ins)
+    if cur:
+        groups.append(cur)
+    return groups
+
+
+def test_failover_merge_rules():
+    """Section 5.2, rules (1)-(4) of the merged failover schedule."""
+    comm = {S.RECV_ACT, S.SEND_ACT, S.RECV_GRAD, S.SEND_GRAD}
+    for P, M in itertools.product(range(2, 6), range(1, 7)):
+        for s in range(P - 1):
+            for k_fail in range(M):
+                b = S.lost_backwards(P, s, M, k_fail)
+                w = S.warmup_depth(P, s, M)
+                assert b == max(0, k_fail - w)
+                pre = S.prefix_until_failure(P, s, M, k_fail)
+                post = S.failover_program(P, s, M, k_fail)
+                assert post[0] == (S.JOIN, 0, -1, k_fail)
+                # rule 2: nothing is exchanged with the victim any more
+                assert not [i for i in post if i[0] in comm and i[3] == s + 1]
+                # after the failure everything runs on lane 0
+                assert all(i[1] == 0 for i in post)
+                # groups can only be told apart where every group has some communication left
+                for g in (_groups(post) if (s > 0 and s + 2 < P) else []):
+                    kinds = [i[0] in comm for i in g]
+                    # rule 1: communication first
+                    assert kinds == sorted(kinds, reverse=True)
+                    # rule 3: the victim's external traffic (peer s+2) first
+                    peers = [i[3] for i in g if i[0] in comm]
+                    far = [p == s + 2 for p in peers]
+                    assert far == sorted(far, reverse=True)
+                    # rule 4: backward work before forward work
+                    is_bwd = [i[0] in (S.BRC, S.BWD) for i in g if i[0] not in comm]
+                    assert is_bwd == sorted(is_bwd, reverse=True)
+                whole = pre + post
+                for k in range(M):
+                    assert sum(1 for i in whole if i[0] == S.FRC and i[2] == k) == 1
+                    assert sum(1 for i in whole if i[0] == S.BRC and i[2] == k) == 1
+                    assert sum(1 for i in whole if i[0] == S.FWD and i[2] == k) == 1
+                    assert sum(1 for i in whole if i[0] == S.BWD and i[2] == k) == 1
+                    i_brc = whole.index((S.BRC, 0, k, k))
+                    i_bwd = [j for j, i in enumerate(whole) if i[0] == S.BWD and i[2] == k][0]
+                    assert (i_brc < i_bwd) == (k >= b)      # replayed ones come after
+                # shadow-gradient accumulation order is 0..M-1
+                assert [i[2] for i in whole if i[0] == S.BRC] == list(range(M))
+                if s + 2 < P:
+                    sent = [i[2] for i in post if i[0] == S.SEND_ACT]
+                    assert sent == list(range(k_fail, M))
+                    assert [i[2] for i in post if i[0] == S.RECV_GRAD] == list(range(M))
+
+
+def test_failover_example_of_the_bert_stage():
+    post = S.failover_program(4, 1, 8, 5)
+    text = S.fmt(post)
+    assert text.startswith("JOIN RECV_GRAD(0) BRC(0) RECV_GRAD(1) BRC(1) RECV_GRAD(2) BRC(2) "
+                           "SEND_ACT(5) RECV_GRAD(3) RECV_ACT(6) BRC(3) BWD(3) FWD(6) FRC(6) "
+                           "SEND_ACT(6) RECV_GRAD(4) SEND_GRAD(3) RECV_ACT(7) BRC(4) BWD(4) FWD(7) FRC(7)")
+    assert text.endswith("BRC(7) BWD(7) SEND_GRAD(7) JOIN ALLREDUCE APPLY")

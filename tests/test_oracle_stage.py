@@ -1,0 +1,106 @@
+"""Pins for oracle/stage.py: the paper's two invariants, by brute force on tiny
+pipelines (no HIP path involved).
+
+Section 5.1: FRC on node n is exactly FNC of node n+1.
+Sections 1, 5.2: after a preemption no computation is wasted and the lost
+gradients are recomputed, so the iteration ends with the gradients of the
+failure-free run.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import layer as L
+from oracle import schedule as S
+from oracle import stage as St
+
+
+def _layers(rng, n, H, F):
+    out = []
+    for _ in range(n):
+        p = {}
+        for name, shp in L.param_shapes(H, F).items():
+            p[name] = rng.standard_normal(shp) * 0.2 + (1.0 if name in ("g1", "g2") else 0.0)
+        out.append(p)
+    return out
+
+
+def _setup(arch, P, s, M, n_own=1, n_shadow=1, seed=0):
+    H, n_h, F, S_len, B = 8, 2, 16, 4, 1
+    rng = np.random.default_rng(seed)
+    own, shadow = _layers(rng, n_own, H, F), _layers(rng, n_shadow, H, F)
+    x = {k: rng.standard_normal((B * S_len, H)) for k in range(M)}
+    gz = {k: rng.standard_normal((B * S_len, H)) for k in range(M)}
+    return (arch, own, shadow, B, S_len, n_h, P, s, M, x, gz)
+
+
+@pytest.mark.parametrize("arch", [0, 1])
+def test_frc_equals_successor_forward(arch):
+    args = _setup(arch, 4, 1, 5, n_own=2, n_shadow=2)
+    sim = St.run_no_failure(*args)
+    for k in range(5):
+        assert np.array_equal(sim.z_frc[k], sim.z_succ[k])
+    assert all(not sim.own_stash for _ in [0])
+    assert sorted(sim.shadow_stash) == list(range(5))       # FRC stash kept for the whole iteration
+    # FRC off: same own results, nothing stashed
+    sim2 = St.run_no_failure(*args, frc=False)
+    assert not sim2.shadow_stash and not sim2.z_frc
+    for k in range(5):
+        assert np.array_equal(sim.gx[k], sim2.gx[k])
+
+
+def test_stage_equals_one_deep_stack():
+    """Own + shadow layers chained by the stage give what a single stack of all
+    the layers gives (forward output and input gradient)."""
+    arch, own, shadow, B, S_len, n_h, P, s, M, x, gz = _setup(1, 3, 0, 2, n_own=2, n_shadow=1)
+    sim = St.run_no_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz)
+    for k in range(M):
+        z, caches = L.stack_fwd(arch, own + shadow, x[k], B, S_len, n_h)
+        gx, grads = L.stack_bwd(arch, own + shadow, caches, gz[k])
+        assert np.allclose(z, sim.z_frc[k], atol=1e-13)
+        assert np.allclose(gx, sim.gx[k], atol=1e-13)
+
+
+def test_failover_reproduces_failure_free_gradients_brute_force():
+    n_cases = 0
+    for arch in (0, 1):
+        for P, M in itertools.product(range(2, 5), range(1, 6)):
+            for s in range(P - 1):
+                args = _setup(arch, P, s, M, seed=P * 10 + M)
+                ref = St.run_no_failure(*args)
+                for k_fail in range(M):
+                    sim = St.run_with_failure(*args, k_fail)
+                    n_cases += 1
+                    assert sim.G_succ is None
+                    for a, b in zip(sim.G_own, ref.G_own):
+                        for n in L.PARAM_NAMES:
+                            assert np.array_equal(a[n], b[n])
+                    for a, b in zip(sim.G_shadow, ref.G_succ):
+                        for n in L.PARAM_NAMES:
+                            assert np.array_equal(a[n], b[n]), (P, M, s, k_fail, n)
+                    for k in range(M):
+                        assert np.array_equal(sim.gx[k], ref.gx[k])
+                        assert np.array_equal(sim.z_frc[k], ref.z_succ[k])
+                    assert not sim.own_stash and not sim.shadow_stash
+                    # the replayed BRCs reproduce the g_y the victim had sent
+                    for k, gy in getattr(sim, "gy_replay", {}).items():
+                        assert np.array_equal(gy, ref.gy[k])
+    assert n_cases > 100
+
+
+def test_too_small_own_stash_is_detected():
+    """The executor refuses to overwrite a live slot, so a capacity below the
+    peak in-flight count cannot go unnoticed."""
+    args = _setup(0, 4, 0, 6)
+    sim = St.StageSim(*args)
+    sim.C_own = 3                                   # stage 0 of 4 needs 4
+    prog = [(op, lane, k, (k % 3 if op in (S.FWD, S.BWD) else a))
+            for op, lane, k, a in S.stage_program(4, 0, 6)]
+    with pytest.raises(AssertionError):
+        sim.run(prog)
+
+
+def test_record_index():
+    assert St.stash_record_index(0, 0, 6) == 0
+    assert St.stash_record_index(2, 3, 6) == 15
