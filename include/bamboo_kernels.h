@@ -1,0 +1,71 @@
+/*
+ * bamboo_kernels.h -- C ABI of the individual layer kernels the Bamboo stage
+ * is built from (arXiv 2204.12013, Section 5.1: FNC/BNC and FRC/BRC are the
+ * same layer computation; the paper leaves the layer math to the models it
+ * trains, Section 7 Table 1: BERT-Large, GPT-2).  Exposed so that each kernel
+ * can be checked and timed on its own.
+ *
+ * All data pointers are device pointers owned by the caller; `stream` is a
+ * hipStream_t passed as void*.  Calls enqueue and return.  dtype: 0 fp32,
+ * 1 bf16 storage with fp32 accumulation.  impl: 0 automatic (MFMA kernel when it
+ * covers the shape, vector-ALU kernel otherwise), 1 vector-ALU kernel,
+ * 2 MFMA kernel (BAMBOO_E_STATE if it does not cover the shape).
+ * Return: 0 or a negative bamboo_status (see bamboo_stage.h).
+ * Tensors are row-major; "tokens" T = batch * seq.
+ */
+#ifndef BAMBOO_KERNELS_H
+#define BAMBOO_KERNELS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Y[T,N] = X[T,K] W[K,N] + bias[N] (+ res[T,N] if res != NULL).
+ * If gelu_out != NULL: Y holds the pre-activation h (rounded to storage) and
+ * gelu_out[T,N] = GELU(h) (erf form) of the stored value. */
+int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const void* W, const void* bias,
+                  const void* res, void* Y, void* gelu_out, void* stream);
+
+/* dX[T,K] = dY[T,N] W[K,N]^T (+ res[T,K] if res != NULL).
+ * If h_in != NULL (and res == NULL): dX = (dY W^T) * GELU'(h_in[T,K]) and
+ * gelu_out[T,K] = GELU(h_in). */
+int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY, const void* W, const void* res,
+                        const void* h_in, void* dX, void* gelu_out, void* stream);
+
+/* dW[K,N] (fp32) += X[T,K]^T dY[T,N]. */
+int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X, const void* dY, float* dW,
+                         void* stream);
+
+/* out[N] (fp32) += sum over tokens of A[T,N]; partial: fp32 scratch of
+ * bk_colsum_scratch_floats(N) floats.  Fixed summation order. */
+int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream);
+uint64_t bk_colsum_scratch_floats(int N);
+
+/* Softmax attention.  qkv[T,3H] = queries | keys | values, head h = columns
+ * h*d..(h+1)*d-1 of each third; scores scaled by 1/sqrt(d); causal != 0 masks
+ * keys after the query.  ctx[T,H]; lse[batch,heads,seq] fp32 = log-sum-exp of
+ * the scaled scores of each row. */
+int bk_attention_fwd(int dtype, int impl, int batch, int seq, int heads, int d, int causal, const void* qkv, void* ctx,
+                     float* lse, void* stream);
+/* dqkv[T,3H] from dctx[T,H], recomputing the probabilities from lse.
+ * delta: fp32 scratch [batch,heads,seq]. */
+int bk_attention_bwd(int dtype, int impl, int batch, int seq, int heads, int d, int causal, const void* qkv,
+                     const void* ctx, const float* lse, const void* dctx, void* dqkv, float* delta, void* stream);
+
+/* y = gamma * (r - mean) * rstd + beta per token row; stats[2t] = mean,
+ * stats[2t+1] = rstd = 1/sqrt(biased variance + eps). */
+int bk_layernorm_fwd(int dtype, int T, int H, float eps, const void* r, const void* gamma, const void* beta, void* y,
+                     float* stats, void* stream);
+/* dr = LayerNorm backward of dout (+ add[T,H] if add != NULL); dgamma, dbeta
+ * (fp32) += their token sums.  partial: fp32 scratch of
+ * bk_layernorm_bwd_scratch_floats(H) floats. */
+int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, const float* stats, const void* gamma,
+                     const void* add, void* dr, float* dgamma, float* dbeta, float* partial, void* stream);
+uint64_t bk_layernorm_bwd_scratch_floats(int H);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAMBOO_KERNELS_H */

@@ -1,0 +1,221 @@
+/*
+ * bamboo_stage.h -- C ABI of the Bamboo stage hot path on MI355X (gfx950).
+ *
+ * One pipeline stage's per-micro-batch training computation with redundant
+ * computation (arXiv 2204.12013, Section 5):
+ *   FNC/BNC  forward/backward normal computation over the stage's own layers,
+ *   FRC      eager forward redundant computation over a replica of the
+ *            successor's layers (Section 5.1), issued on a second stream so that
+ *            it falls into the pipeline bubble or overlaps the next forward
+ *            (Section 5.2 "Eager FRC", "Scheduling"),
+ *   BRC      lazy backward redundant computation from the stashed FRC
+ *            intermediates once the successor is preempted (Section 5.2 "Lazy
+ *            BRC and Recovery"),
+ *   failover merge of the victim's and the shadow's instruction groups
+ *            (Section 5.2, rules 1-4).
+ *
+ * Conventions
+ *   - Plain C types only.  "device" pointers are HIP device addresses owned by
+ *     the caller; the library never allocates or frees device memory and keeps
+ *     only the pointers.  "host" pointers are ordinary host memory.
+ *   - Streams are hipStream_t values passed as void*; they stay the caller's.
+ *   - Every compute call enqueues work and returns; nothing blocks the host
+ *     except stage_sync.  Calls on one stage must come from one host thread.
+ *   - Return value: 0 (BAMBOO_OK) or a negative bamboo_status; no exception
+ *     crosses this boundary and nothing aborts.
+ *   - Tensors are row-major [tokens, features], tokens = micro_batch * seq,
+ *     token t = sample (t / seq), position (t % seq).
+ */
+#ifndef BAMBOO_STAGE_H
+#define BAMBOO_STAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct bamboo_stage bamboo_stage_t; /* opaque, host side */
+
+enum bamboo_status {
+  BAMBOO_OK = 0,
+  BAMBOO_E_BADCFG = -1, /* configuration rejected (e.g. heads does not divide hidden) */
+  BAMBOO_E_BADMB = -2,  /* micro-batch id out of range, or no stashed forward for it */
+  BAMBOO_E_STATE = -3,  /* call not valid in the stage's current state */
+  BAMBOO_E_HIP = -4,    /* a HIP runtime call failed */
+  BAMBOO_E_ARG = -5,    /* null pointer, too small a buffer, misaligned pointer */
+  BAMBOO_E_NOMEM = -6   /* host allocation failed */
+};
+
+enum bamboo_arch {
+  BAMBOO_ARCH_POST_LN_ENCODER = 0, /* r1 = x + attn(x); y1 = LN1(r1); r2 = y1 + ffn(y1); y = LN2(r2) */
+  BAMBOO_ARCH_PRE_LN_CAUSAL = 1    /* u = LN1(x); x1 = x + attn(u); v = LN2(x1); y = x1 + ffn(v); causal mask */
+};
+
+enum bamboo_dtype {
+  BAMBOO_F32 = 0, /* fp32 weights, activations, arithmetic */
+  BAMBOO_BF16 = 1 /* bf16 weights and activations, fp32 accumulation, fp32 gradients */
+};
+
+/* Configuration of one stage (Section 4: the schedule is a static function of
+ * the stage id, the pipeline depth and the number of micro-batches). */
+typedef struct {
+  int32_t arch;        /* enum bamboo_arch */
+  int32_t dtype;       /* enum bamboo_dtype */
+  int32_t hidden;      /* H, multiple of 8 */
+  int32_t heads;       /* divides H; H/heads in {32, 64, 128} */
+  int32_t ffn;         /* F, multiple of 8 */
+  int32_t seq;         /* S */
+  int32_t micro_batch; /* samples per micro-batch */
+  int32_t n_own;       /* layers of this stage */
+  int32_t n_shadow;    /* replica layers of the successor (0: no redundancy) */
+  int32_t P;           /* pipeline depth */
+  int32_t stage_id;    /* 0-indexed forward stage id (Section 5.1) */
+  int32_t M;           /* micro-batches per iteration, <= 32767 */
+  int32_t frc_enabled; /* emit and allow FRC */
+  int32_t tick_F;      /* slot-timeline duration of a forward (>= 1) */
+  int32_t tick_B;      /* slot-timeline duration of a backward (>= 1) */
+  float ln_eps;        /* LayerNorm epsilon */
+} bamboo_cfg_t;
+
+/* Instruction set: the paper's computation and communication instructions
+ * (Section 4) plus FRC/BRC, the simulated bubble and the join of the two lanes. */
+enum bamboo_op {
+  BAMBOO_RECV_ACT = 0,
+  BAMBOO_SEND_ACT = 1,
+  BAMBOO_RECV_GRAD = 2,
+  BAMBOO_SEND_GRAD = 3,
+  BAMBOO_FWD = 4,
+  BAMBOO_BWD = 5,
+  BAMBOO_FRC = 6,
+  BAMBOO_BRC = 7,
+  BAMBOO_BUBBLE = 8,
+  BAMBOO_JOIN = 9,
+  BAMBOO_ALLREDUCE = 10,
+  BAMBOO_APPLY = 11
+};
+
+/* lane: 0 main stream, 1 FRC stream.  mb: micro-batch or -1.
+ * arg: FWD/BWD own stash slot (mb mod c_own); FRC/BRC shadow stash slot (mb);
+ *      communication: peer stage id; BUBBLE: ticks; JOIN: last FRC waited for
+ *      (-1 all); otherwise 0. */
+typedef struct {
+  uint8_t op;
+  uint8_t lane;
+  int16_t mb;
+  int32_t arg;
+} bamboo_instr_t;
+
+/* Buffer sizes in bytes the caller must provide for a configuration. */
+typedef struct {
+  uint64_t own_w, shadow_w;         /* parameters in the storage dtype */
+  uint64_t own_g, shadow_g;         /* fp32 gradients, same element layout */
+  uint64_t own_stash, shadow_stash; /* c_own (c_shadow) slots x layers x rec_bytes */
+  uint64_t workspace;               /* scratch for both lanes */
+  uint64_t rec_bytes;               /* one stash record: one layer, one micro-batch */
+  uint64_t layer_params;            /* elements per layer: 4H^2 + 2HF + 9H + F */
+  int32_t c_own;                    /* own stash slots = min(P - stage_id, M) */
+  int32_t c_shadow;                 /* shadow stash slots = M (everything BRC may need) */
+} bamboo_sizes_t;
+
+/* ---- host-only entry points (no GPU needed) ------------------------------ */
+
+/* Validate cfg and report buffer sizes.  host pointers. */
+int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out);
+
+/* The stage's instruction list for one failure-free iteration: 1F1B with flush
+ * (Section 2), groups of leading communication + computation (Section 5.2),
+ * BUBBLE(ticks) where the zero-latency slot timeline of all P stages leaves the
+ * stage idle, FRC(k) on lane 1 right after FWD(k) and before the stage talks to
+ * its successor (Section 5.2 "Scheduling").  out: host array of cap entries, may
+ * be NULL with cap 0 to ask for the count.  Returns the count or a negative
+ * status; BAMBOO_E_ARG if cap is too small. */
+int stage_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap);
+
+/* The failover schedule of the shadow stage when sending micro-batch k_fail's
+ * activation to the successor fails (Section 5.2, merge rules 1-4): join the FRC
+ * lane, replay BRC for the micro-batches whose successor-side gradients were
+ * lost, then the rest of the 1F1B program with the victim's groups merged in.
+ * Same out/cap/return convention as stage_program. */
+int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
+
+/* Byte offset of stash record (slot, layer) inside a stash arena:
+ * (slot * n_layers + layer) * rec_bytes.  kind 0 own, 1 shadow.  Negative status
+ * on a bad index. */
+int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot, int32_t layer);
+
+const char* stage_strerror(int status);
+
+/* ---- stage object --------------------------------------------------------- */
+
+/* Create a stage.  All device buffers must be at least as large as
+ * stage_query_sizes reports and 256-byte aligned.
+ *   own_w, shadow_w   device, read-only: layers concatenated in forward order,
+ *                     each layer = Wqkv[H,3H] bqkv[3H] Wo[H,H] bo[H] g1[H] be1[H]
+ *                     W1[H,F] b1[F] W2[F,H] b2[H] g2[H] be2[H]; matrices are
+ *                     [in,out] row-major (Y = X W); Wqkv columns [0,H) queries,
+ *                     [H,2H) keys, [2H,3H) values, head h = columns h*d..(h+1)*d-1
+ *                     of each third.  shadow_w holds the successor's values
+ *                     (Section 5.1: same parameters); NULL iff n_shadow == 0.
+ *   own_g, shadow_g   device fp32, same element layout; the library only adds
+ *                     to them, the caller zeroes them at the start of an iteration.
+ *   stashes, workspace device scratch owned by the caller for the stage's life.
+ *   stream_main/frc   hipStream_t of lane 0 and lane 1 (default priority).
+ * The replica is assumed equal to the successor's parameters at iteration start. */
+int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void* own_w, const void* shadow_w,
+               void* own_g, void* shadow_g, void* own_stash, void* shadow_stash, void* workspace,
+               void* stream_main, void* stream_frc, bamboo_stage_t** out);
+
+/* Copy the current instruction list (stage_program, or the failover schedule
+ * once failover_merge has been called).  Same convention as stage_program. */
+int stage_schedule(const bamboo_stage_t* st, bamboo_instr_t* out, int32_t cap);
+
+/* Forget all stash contents and events: start of a new iteration.  Does not
+ * touch gradients.  After failover_merge the stage stays merged. */
+int stage_begin_iteration(bamboo_stage_t* st);
+
+/* FNC_s(k): y = own layers(x) on lane 0; intermediates go to own slot k mod c_own.
+ * x, y device [tokens, H] in the storage dtype.  BAMBOO_E_BADMB if k is outside
+ * [0, M) or its slot still holds a forward that has not been back-propagated. */
+int stage_fwd(bamboo_stage_t* st, int32_t k, const void* x, void* y);
+
+/* FRC(k): z = shadow layers(y) on lane 1 (lane 0 after failover_merge), ordered
+ * after stage_fwd(k) by an event; intermediates go to shadow slot k and stay
+ * until BRC(k) or the next iteration.  z (device, [tokens,H]) may be NULL.  y
+ * must stay untouched until FRC(k) has run.  BAMBOO_E_STATE if n_shadow == 0 or
+ * FRC is disabled; BAMBOO_E_BADMB if stage_fwd(k) was not issued or FRC(k)
+ * already was. */
+int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z);
+
+/* BNC_s(k): gx = own backward(gy) on lane 0 from own slot k mod c_own; own_g +=.
+ * Frees the slot. */
+int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx);
+
+/* BRC(k): gy = shadow backward(gz) on lane 0 from shadow slot k; shadow_g +=.
+ * gy may be NULL (replayed micro-batch whose own backward already ran).  Only
+ * valid after failover_merge.  Frees the slot. */
+int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy);
+
+/* The successor was found dead while handing over micro-batch k_fail: lane 0
+ * waits for the FRC lane, the stage switches to merged mode (FRC on lane 0, BRC
+ * allowed) and the failover schedule is written to out.  BAMBOO_E_STATE when
+ * called twice or with n_shadow == 0.  Returns the instruction count. */
+int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
+
+/* Simulated pipeline bubble: one single-wave workgroup on lane 0 that spins on
+ * the device wall clock for ticks * us_per_tick microseconds. */
+int stage_bubble(bamboo_stage_t* st, int32_t ticks, float us_per_tick);
+
+/* JOIN on the device: lane 0 waits for everything issued on lane 1. */
+int stage_join(bamboo_stage_t* st);
+
+/* JOIN and block the host until both lanes are idle. */
+int stage_sync(bamboo_stage_t* st);
+
+int stage_destroy(bamboo_stage_t* st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BAMBOO_STAGE_H */

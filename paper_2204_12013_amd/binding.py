@@ -1,0 +1,305 @@
+"""Thin ctypes binding over libbamboo_stage.so (argument marshalling only).
+
+Every step of the hot path runs inside the library's HIP kernels.  PyTorch is
+used for device memory and streams.  There is no fallback: if the native
+library has not been built, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbamboo_stage.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError("native library missing: %s (build it with `python %s`)"
+                      % (LIB_PATH, os.path.join(_HERE, "build.py")))
+lib = C.CDLL(LIB_PATH)
+
+OK, E_BADCFG, E_BADMB, E_STATE, E_HIP, E_ARG, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
+(RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, FWD, BWD, FRC, BRC, BUBBLE, JOIN, ALLREDUCE, APPLY) = range(12)
+
+
+class Cfg(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("arch", "dtype", "hidden", "heads", "ffn", "seq", "micro_batch", "n_own", "n_shadow",
+                 "P", "stage_id", "M", "frc_enabled", "tick_F", "tick_B")] + [("ln_eps", C.c_float)]
+
+
+class Instr(C.Structure):
+    _fields_ = [("op", C.c_uint8), ("lane", C.c_uint8), ("mb", C.c_int16), ("arg", C.c_int32)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in
+                ("own_w", "shadow_w", "own_g", "shadow_g", "own_stash", "shadow_stash", "workspace",
+                 "rec_bytes", "layer_params")] + [("c_own", C.c_int32), ("c_shadow", C.c_int32)]
+
+
+class BambooError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, lib.stage_strerror(status).decode(), status))
+
+
+_vp, _i32, _i64, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+_cfgp, _insp, _szp = C.POINTER(Cfg), C.POINTER(Instr), C.POINTER(Sizes)
+_SIGS = {
+    "stage_query_sizes": (C.c_int, [_cfgp, _szp]),
+    "stage_program": (C.c_int, [_cfgp, _insp, _i32]),
+    "stage_failover_program": (C.c_int, [_cfgp, _i32, _insp, _i32]),
+    "stage_record_offset": (_i64, [_cfgp, _i32, _i32, _i32]),
+    "stage_strerror": (C.c_char_p, [C.c_int]),
+    "stage_init": (C.c_int, [_cfgp, _szp] + [_vp] * 9 + [C.POINTER(_vp)]),
+    "stage_schedule": (C.c_int, [_vp, _insp, _i32]),
+    "stage_begin_iteration": (C.c_int, [_vp]),
+    "stage_fwd": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "shadow_fwd_frc": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "stage_bwd": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "shadow_bwd_brc": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "failover_merge": (C.c_int, [_vp, _i32, _insp, _i32]),
+    "stage_bubble": (C.c_int, [_vp, _i32, _f32]),
+    "stage_join": (C.c_int, [_vp]),
+    "stage_sync": (C.c_int, [_vp]),
+    "stage_destroy": (C.c_int, [_vp]),
+    "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
+    "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
+    "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 4),
+    "bk_colsum_acc": (C.c_int, [C.c_int] * 3 + [_vp] * 4),
+    "bk_colsum_scratch_floats": (C.c_uint64, [C.c_int]),
+    "bk_attention_fwd": (C.c_int, [C.c_int] * 7 + [_vp] * 4),
+    "bk_attention_bwd": (C.c_int, [C.c_int] * 7 + [_vp] * 7),
+    "bk_layernorm_fwd": (C.c_int, [C.c_int] * 3 + [_f32] + [_vp] * 6),
+    "bk_layernorm_bwd": (C.c_int, [C.c_int] * 3 + [_vp] * 10),
+    "bk_layernorm_bwd_scratch_floats": (C.c_uint64, [C.c_int]),
+}
+EXPORTS = tuple(_SIGS)
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+def _check(status, where):
+    if status < 0:
+        raise BambooError(status, where)
+    return status
+
+
+def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, **override):
+    """Cfg from a synth.StageConfig (or anything with the same attributes)."""
+    vals = dict(arch=sc.arch, dtype=sc.dtype, hidden=sc.hidden, heads=sc.heads, ffn=sc.ffn, seq=sc.seq,
+                micro_batch=sc.micro_batch, n_own=sc.n_own, n_shadow=sc.n_shadow, P=sc.P,
+                stage_id=sc.stage_id, M=sc.M, frc_enabled=int(frc_enabled), tick_F=tick_F, tick_B=tick_B,
+                ln_eps=ln_eps)
+    vals.update(override)
+    return Cfg(**vals)
+
+
+def _instr_list(arr, n):
+    return [(int(i.op), int(i.lane), int(i.mb), int(i.arg)) for i in arr[:n]]
+
+
+def stage_query_sizes(cfg):
+    sz = Sizes()
+    _check(lib.stage_query_sizes(C.byref(cfg), C.byref(sz)), "stage_query_sizes")
+    return sz
+
+
+def stage_program(cfg):
+    n = _check(lib.stage_program(C.byref(cfg), None, 0), "stage_program")
+    arr = (Instr * n)()
+    _check(lib.stage_program(C.byref(cfg), arr, n), "stage_program")
+    return _instr_list(arr, n)
+
+
+def stage_failover_program(cfg, k_fail):
+    n = _check(lib.stage_failover_program(C.byref(cfg), k_fail, None, 0), "stage_failover_program")
+    arr = (Instr * n)()
+    _check(lib.stage_failover_program(C.byref(cfg), k_fail, arr, n), "stage_failover_program")
+    return _instr_list(arr, n)
+
+
+def stage_record_offset(cfg, kind, slot, layer):
+    return _check(lib.stage_record_offset(C.byref(cfg), kind, slot, layer), "stage_record_offset")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+class Stage:
+    """Owns the device buffers (as torch tensors) and the two streams of one
+    stage and forwards every call to the C ABI."""
+
+    def __init__(self, cfg, own_w, shadow_w, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self.sizes = sz = stage_query_sizes(cfg)
+        self.act_dtype = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+        self.T, self.H = cfg.micro_batch * cfg.seq, cfg.hidden
+
+        def buf(nbytes):
+            return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=self.device)
+        assert own_w.dtype == self.act_dtype and own_w.numel() == sz.layer_params * cfg.n_own
+        self.own_w = own_w.to(self.device).contiguous()
+        self.shadow_w = None
+        if cfg.n_shadow > 0:
+            assert shadow_w.dtype == self.act_dtype and shadow_w.numel() == sz.layer_params * cfg.n_shadow
+            self.shadow_w = shadow_w.to(self.device).contiguous()
+        self.own_g = torch.zeros(int(sz.layer_params) * cfg.n_own, dtype=torch.float32, device=self.device)
+        self.shadow_g = torch.zeros(max(int(sz.layer_params) * cfg.n_shadow, 1), dtype=torch.float32,
+                                    device=self.device)
+        self.own_stash = buf(sz.own_stash)
+        self.shadow_stash = buf(sz.shadow_stash)
+        self.workspace = buf(sz.workspace)
+        self.stream_main = torch.cuda.Stream(device=self.device)
+        self.stream_frc = torch.cuda.Stream(device=self.device)
+        self._h = C.c_void_p()
+        torch.cuda.synchronize(self.device)
+        _check(lib.stage_init(C.byref(cfg), C.byref(sz), _ptr(self.own_w), _ptr(self.shadow_w), _ptr(self.own_g),
+                              _ptr(self.shadow_g) if cfg.n_shadow > 0 else None, _ptr(self.own_stash),
+                              _ptr(self.shadow_stash) if cfg.n_shadow > 0 else None, _ptr(self.workspace),
+                              C.c_void_p(self.stream_main.cuda_stream), C.c_void_p(self.stream_frc.cuda_stream),
+                              C.byref(self._h)), "stage_init")
+
+    def new_act(self):
+        return self.torch.empty(self.T, self.H, dtype=self.act_dtype, device=self.device)
+
+    def zero_grads(self):
+        with self.torch.cuda.stream(self.stream_main):
+            self.own_g.zero_()
+            self.shadow_g.zero_()
+
+    def stage_schedule(self):
+        n = _check(lib.stage_schedule(self._h, None, 0), "stage_schedule")
+        arr = (Instr * n)()
+        _check(lib.stage_schedule(self._h, arr, n), "stage_schedule")
+        return _instr_list(arr, n)
+
+    def stage_begin_iteration(self):
+        _check(lib.stage_begin_iteration(self._h), "stage_begin_iteration")
+
+    def stage_fwd(self, k, x, y):
+        _check(lib.stage_fwd(self._h, k, _ptr(x), _ptr(y)), "stage_fwd")
+
+    def shadow_fwd_frc(self, k, y, z=None):
+        _check(lib.shadow_fwd_frc(self._h, k, _ptr(y), _ptr(z)), "shadow_fwd_frc")
+
+    def stage_bwd(self, k, gy, gx):
+        _check(lib.stage_bwd(self._h, k, _ptr(gy), _ptr(gx)), "stage_bwd")
+
+    def shadow_bwd_brc(self, k, gz, gy=None):
+        _check(lib.shadow_bwd_brc(self._h, k, _ptr(gz), _ptr(gy)), "shadow_bwd_brc")
+
+    def failover_merge(self, k_fail):
+        cap = 8 * self.cfg.M + 16
+        arr = (Instr * cap)()
+        n = _check(lib.failover_merge(self._h, k_fail, arr, cap), "failover_merge")
+        return _instr_list(arr, n)
+
+    def stage_bubble(self, ticks, us_per_tick):
+        _check(lib.stage_bubble(self._h, ticks, us_per_tick), "stage_bubble")
+
+    def stage_join(self):
+        _check(lib.stage_join(self._h), "stage_join")
+
+    def stage_sync(self):
+        _check(lib.stage_sync(self._h), "stage_sync")
+
+    def stage_destroy(self):
+        if self._h:
+            lib.stage_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.stage_destroy()
+        except Exception:
+            pass
+
+
+# ---- individual kernels (tensors are torch device tensors) -------------------
+
+def _stream(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dt(t):
+    import torch
+    return 1 if t.dtype == torch.bfloat16 else 0
+
+
+def bk_linear_fwd(X, W, bias, Y, res=None, gelu_out=None, impl=0, stream=None):
+    T, K = X.shape
+    N = W.shape[1]
+    _check(lib.bk_linear_fwd(_dt(X), impl, T, N, K, _ptr(X), _ptr(W), _ptr(bias), _ptr(res), _ptr(Y),
+                             _ptr(gelu_out), _stream(stream)), "bk_linear_fwd")
+
+
+def bk_linear_bwd_input(dY, W, dX, res=None, h_in=None, gelu_out=None, impl=0, stream=None):
+    T, N = dY.shape
+    K = W.shape[0]
+    _check(lib.bk_linear_bwd_input(_dt(dY), impl, T, K, N, _ptr(dY), _ptr(W), _ptr(res), _ptr(h_in), _ptr(dX),
+                                   _ptr(gelu_out), _stream(stream)), "bk_linear_bwd_input")
+
+
+def bk_linear_bwd_weight(X, dY, dW, impl=0, stream=None):
+    T, K = X.shape
+    N = dY.shape[1]
+    _check(lib.bk_linear_bwd_weight(_dt(X), impl, T, K, N, _ptr(X), _ptr(dY), _ptr(dW), _stream(stream)),
+           "bk_linear_bwd_weight")
+
+
+def bk_colsum_acc(A, out, stream=None):
+    import torch
+    T, N = A.shape
+    partial = torch.empty(int(lib.bk_colsum_scratch_floats(N)), dtype=torch.float32, device=A.device)
+    _check(lib.bk_colsum_acc(_dt(A), T, N, _ptr(A), _ptr(out), _ptr(partial), _stream(stream)), "bk_colsum_acc")
+    return partial
+
+
+def bk_attention_fwd(qkv, ctx, lse, batch, seq, heads, causal, impl=0, stream=None):
+    d = qkv.shape[1] // 3 // heads
+    _check(lib.bk_attention_fwd(_dt(qkv), impl, batch, seq, heads, d, int(causal), _ptr(qkv), _ptr(ctx), _ptr(lse),
+                                _stream(stream)), "bk_attention_fwd")
+
+
+def bk_attention_bwd(qkv, ctx, lse, dctx, dqkv, batch, seq, heads, causal, impl=0, stream=None):
+    import torch
+    d = qkv.shape[1] // 3 // heads
+    delta = torch.empty(batch * heads * seq, dtype=torch.float32, device=qkv.device)
+    _check(lib.bk_attention_bwd(_dt(qkv), impl, batch, seq, heads, d, int(causal), _ptr(qkv), _ptr(ctx), _ptr(lse),
+                                _ptr(dctx), _ptr(dqkv), _ptr(delta), _stream(stream)), "bk_attention_bwd")
+    return delta
+
+
+def bk_layernorm_fwd(r, gamma, beta, y, stats, eps=1e-5, stream=None):
+    T, H = r.shape
+    _check(lib.bk_layernorm_fwd(_dt(r), T, H, eps, _ptr(r), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(stats),
+                                _stream(stream)), "bk_layernorm_fwd")
+
+
+def bk_layernorm_bwd(dout, r, stats, gamma, dr, dgamma, dbeta, add=None, stream=None):
+    import torch
+    T, H = r.shape
+    partial = torch.empty(int(lib.bk_layernorm_bwd_scratch_floats(H)), dtype=torch.float32, device=r.device)
+    _check(lib.bk_layernorm_bwd(_dt(r), T, H, _ptr(dout), _ptr(r), _ptr(stats), _ptr(gamma), _ptr(add), _ptr(dr),
+                                _ptr(dgamma), _ptr(dbeta), _ptr(partial), _stream(stream)), "bk_layernorm_bwd")
+    return partial
+
+
+# ---- numpy <-> device helpers (storage conversion only) ------------------------
+
+def to_device(a_f32, dtype, device="cuda:0"):
+    """float32 numpy array (already representable in the storage type) -> tensor."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a_f32, dtype=np.float32))
+    return t.to(torch.bfloat16 if dtype == 1 else torch.float32).to(device)
+
+
+def to_host(t):
+    return t.detach().to("cpu").float().numpy().astype(np.float64)

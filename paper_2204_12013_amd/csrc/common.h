@@ -1,0 +1,108 @@
+// Shared device helpers and the internal launcher interface of the Bamboo
+// stage library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16_t;
+
+namespace bamboo {
+
+// ---- storage <-> fp32 ------------------------------------------------------
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+// value after a round trip through the storage type
+template <typename T> __device__ __forceinline__ float round_storage(float v) { return to_f32<T>(from_f32<T>(v)); }
+
+// erf-form GELU and its derivative (fp32)
+__device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float h) {
+  return 0.5f * (1.0f + erff(h * 0.70710678118654752f)) + h * __expf(-0.5f * h * h) * 0.39894228040143268f;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- GEMM ------------------------------------------------------------------
+// C[M,N] = op(A)[M,K] * op(B)[K,N] with an epilogue; fp32 accumulation.
+// A(m,k) sits at A[m*a_sm + k*a_sk], B(k,n) at B[k*b_sk + n*b_sn]; exactly one
+// stride of each operand is 1.  C, res, aux are row-major with leading
+// dimension N.
+enum Epilogue : int {
+  EPI_STORE = 0,      // C = acc
+  EPI_BIAS = 1,       // C = acc + bias[n]
+  EPI_BIAS_RES = 2,   // C = acc + bias[n] + res[m,n]
+  EPI_BIAS_GELU = 3,  // C = h = acc + bias[n] (stored), aux_out = gelu(stored h)
+  EPI_RES = 4,        // C = acc + res[m,n]
+  EPI_DGELU = 5,      // C = acc * gelu'(aux_in[m,n]); aux_out = gelu(aux_in[m,n])
+  EPI_ACC_F32 = 6     // C (fp32) += acc
+};
+
+struct GemmDesc {
+  const void* A;
+  const void* B;
+  void* C;
+  int M, N, K;
+  long a_sm, a_sk, b_sk, b_sn;
+  int epi;
+  const void* bias;     // [N] storage dtype
+  const void* res;      // [M,N]
+  const void* aux_in;   // [M,N]
+  void* aux_out;        // [M,N]
+};
+
+// dtype: 0 fp32, 1 bf16 (enum bamboo_dtype).  All launchers return hipError_t
+// from the launch and never synchronise.
+hipError_t launch_gemm_simple(hipStream_t s, int dtype, const GemmDesc& d);
+// bf16 MFMA path; returns hipErrorNotSupported when the shape is not covered.
+hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d);
+hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
+
+// ---- attention ---------------------------------------------------------------
+// qkv [T,3H] (queries | keys | values), ctx [T,H], lse fp32 [B,heads,S]
+struct AttnDesc {
+  int B, S, heads, d;   // H = heads*d
+  int causal;
+  const void* qkv;
+  void* ctx;            // fwd out / bwd in
+  float* lse;           // fwd out / bwd in: log-sum-exp of the scaled scores per row
+  const void* dctx;     // bwd in
+  void* dqkv;           // bwd out [T,3H]
+  float* delta;         // bwd scratch [B,heads,S]
+};
+hipError_t launch_attention_fwd_simple(hipStream_t s, int dtype, const AttnDesc& d);
+hipError_t launch_attention_bwd_simple(hipStream_t s, int dtype, const AttnDesc& d);
+hipError_t launch_attention_fwd_mfma(hipStream_t s, const AttnDesc& d);
+hipError_t launch_attention_bwd_mfma(hipStream_t s, const AttnDesc& d);
+hipError_t launch_attention_fwd(hipStream_t s, int dtype, const AttnDesc& d);
+hipError_t launch_attention_bwd(hipStream_t s, int dtype, const AttnDesc& d);
+
+// ---- LayerNorm / reductions / misc ------------------------------------------------
+// y = gamma * (r - mean) * rstd + beta; stats[2*t] = mean, stats[2*t+1] = rstd
+hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, int T, int H, float eps, const void* r, const void* gamma,
+                                const void* beta, void* y, float* stats);
+// dr = LN backward(dout) (+ add if add != nullptr); dgamma/dbeta (fp32) += column sums
+// partial: fp32 scratch of ln_bwd_partial_floats(H) floats
+hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const void* dout, const void* r,
+                                const float* stats, const void* gamma, const void* add, void* dr, float* dgamma,
+                                float* dbeta, float* partial);
+// out[n] (fp32) += sum_t a[t,n]; partial: fp32 scratch of colsum_partial_floats(N)
+hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial);
+size_t colsum_partial_floats(int N);
+size_t ln_bwd_partial_floats(int H);
+hipError_t launch_bubble(hipStream_t s, float microseconds);
+
+}  // namespace bamboo

@@ -1,0 +1,119 @@
+// C ABI of the individual kernels: argument checks and marshalling only.
+#include <string.h>
+
+#include "../../include/bamboo_kernels.h"
+#include "../../include/bamboo_stage.h"
+#include "common.h"
+
+using namespace bamboo;
+
+namespace {
+int finish(hipError_t e) {
+  if (e == hipSuccess) return BAMBOO_OK;
+  (void)hipGetLastError();
+  return e == hipErrorNotSupported ? BAMBOO_E_STATE : BAMBOO_E_HIP;
+}
+int run_gemm(int dtype, int impl, const GemmDesc& d, void* stream) {
+  if (dtype != 0 && dtype != 1) return BAMBOO_E_ARG;
+  if (d.M <= 0 || d.N <= 0 || d.K <= 0 || !d.A || !d.B || !d.C) return BAMBOO_E_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  if (impl == 1) return finish(launch_gemm_simple(s, dtype, d));
+  if (impl == 2) return dtype == 1 ? finish(launch_gemm_mfma(s, d)) : BAMBOO_E_STATE;
+  if (impl != 0) return BAMBOO_E_ARG;
+  return finish(launch_gemm(s, dtype, d));
+}
+}  // namespace
+
+extern "C" {
+
+int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const void* W, const void* bias,
+                  const void* res, void* Y, void* gelu_out, void* stream) {
+  if (!bias || (res && gelu_out)) return BAMBOO_E_ARG;
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = X; d.B = W; d.C = Y; d.M = T; d.N = N; d.K = K;
+  d.a_sm = K; d.a_sk = 1; d.b_sk = N; d.b_sn = 1;
+  d.bias = bias; d.res = res; d.aux_out = gelu_out;
+  d.epi = gelu_out ? EPI_BIAS_GELU : (res ? EPI_BIAS_RES : EPI_BIAS);
+  return run_gemm(dtype, impl, d, stream);
+}
+
+int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY, const void* W, const void* res,
+                        const void* h_in, void* dX, void* gelu_out, void* stream) {
+  if ((h_in != nullptr) != (gelu_out != nullptr) || (h_in && res)) return BAMBOO_E_ARG;
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = dY; d.B = W; d.C = dX; d.M = T; d.N = K; d.K = N;
+  d.a_sm = N; d.a_sk = 1; d.b_sk = 1; d.b_sn = N;
+  d.res = res; d.aux_in = h_in; d.aux_out = gelu_out;
+  d.epi = h_in ? EPI_DGELU : (res ? EPI_RES : EPI_STORE);
+  return run_gemm(dtype, impl, d, stream);
+}
+
+int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X, const void* dY, float* dW,
+                         void* stream) {
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = X; d.B = dY; d.C = dW; d.M = K; d.N = N; d.K = T;
+  d.a_sm = 1; d.a_sk = K; d.b_sk = N; d.b_sn = 1;
+  d.epi = EPI_ACC_F32;
+  return run_gemm(dtype, impl, d, stream);
+}
+
+int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || N <= 0 || N % 2 || !A || !out || !partial) return BAMBOO_E_ARG;
+  return finish(launch_colsum_acc((hipStream_t)stream, dtype, T, N, A, out, partial));
+}
+uint64_t bk_colsum_scratch_floats(int N) { return colsum_partial_floats(N); }
+
+static int attn_desc(AttnDesc& a, int dtype, int batch, int seq, int heads, int d, int causal) {
+  if ((dtype != 0 && dtype != 1) || batch <= 0 || seq <= 0 || heads <= 0 || d <= 0 || d > 128) return BAMBOO_E_ARG;
+  memset(&a, 0, sizeof(a));
+  a.B = batch; a.S = seq; a.heads = heads; a.d = d; a.causal = causal != 0;
+  return BAMBOO_OK;
+}
+
+int bk_attention_fwd(int dtype, int impl, int batch, int seq, int heads, int d, int causal, const void* qkv, void* ctx,
+                     float* lse, void* stream) {
+  AttnDesc a;
+  if (attn_desc(a, dtype, batch, seq, heads, d, causal) != BAMBOO_OK || !qkv || !ctx || !lse) return BAMBOO_E_ARG;
+  a.qkv = qkv; a.ctx = ctx; a.lse = lse;
+  hipStream_t s = (hipStream_t)stream;
+  if (impl == 1) return finish(launch_attention_fwd_simple(s, dtype, a));
+  if (impl == 2) return dtype == 1 ? finish(launch_attention_fwd_mfma(s, a)) : BAMBOO_E_STATE;
+  if (impl != 0) return BAMBOO_E_ARG;
+  return finish(launch_attention_fwd(s, dtype, a));
+}
+
+int bk_attention_bwd(int dtype, int impl, int batch, int seq, int heads, int d, int causal, const void* qkv,
+                     const void* ctx, const float* lse, const void* dctx, void* dqkv, float* delta, void* stream) {
+  AttnDesc a;
+  if (attn_desc(a, dtype, batch, seq, heads, d, causal) != BAMBOO_OK || !qkv || !ctx || !lse || !dctx || !dqkv ||
+      !delta)
+    return BAMBOO_E_ARG;
+  a.qkv = qkv; a.ctx = (void*)ctx; a.lse = (float*)lse; a.dctx = dctx; a.dqkv = dqkv; a.delta = delta;
+  hipStream_t s = (hipStream_t)stream;
+  if (impl == 1) return finish(launch_attention_bwd_simple(s, dtype, a));
+  if (impl == 2) return dtype == 1 ? finish(launch_attention_bwd_mfma(s, a)) : BAMBOO_E_STATE;
+  if (impl != 0) return BAMBOO_E_ARG;
+  return finish(launch_attention_bwd(s, dtype, a));
+}
+
+int bk_layernorm_fwd(int dtype, int T, int H, float eps, const void* r, const void* gamma, const void* beta, void* y,
+                     float* stats, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || H <= 0 || H % 8 || !r || !gamma || !beta || !y || !stats)
+    return BAMBOO_E_ARG;
+  return finish(launch_layernorm_fwd((hipStream_t)stream, dtype, T, H, eps, r, gamma, beta, y, stats));
+}
+
+int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, const float* stats, const void* gamma,
+                     const void* add, void* dr, float* dgamma, float* dbeta, float* partial, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || H <= 0 || H % 8 || !dout || !r || !stats || !gamma || !dr || !dgamma ||
+      !dbeta || !partial)
+    return BAMBOO_E_ARG;
+  return finish(launch_layernorm_bwd((hipStream_t)stream, dtype, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta,
+                                     partial));
+}
+uint64_t bk_layernorm_bwd_scratch_floats(int H) { return ln_bwd_partial_floats(H); }
+
+}  // extern "C"

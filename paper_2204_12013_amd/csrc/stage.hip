@@ -1,0 +1,606 @@
+// Stage object and the C ABI: host orchestration of the Bamboo stage hot path.
+//
+// Lane 0 (main stream) carries FNC/BNC of the stage's own layers and, after a
+// failover, BRC and FRC as well.  Lane 1 (FRC stream) carries the eager forward
+// redundant computation over the successor's replica layers, ordered after the
+// forward of the same micro-batch by an event, so that it falls into whatever
+// the main lane leaves idle (a bubble) or overlaps the next forward (paper
+// Section 5.2).  FRC intermediates stay in an HBM stash (one slot per
+// micro-batch) until BRC consumes them; the paper swaps them to host memory
+// instead, which 288 GB of HBM makes unnecessary.
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "common.h"
+#include "schedule.h"
+
+using namespace bamboo;
+
+namespace {
+
+constexpr uint64_t kAlign = 256;
+inline uint64_t align_up(uint64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Byte offsets of the named tensors inside one layer's parameter vector.
+struct ParamOffsets {
+  uint64_t Wqkv, bqkv, Wo, bo, g1, be1, W1, b1, W2, b2, g2, be2, count;
+};
+ParamOffsets param_offsets(int H, int F) {
+  ParamOffsets p;
+  uint64_t o = 0;
+  p.Wqkv = o; o += (uint64_t)H * 3 * H;
+  p.bqkv = o; o += 3 * (uint64_t)H;
+  p.Wo = o; o += (uint64_t)H * H;
+  p.bo = o; o += H;
+  p.g1 = o; o += H;
+  p.be1 = o; o += H;
+  p.W1 = o; o += (uint64_t)H * F;
+  p.b1 = o; o += F;
+  p.W2 = o; o += (uint64_t)F * H;
+  p.b2 = o; o += H;
+  p.g2 = o; o += H;
+  p.be2 = o; o += H;
+  p.count = o;
+  return p;
+}
+
+// One stash record = everything the backward of one layer needs for one
+// micro-batch.  Probabilities are not kept (recomputed from the log-sum-exp).
+//   x     layer input                      [T,H]
+//   ain   attention input (pre-LN: LN1(x); post-LN: aliases x)
+//   qkv   projected queries|keys|values    [T,3H]
+//   ctx   attention output before Wo       [T,H]
+//   r1    x + attention block              [T,H]   (post-LN: LN1 input, pre-LN: x1)
+//   fin   FFN input (post-LN: y1 = LN1(r1); pre-LN: v = LN2(x1))
+//   h     FFN pre-activation               [T,F]
+//   r2    post-LN only: y1 + ffn, LN2 input [T,H]
+//   lse, ln1, ln2  fp32 side data
+struct RecordLayout {
+  uint64_t x, ain, qkv, ctx, r1, fin, h, r2, lse, ln1, ln2, bytes;
+};
+RecordLayout record_layout(const bamboo_cfg_t& c) {
+  const uint64_t es = c.dtype == BAMBOO_BF16 ? 2 : 4;
+  const uint64_t T = (uint64_t)c.micro_batch * c.seq, H = c.hidden, F = c.ffn;
+  RecordLayout r;
+  uint64_t o = 0;
+  r.x = o; o = align_up(o + T * H * es);
+  if (c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL) { r.ain = o; o = align_up(o + T * H * es); } else { r.ain = r.x; }
+  r.qkv = o; o = align_up(o + T * 3 * H * es);
+  r.ctx = o; o = align_up(o + T * H * es);
+  r.r1 = o; o = align_up(o + T * H * es);
+  r.fin = o; o = align_up(o + T * H * es);
+  r.h = o; o = align_up(o + T * F * es);
+  if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) { r.r2 = o; o = align_up(o + T * H * es); } else { r.r2 = 0; }
+  r.lse = o; o = align_up(o + (uint64_t)c.micro_batch * c.heads * c.seq * 4);
+  r.ln1 = o; o = align_up(o + 2 * T * 4);
+  r.ln2 = o; o = align_up(o + 2 * T * 4);
+  r.bytes = o;
+  return r;
+}
+
+// Scratch of one lane.  Lane 1 only ever runs forwards: it needs g (GELU output)
+// and out (where an output the caller does not want is written).
+struct LaneScratch {
+  uint64_t g, out, dh, d1, d2, dctx, ping, pong, dqkv, delta, partial, bytes;
+};
+LaneScratch lane_scratch(const bamboo_cfg_t& c, bool backward) {
+  const uint64_t es = c.dtype == BAMBOO_BF16 ? 2 : 4;
+  const uint64_t T = (uint64_t)c.micro_batch * c.seq, H = c.hidden, F = c.ffn;
+  LaneScratch w;
+  memset(&w, 0, sizeof(w));
+  uint64_t o = 0;
+  w.g = o; o = align_up(o + T * F * es);
+  w.out = o; o = align_up(o + T * H * es);
+  if (backward) {
+    w.dh = o; o = align_up(o + T * F * es);
+    w.d1 = o; o = align_up(o + T * H * es);
+    w.d2 = o; o = align_up(o + T * H * es);
+    w.dctx = o; o = align_up(o + T * H * es);
+    w.ping = o; o = align_up(o + T * H * es);
+    w.pong = o; o = align_up(o + T * H * es);
+    w.dqkv = o; o = align_up(o + T * 3 * H * es);
+    w.delta = o; o = align_up(o + (uint64_t)c.micro_batch * c.heads * c.seq * 4);
+    const uint64_t widest = 3 * H > F ? 3 * H : F;
+    uint64_t pf = colsum_partial_floats((int)widest);
+    if (ln_bwd_partial_floats((int)H) > pf) pf = ln_bwd_partial_floats((int)H);
+    w.partial = o; o = align_up(o + pf * 4);
+  }
+  w.bytes = o;
+  return w;
+}
+
+int validate(const bamboo_cfg_t* c) {
+  if (!c) return BAMBOO_E_ARG;
+  if (c->arch != BAMBOO_ARCH_POST_LN_ENCODER && c->arch != BAMBOO_ARCH_PRE_LN_CAUSAL) return BAMBOO_E_BADCFG;
+  if (c->dtype != BAMBOO_F32 && c->dtype != BAMBOO_BF16) return BAMBOO_E_BADCFG;
+  if (c->hidden <= 0 || c->hidden % 8 || c->ffn <= 0 || c->ffn % 8) return BAMBOO_E_BADCFG;
+  if (c->heads <= 0 || c->hidden % c->heads || c->hidden / c->heads > 128) return BAMBOO_E_BADCFG;
+  if (c->seq <= 0 || c->micro_batch <= 0 || c->n_own <= 0 || c->n_shadow < 0) return BAMBOO_E_BADCFG;
+  if (c->P <= 0 || c->stage_id < 0 || c->stage_id >= c->P || c->M <= 0 || c->M > 32767) return BAMBOO_E_BADCFG;
+  if (c->tick_F < 1 || c->tick_B < 1 || !(c->ln_eps >= 0.f)) return BAMBOO_E_BADCFG;
+  if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
+  return BAMBOO_OK;
+}
+
+int copy_out(const std::vector<bamboo_instr_t>& v, bamboo_instr_t* out, int32_t cap) {
+  if (out == nullptr && cap == 0) return (int)v.size();
+  if (out == nullptr || cap < (int32_t)v.size()) return BAMBOO_E_ARG;
+  memcpy(out, v.data(), v.size() * sizeof(bamboo_instr_t));
+  return (int)v.size();
+}
+
+}  // namespace
+
+struct bamboo_stage {
+  bamboo_cfg_t cfg;
+  bamboo_sizes_t sizes;
+  ParamOffsets po;
+  RecordLayout rl;
+  LaneScratch ws0, ws1;
+  const char* w[2];   // own, shadow parameters
+  float* g[2];        // own, shadow gradients
+  char* stash[2];
+  char* wsbase;
+  hipStream_t lane[2];
+  std::vector<bamboo_instr_t> program;
+  bool merged;
+  std::vector<int> own_slot_mb;        // micro-batch stashed in each own slot, -1 free
+  std::vector<char> fwd_issued, frc_issued, shadow_live;
+  std::vector<hipEvent_t> ev_fwd, ev_frc;
+  hipEvent_t ev_join;
+  int last_frc_on_lane1;
+};
+
+namespace {
+
+#define HIPCHK(expr)                         \
+  do {                                       \
+    if ((expr) != hipSuccess) {              \
+      (void)hipGetLastError();               \
+      return BAMBOO_E_HIP;                   \
+    }                                        \
+  } while (0)
+
+uint64_t esize(const bamboo_stage* st) { return st->cfg.dtype == BAMBOO_BF16 ? 2 : 4; }
+
+GemmDesc gemm_nn(const void* X, const void* W, void* Y, int T, int N, int K, int epi) {
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = X; d.B = W; d.C = Y; d.M = T; d.N = N; d.K = K;
+  d.a_sm = K; d.a_sk = 1; d.b_sk = N; d.b_sn = 1; d.epi = epi;
+  return d;
+}
+// dX[T,Kw] = dY[T,Nw] * W[Kw,Nw]^T
+GemmDesc gemm_nt(const void* dY, const void* W, void* dX, int T, int Kw, int Nw, int epi) {
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = dY; d.B = W; d.C = dX; d.M = T; d.N = Kw; d.K = Nw;
+  d.a_sm = Nw; d.a_sk = 1; d.b_sk = 1; d.b_sn = Nw; d.epi = epi;
+  return d;
+}
+// dW[Kw,Nw] += X[T,Kw]^T * dY[T,Nw]
+GemmDesc gemm_tn(const void* X, const void* dY, float* dW, int T, int Kw, int Nw) {
+  GemmDesc d;
+  memset(&d, 0, sizeof(d));
+  d.A = X; d.B = dY; d.C = dW; d.M = Kw; d.N = Nw; d.K = T;
+  d.a_sm = 1; d.a_sk = Kw; d.b_sk = Nw; d.b_sn = 1; d.epi = EPI_ACC_F32;
+  return d;
+}
+
+// forward of one layer stack; kind 0 own, 1 shadow
+int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x, void* y) {
+  const bamboo_cfg_t& c = st->cfg;
+  const int n = kind == 0 ? c.n_own : c.n_shadow;
+  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const uint64_t es = esize(st);
+  hipStream_t s = st->lane[lane_id];
+  char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
+  void* gbuf = ws + (lane_id == 0 ? st->ws0.g : st->ws1.g);
+  const RecordLayout& r = st->rl;
+  char* rec0 = st->stash[kind] + (uint64_t)slot * n * r.bytes;
+  HIPCHK(hipMemcpyAsync(rec0 + r.x, x, (uint64_t)T * H * es, hipMemcpyDeviceToDevice, s));
+  for (int l = 0; l < n; ++l) {
+    char* rec = rec0 + (uint64_t)l * r.bytes;
+    const char* W = st->w[kind] + (uint64_t)l * st->po.count * es;
+    auto P = [&](uint64_t off) { return (const void*)(W + off * es); };
+    void* out = (l == n - 1) ? y : (void*)(rec + r.bytes + r.x);
+    AttnDesc a;
+    memset(&a, 0, sizeof(a));
+    a.B = c.micro_batch; a.S = c.seq; a.heads = c.heads; a.d = H / c.heads;
+    a.causal = c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL;
+    a.qkv = rec + r.qkv; a.ctx = rec + r.ctx; a.lse = (float*)(rec + r.lse);
+    GemmDesc d;
+    if (c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL)
+      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.x, P(st->po.g1), P(st->po.be1), rec + r.ain,
+                                  (float*)(rec + r.ln1)));
+    d = gemm_nn(rec + r.ain, P(st->po.Wqkv), rec + r.qkv, T, 3 * H, H, EPI_BIAS);
+    d.bias = P(st->po.bqkv);
+    HIPCHK(launch_gemm(s, dt, d));
+    HIPCHK(launch_attention_fwd(s, dt, a));
+    d = gemm_nn(rec + r.ctx, P(st->po.Wo), rec + r.r1, T, H, H, EPI_BIAS_RES);
+    d.bias = P(st->po.bo);
+    d.res = rec + r.x;
+    HIPCHK(launch_gemm(s, dt, d));
+    if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER)
+      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r1, P(st->po.g1), P(st->po.be1), rec + r.fin,
+                                  (float*)(rec + r.ln1)));
+    else
+      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r1, P(st->po.g2), P(st->po.be2), rec + r.fin,
+                                  (float*)(rec + r.ln2)));
+    d = gemm_nn(rec + r.fin, P(st->po.W1), rec + r.h, T, F, H, EPI_BIAS_GELU);
+    d.bias = P(st->po.b1);
+    d.aux_out = gbuf;
+    HIPCHK(launch_gemm(s, dt, d));
+    if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
+      d = gemm_nn(gbuf, P(st->po.W2), rec + r.r2, T, H, F, EPI_BIAS_RES);
+      d.bias = P(st->po.b2);
+      d.res = rec + r.fin;
+      HIPCHK(launch_gemm(s, dt, d));
+      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r2, P(st->po.g2), P(st->po.be2), out,
+                                  (float*)(rec + r.ln2)));
+    } else {
+      d = gemm_nn(gbuf, P(st->po.W2), out, T, H, F, EPI_BIAS_RES);
+      d.bias = P(st->po.b2);
+      d.res = rec + r.r1;
+      HIPCHK(launch_gemm(s, dt, d));
+    }
+  }
+  return BAMBOO_OK;
+}
+
+// backward of one layer stack on lane 0; gx may be null (input gradient discarded)
+int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx) {
+  const bamboo_cfg_t& c = st->cfg;
+  const int n = kind == 0 ? c.n_own : c.n_shadow;
+  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const uint64_t es = esize(st);
+  hipStream_t s = st->lane[0];
+  char* ws = st->wsbase;
+  const LaneScratch& w = st->ws0;
+  void* gbuf = ws + w.g;
+  void* dh = ws + w.dh;
+  void* d1 = ws + w.d1;
+  void* d2 = ws + w.d2;
+  void* dctx = ws + w.dctx;
+  void* dqkv = ws + w.dqkv;
+  float* partial = (float*)(ws + w.partial);
+  const RecordLayout& r = st->rl;
+  char* rec0 = st->stash[kind] + (uint64_t)slot * n * r.bytes;
+  const void* dy = gy;
+  for (int l = n - 1; l >= 0; --l) {
+    char* rec = rec0 + (uint64_t)l * r.bytes;
+    const char* W = st->w[kind] + (uint64_t)l * st->po.count * es;
+    float* G = st->g[kind] + (uint64_t)l * st->po.count;
+    auto P = [&](uint64_t off) { return (const void*)(W + off * es); };
+    void* dx = (l == 0) ? (gx ? gx : (void*)(ws + w.ping)) : (void*)(ws + (((n - 1 - l) & 1) ? w.pong : w.ping));
+    if (dx == dy) dx = ws + w.pong;  // never alias input and output of a layer
+    AttnDesc a;
+    memset(&a, 0, sizeof(a));
+    a.B = c.micro_batch; a.S = c.seq; a.heads = c.heads; a.d = H / c.heads;
+    a.causal = c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL;
+    a.qkv = rec + r.qkv; a.ctx = rec + r.ctx; a.lse = (float*)(rec + r.lse);
+    a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(ws + w.delta);
+    GemmDesc d;
+    const void* df;     // gradient at the FFN output
+    if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
+      HIPCHK(launch_layernorm_bwd(s, dt, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
+                                  G + st->po.g2, G + st->po.be2, partial));
+      df = d1;
+    } else {
+      df = dy;
+    }
+    // f = g W2 + b2
+    HIPCHK(launch_colsum_acc(s, dt, T, H, df, G + st->po.b2, partial));
+    d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_DGELU);
+    d.aux_in = rec + r.h;
+    d.aux_out = gbuf;
+    HIPCHK(launch_gemm(s, dt, d));
+    HIPCHK(launch_gemm(s, dt, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
+    // h = fin W1 + b1
+    HIPCHK(launch_colsum_acc(s, dt, T, F, dh, G + st->po.b1, partial));
+    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
+    const void* da;     // gradient at the attention block's output
+    if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
+      d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
+      d.res = d1;
+      HIPCHK(launch_gemm(s, dt, d));
+      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
+                                  G + st->po.g1, G + st->po.be1, partial));
+      da = d1;
+    } else {
+      HIPCHK(launch_gemm(s, dt, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
+      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
+                                  G + st->po.g2, G + st->po.be2, partial));   // + residual branch of y = x1 + f
+      da = d2;
+    }
+    // a = ctx Wo + bo
+    HIPCHK(launch_colsum_acc(s, dt, T, H, da, G + st->po.bo, partial));
+    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
+    HIPCHK(launch_gemm(s, dt, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
+    HIPCHK(launch_attention_bwd(s, dt, a));
+    // qkv = ain Wqkv + bqkv
+    HIPCHK(launch_colsum_acc(s, dt, T, 3 * H, dqkv, G + st->po.bqkv, partial));
+    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
+    if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
+      d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
+      d.res = da;
+      HIPCHK(launch_gemm(s, dt, d));
+    } else {
+      HIPCHK(launch_gemm(s, dt, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
+      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
+                                  G + st->po.g1, G + st->po.be1, partial));   // + residual branch of x1 = x + a
+    }
+    dy = dx;
+  }
+  return BAMBOO_OK;
+}
+
+int get_event(std::vector<hipEvent_t>& v, int k, hipEvent_t* out) {
+  if (v[k] == nullptr) HIPCHK(hipEventCreateWithFlags(&v[k], hipEventDisableTiming));
+  *out = v[k];
+  return BAMBOO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* stage_strerror(int status) {
+  switch (status) {
+    case BAMBOO_OK: return "ok";
+    case BAMBOO_E_BADCFG: return "configuration rejected";
+    case BAMBOO_E_BADMB: return "micro-batch id out of range or no stashed forward for it";
+    case BAMBOO_E_STATE: return "call not valid in the stage's current state";
+    case BAMBOO_E_HIP: return "HIP runtime call failed";
+    case BAMBOO_E_ARG: return "bad argument (null pointer, small buffer or misaligned pointer)";
+    case BAMBOO_E_NOMEM: return "host allocation failed";
+    default: return "unknown status";
+  }
+}
+
+int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (!out) return BAMBOO_E_ARG;
+  const uint64_t es = cfg->dtype == BAMBOO_BF16 ? 2 : 4;
+  const ParamOffsets po = param_offsets(cfg->hidden, cfg->ffn);
+  const RecordLayout rl = record_layout(*cfg);
+  memset(out, 0, sizeof(*out));
+  out->layer_params = po.count;
+  out->own_w = po.count * cfg->n_own * es;
+  out->shadow_w = po.count * cfg->n_shadow * es;
+  out->own_g = po.count * cfg->n_own * 4;
+  out->shadow_g = po.count * cfg->n_shadow * 4;
+  out->rec_bytes = rl.bytes;
+  out->c_own = own_slot_count(cfg->P, cfg->stage_id, cfg->M);
+  out->c_shadow = cfg->n_shadow > 0 ? cfg->M : 0;
+  out->own_stash = (uint64_t)out->c_own * cfg->n_own * rl.bytes;
+  out->shadow_stash = (uint64_t)out->c_shadow * cfg->n_shadow * rl.bytes;
+  out->workspace = lane_scratch(*cfg, true).bytes + lane_scratch(*cfg, false).bytes;
+  return BAMBOO_OK;
+}
+
+int stage_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  try {
+    return copy_out(build_program(*cfg), out, cap);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+}
+
+int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (cfg->n_shadow <= 0 || cfg->stage_id >= cfg->P - 1) return BAMBOO_E_STATE;
+  if (k_fail < 0 || k_fail >= cfg->M) return BAMBOO_E_BADMB;
+  try {
+    return copy_out(build_failover_program(*cfg, k_fail), out, cap);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+}
+
+int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot, int32_t layer) {
+  bamboo_sizes_t sz;
+  const int v = stage_query_sizes(cfg, &sz);
+  if (v != BAMBOO_OK) return v;
+  const int n = kind == 0 ? cfg->n_own : cfg->n_shadow;
+  const int slots = kind == 0 ? sz.c_own : sz.c_shadow;
+  if ((kind != 0 && kind != 1) || slot < 0 || slot >= slots || layer < 0 || layer >= n) return BAMBOO_E_ARG;
+  return (int64_t)(((uint64_t)slot * n + layer) * sz.rec_bytes);
+}
+
+int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void* own_w, const void* shadow_w,
+               void* own_g, void* shadow_g, void* own_stash, void* shadow_stash, void* workspace, void* stream_main,
+               void* stream_frc, bamboo_stage_t** out) {
+  bamboo_sizes_t need;
+  const int v = stage_query_sizes(cfg, &need);
+  if (v != BAMBOO_OK) return v;
+  if (!sizes || !out || !own_w || !own_g || !own_stash || !workspace) return BAMBOO_E_ARG;
+  if (cfg->n_shadow > 0 && (!shadow_w || !shadow_g || !shadow_stash)) return BAMBOO_E_ARG;
+  if (sizes->own_w < need.own_w || sizes->shadow_w < need.shadow_w || sizes->own_g < need.own_g ||
+      sizes->shadow_g < need.shadow_g || sizes->own_stash < need.own_stash ||
+      sizes->shadow_stash < need.shadow_stash || sizes->workspace < need.workspace)
+    return BAMBOO_E_ARG;
+  const void* ptrs[] = {own_w, shadow_w, own_g, shadow_g, own_stash, shadow_stash, workspace};
+  for (const void* p : ptrs)
+    if (((uintptr_t)p) % kAlign) return BAMBOO_E_ARG;
+  bamboo_stage* st = new (std::nothrow) bamboo_stage();
+  if (!st) return BAMBOO_E_NOMEM;
+  try {
+    st->cfg = *cfg;
+    st->sizes = need;
+    st->po = param_offsets(cfg->hidden, cfg->ffn);
+    st->rl = record_layout(*cfg);
+    st->ws0 = lane_scratch(*cfg, true);
+    st->ws1 = lane_scratch(*cfg, false);
+    st->w[0] = (const char*)own_w;
+    st->w[1] = (const char*)shadow_w;
+    st->g[0] = (float*)own_g;
+    st->g[1] = (float*)shadow_g;
+    st->stash[0] = (char*)own_stash;
+    st->stash[1] = (char*)shadow_stash;
+    st->wsbase = (char*)workspace;
+    st->lane[0] = (hipStream_t)stream_main;
+    st->lane[1] = (hipStream_t)stream_frc;
+    st->program = build_program(*cfg);
+    st->merged = false;
+    st->own_slot_mb.assign(need.c_own, -1);
+    st->fwd_issued.assign(cfg->M, 0);
+    st->frc_issued.assign(cfg->M, 0);
+    st->shadow_live.assign(cfg->M, 0);
+    st->ev_fwd.assign(cfg->M, nullptr);
+    st->ev_frc.assign(cfg->M, nullptr);
+    st->ev_join = nullptr;
+    st->last_frc_on_lane1 = -1;
+  } catch (const std::bad_alloc&) {
+    delete st;
+    return BAMBOO_E_NOMEM;
+  }
+  if (hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    delete st;
+    return BAMBOO_E_HIP;
+  }
+  *out = st;
+  return BAMBOO_OK;
+}
+
+int stage_schedule(const bamboo_stage_t* st, bamboo_instr_t* out, int32_t cap) {
+  if (!st) return BAMBOO_E_ARG;
+  return copy_out(st->program, out, cap);
+}
+
+int stage_begin_iteration(bamboo_stage_t* st) {
+  if (!st) return BAMBOO_E_ARG;
+  std::fill(st->own_slot_mb.begin(), st->own_slot_mb.end(), -1);
+  std::fill(st->fwd_issued.begin(), st->fwd_issued.end(), 0);
+  std::fill(st->frc_issued.begin(), st->frc_issued.end(), 0);
+  std::fill(st->shadow_live.begin(), st->shadow_live.end(), 0);
+  st->last_frc_on_lane1 = -1;
+  return BAMBOO_OK;
+}
+
+int stage_fwd(bamboo_stage_t* st, int32_t k, const void* x, void* y) {
+  if (!st || !x || !y) return BAMBOO_E_ARG;
+  if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
+  const int slot = k % st->sizes.c_own;
+  if (st->own_slot_mb[slot] != -1 || st->fwd_issued[k]) return BAMBOO_E_BADMB;
+  const int rc = run_forward(st, 0, 0, slot, x, y);
+  if (rc != BAMBOO_OK) return rc;
+  st->own_slot_mb[slot] = k;
+  st->fwd_issued[k] = 1;
+  hipEvent_t ev;
+  if (get_event(st->ev_fwd, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
+  HIPCHK(hipEventRecord(ev, st->lane[0]));
+  return BAMBOO_OK;
+}
+
+int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z) {
+  if (!st || !y) return BAMBOO_E_ARG;
+  if (st->cfg.n_shadow <= 0 || !st->cfg.frc_enabled) return BAMBOO_E_STATE;
+  if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
+  if (!st->fwd_issued[k] || st->frc_issued[k]) return BAMBOO_E_BADMB;
+  const int lane_id = st->merged ? 0 : 1;
+  hipEvent_t ev;
+  if (lane_id == 1) {
+    if (get_event(st->ev_fwd, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
+    HIPCHK(hipStreamWaitEvent(st->lane[1], ev, 0));
+  }
+  char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
+  void* zout = z ? z : (void*)(ws + (lane_id == 0 ? st->ws0.out : st->ws1.out));
+  const int rc = run_forward(st, 1, lane_id, k, y, zout);
+  if (rc != BAMBOO_OK) return rc;
+  st->frc_issued[k] = 1;
+  st->shadow_live[k] = 1;
+  if (lane_id == 1) {
+    if (get_event(st->ev_frc, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
+    HIPCHK(hipEventRecord(ev, st->lane[1]));
+    st->last_frc_on_lane1 = k;
+  }
+  return BAMBOO_OK;
+}
+
+int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx) {
+  if (!st || !gy || !gx) return BAMBOO_E_ARG;
+  if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
+  const int slot = k % st->sizes.c_own;
+  if (st->own_slot_mb[slot] != k) return BAMBOO_E_BADMB;
+  const int rc = run_backward(st, 0, slot, gy, gx);
+  if (rc != BAMBOO_OK) return rc;
+  st->own_slot_mb[slot] = -1;
+  return BAMBOO_OK;
+}
+
+int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy) {
+  if (!st || !gz) return BAMBOO_E_ARG;
+  if (st->cfg.n_shadow <= 0 || !st->merged) return BAMBOO_E_STATE;
+  if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
+  if (!st->shadow_live[k]) return BAMBOO_E_STATE;
+  if (st->ev_frc[k] != nullptr) HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_frc[k], 0));
+  const int rc = run_backward(st, 1, k, gz, gy);
+  if (rc != BAMBOO_OK) return rc;
+  st->shadow_live[k] = 0;
+  return BAMBOO_OK;
+}
+
+int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
+  if (!st) return BAMBOO_E_ARG;
+  if (st->merged || st->cfg.n_shadow <= 0 || st->cfg.stage_id >= st->cfg.P - 1) return BAMBOO_E_STATE;
+  if (k_fail < 0 || k_fail >= st->cfg.M) return BAMBOO_E_BADMB;
+  std::vector<bamboo_instr_t> prog;
+  try {
+    prog = build_failover_program(st->cfg, k_fail);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+  const int n = copy_out(prog, out, cap);
+  if (n < 0) return n;
+  // JOIN: everything issued on the FRC lane must be visible to lane 0
+  HIPCHK(hipEventRecord(st->ev_join, st->lane[1]));
+  HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_join, 0));
+  st->merged = true;
+  st->program.swap(prog);
+  return n;
+}
+
+int stage_bubble(bamboo_stage_t* st, int32_t ticks, float us_per_tick) {
+  if (!st) return BAMBOO_E_ARG;
+  if (ticks < 0 || !(us_per_tick >= 0.f)) return BAMBOO_E_ARG;
+  HIPCHK(launch_bubble(st->lane[0], (float)ticks * us_per_tick));
+  return BAMBOO_OK;
+}
+
+int stage_join(bamboo_stage_t* st) {
+  if (!st) return BAMBOO_E_ARG;
+  HIPCHK(hipEventRecord(st->ev_join, st->lane[1]));
+  HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_join, 0));
+  return BAMBOO_OK;
+}
+
+int stage_sync(bamboo_stage_t* st) {
+  const int rc = stage_join(st);
+  if (rc != BAMBOO_OK) return rc;
+  HIPCHK(hipStreamSynchronize(st->lane[0]));
+  HIPCHK(hipStreamSynchronize(st->lane[1]));
+  return BAMBOO_OK;
+}
+
+int stage_destroy(bamboo_stage_t* st) {
+  if (!st) return BAMBOO_E_ARG;
+  for (hipEvent_t e : st->ev_fwd)
+    if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->ev_frc)
+    if (e) (void)hipEventDestroy(e);
+  if (st->ev_join) (void)hipEventDestroy(st->ev_join);
+  delete st;
+  return BAMBOO_OK;
+}
+
+}  // extern "C"

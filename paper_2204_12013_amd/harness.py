@@ -1,0 +1,92 @@
+"""Instruction-list interpreter around one Stage: stands in for the neighbours.
+
+The stage before (s-1) is a table of inputs x_k, the stage after the successor
+(s+2) a table of upstream gradients g_z_k, both pre-staged in device memory
+(they replace RECV_ACT / RECV_GRAD).  The successor (s+1) is either absent
+(benchmark: g_y_k comes from a table) or simulated by a second Stage object
+running the replica's parameter values as its own layers, with its own stash
+and gradient buffer, until it is "preempted".  No arithmetic happens here: every
+compute instruction is one call into the C ABI.
+"""
+from . import binding as B
+
+
+class StageHarness:
+    def __init__(self, stage, x, gz, successor=None, gy_table=None, us_per_tick=0.0):
+        self.st = stage
+        self.x, self.gz = x, gz
+        self.succ = successor
+        self.gy_table = gy_table
+        self.us_per_tick = us_per_tick
+        M = stage.cfg.M
+        self.y = [stage.new_act() for _ in range(M)]
+        self.gx = [stage.new_act() for _ in range(M)]
+        self.z_frc = [stage.new_act() for _ in range(M)] if stage.cfg.n_shadow > 0 else None
+        self.gy = list(gy_table) if gy_table is not None else [stage.new_act() for _ in range(M)]
+        self.gy_replay = {}
+        self.bwd_done = set()
+        if successor is not None:
+            self.z_succ = [stage.new_act() for _ in range(M)]
+            self.succ_fwd_done = set()
+
+    def begin_iteration(self, zero_grads=True):
+        self.st.stage_begin_iteration()
+        self.bwd_done = set()
+        if zero_grads:
+            self.st.zero_grads()
+        if self.succ is not None:
+            self.succ.stage_begin_iteration()
+            self.succ_fwd_done = set()
+            if zero_grads:
+                self.succ.zero_grads()
+
+    def _successor_backward(self, k):
+        """What the live successor does between SEND_ACT(k) and RECV_GRAD(k)."""
+        torch = self.st.torch
+        succ = self.succ
+        # the successor works on its own stream; order it after our forward
+        succ.stream_main.wait_stream(self.st.stream_main)
+        if k not in self.succ_fwd_done:
+            succ.stage_fwd(k, self.y[k], self.z_succ[k])
+            self.succ_fwd_done.add(k)
+        succ.stage_bwd(k, self.gz[k], self.gy[k])
+        self.st.stream_main.wait_stream(succ.stream_main)
+
+    def run(self, program):
+        st = self.st
+        for op, lane, k, arg in program:
+            if op == B.FWD:
+                st.stage_fwd(k, self.x[k], self.y[k])
+            elif op == B.FRC:
+                st.shadow_fwd_frc(k, self.y[k], self.z_frc[k])
+            elif op == B.RECV_GRAD:
+                if arg == st.cfg.stage_id + 1 and self.succ is not None:
+                    self._successor_backward(k)
+            elif op == B.BWD:
+                st.stage_bwd(k, self.gy[k], self.gx[k])
+                self.bwd_done.add(k)
+            elif op == B.BRC:
+                if k in self.bwd_done:            # replayed: own backward already ran
+                    self.gy_replay[k] = st.new_act()
+                    st.shadow_bwd_brc(k, self.gz[k], self.gy_replay[k])
+                else:
+                    st.shadow_bwd_brc(k, self.gz[k], self.gy[k])
+            elif op == B.BUBBLE:
+                if self.us_per_tick > 0:
+                    st.stage_bubble(arg, self.us_per_tick)
+            elif op == B.JOIN:
+                st.stage_join()
+            # SEND_*, RECV_ACT, ALLREDUCE, APPLY: placeholders on one GPU
+        return self
+
+    def sync(self):
+        self.st.stage_sync()
+        if self.succ is not None:
+            self.succ.stage_sync()
+
+
+def split_at_failure(program, k_fail):
+    """The instructions that ran before the failure was noticed: up to and
+    including FWD(k_fail) and its FRC."""
+    last = max(i for i, ins in enumerate(program) if ins[2] == k_fail and ins[0] in (B.FWD, B.FRC))
+    return program[:last + 1]
