@@ -8,6 +8,10 @@ import ctypes as C
 import os
 
 import numpy as np
+# torch ships its own HIP runtime; it has to be in the process before the
+# library is loaded so that both resolve to the same runtime (two runtimes in
+# one process cannot share streams or memory)
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbamboo_stage.so")

@@ -1,4 +1,6 @@
 // C ABI of the individual kernels: argument checks and marshalling only.
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "../../include/bamboo_kernels.h"
@@ -10,10 +12,12 @@ using namespace bamboo;
 namespace {
 int finish(hipError_t e) {
   if (e == hipSuccess) return BAMBOO_OK;
+  if (getenv("BAMBOO_DEBUG")) fprintf(stderr, "[bamboo] HIP error %d: %s\n", (int)e, hipGetErrorString(e));
   (void)hipGetLastError();
   return e == hipErrorNotSupported ? BAMBOO_E_STATE : BAMBOO_E_HIP;
 }
 int run_gemm(int dtype, int impl, const GemmDesc& d, void* stream) {
+  (void)hipGetLastError();  // an earlier, unrelated failure in this thread must not be blamed on this launch
   if (dtype != 0 && dtype != 1) return BAMBOO_E_ARG;
   if (d.M <= 0 || d.N <= 0 || d.K <= 0 || !d.A || !d.B || !d.C) return BAMBOO_E_ARG;
   hipStream_t s = (hipStream_t)stream;
@@ -62,6 +66,7 @@ int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X
 
 int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream) {
   if ((dtype != 0 && dtype != 1) || T <= 0 || N <= 0 || N % 2 || !A || !out || !partial) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
   return finish(launch_colsum_acc((hipStream_t)stream, dtype, T, N, A, out, partial));
 }
 uint64_t bk_colsum_scratch_floats(int N) { return colsum_partial_floats(N); }
@@ -79,6 +84,7 @@ int bk_attention_fwd(int dtype, int impl, int batch, int seq, int heads, int d, 
   if (attn_desc(a, dtype, batch, seq, heads, d, causal) != BAMBOO_OK || !qkv || !ctx || !lse) return BAMBOO_E_ARG;
   a.qkv = qkv; a.ctx = ctx; a.lse = lse;
   hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();
   if (impl == 1) return finish(launch_attention_fwd_simple(s, dtype, a));
   if (impl == 2) return dtype == 1 ? finish(launch_attention_fwd_mfma(s, a)) : BAMBOO_E_STATE;
   if (impl != 0) return BAMBOO_E_ARG;
@@ -93,6 +99,7 @@ int bk_attention_bwd(int dtype, int impl, int batch, int seq, int heads, int d, 
     return BAMBOO_E_ARG;
   a.qkv = qkv; a.ctx = (void*)ctx; a.lse = (float*)lse; a.dctx = dctx; a.dqkv = dqkv; a.delta = delta;
   hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();
   if (impl == 1) return finish(launch_attention_bwd_simple(s, dtype, a));
   if (impl == 2) return dtype == 1 ? finish(launch_attention_bwd_mfma(s, a)) : BAMBOO_E_STATE;
   if (impl != 0) return BAMBOO_E_ARG;
@@ -103,6 +110,7 @@ int bk_layernorm_fwd(int dtype, int T, int H, float eps, const void* r, const vo
                      float* stats, void* stream) {
   if ((dtype != 0 && dtype != 1) || T <= 0 || H <= 0 || H % 8 || !r || !gamma || !beta || !y || !stats)
     return BAMBOO_E_ARG;
+  (void)hipGetLastError();
   return finish(launch_layernorm_fwd((hipStream_t)stream, dtype, T, H, eps, r, gamma, beta, y, stats));
 }
 
@@ -111,6 +119,7 @@ int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, c
   if ((dtype != 0 && dtype != 1) || T <= 0 || H <= 0 || H % 8 || !dout || !r || !stats || !gamma || !dr || !dgamma ||
       !dbeta || !partial)
     return BAMBOO_E_ARG;
+  (void)hipGetLastError();
   return finish(launch_layernorm_bwd((hipStream_t)stream, dtype, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta,
                                      partial));
 }

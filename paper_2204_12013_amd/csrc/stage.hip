@@ -8,6 +8,7 @@
 // Section 5.2).  FRC intermediates stay in an HBM stash (one slot per
 // micro-batch) until BRC consumes them; the paper swaps them to host memory
 // instead, which 288 GB of HBM makes unnecessary.
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 
@@ -157,12 +158,15 @@ struct bamboo_stage {
 
 namespace {
 
-#define HIPCHK(expr)                         \
-  do {                                       \
-    if ((expr) != hipSuccess) {              \
-      (void)hipGetLastError();               \
-      return BAMBOO_E_HIP;                   \
-    }                                        \
+#define HIPCHK(expr)                                                                          \
+  do {                                                                                        \
+    const hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess) {                                                                   \
+      if (getenv("BAMBOO_DEBUG"))                                                             \
+        fprintf(stderr, "[bamboo] %s:%d HIP error %d: %s\n", __FILE__, __LINE__, (int)e_, hipGetErrorString(e_)); \
+      (void)hipGetLastError();                                                                \
+      return BAMBOO_E_HIP;                                                                    \
+    }                                                                                         \
   } while (0)
 
 uint64_t esize(const bamboo_stage* st) { return st->cfg.dtype == BAMBOO_BF16 ? 2 : 4; }
@@ -198,6 +202,7 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
   const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
   const uint64_t es = esize(st);
   hipStream_t s = st->lane[lane_id];
+  (void)hipGetLastError();  // do not inherit an unrelated earlier error of this thread
   char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
   void* gbuf = ws + (lane_id == 0 ? st->ws0.g : st->ws1.g);
   const RecordLayout& r = st->rl;
@@ -259,6 +264,7 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
   const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
   const uint64_t es = esize(st);
   hipStream_t s = st->lane[0];
+  (void)hipGetLastError();
   char* ws = st->wsbase;
   const LaneScratch& w = st->ws0;
   void* gbuf = ws + w.g;
@@ -573,6 +579,7 @@ int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int3
 int stage_bubble(bamboo_stage_t* st, int32_t ticks, float us_per_tick) {
   if (!st) return BAMBOO_E_ARG;
   if (ticks < 0 || !(us_per_tick >= 0.f)) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
   HIPCHK(launch_bubble(st->lane[0], (float)ticks * us_per_tick));
   return BAMBOO_OK;
 }
