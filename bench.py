@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the Bamboo stage hot path on one MI355X.
+
+A step is one training iteration of the stage: the stage's instruction list for
+all M micro-batches (forward + backward over the own layers, eager FRC over the
+replica layers on the second lane).  Inputs are synthetic, seeded, and resident
+in HBM before the timed region.  Prints one JSON line.
+
+Modes (all reported; `value` is mode B):
+  A  FRC off, no bubbles      pure stage compute
+  B  FRC on,  no bubbles      FRC fully exposed (worst case)
+  C  FRC off / on with the simulated 1F1B bubbles of the slot timeline
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"mfma_bf16": 2.5e15, "hbm": 8.0e12, "fp32_vector": 157.3e12}
+
+
+def _iteration_flops(sc, frc):
+    T, H, S, F = sc.tokens, sc.hidden, sc.seq, sc.ffn
+    gemm_fwd = 2.0 * T * (3 * H * H + H * H + 2 * H * F)
+    attn_fwd = 4.0 * T * S * H * (0.5 if sc.arch == 1 else 1.0)
+    fwd = gemm_fwd + attn_fwd
+    bwd = 2.0 * gemm_fwd + 2.5 * attn_fwd
+    return sc.M * (sc.n_own * (fwd + bwd) + (sc.n_shadow * fwd if frc else 0.0))
+
+
+def _cpu_baseline(sc, seconds_hint=20.0):
+    """The oracle as it stands, timed on the host: one layer forward + backward
+    for one micro-batch of this workload, extrapolated linearly to an iteration
+    (flops are linear in layers x micro-batches)."""
+    import numpy as np
+    from oracle import layer as L
+    from paper_2204_12013_amd import synth
+    one = sc.replace(n_own=1, n_shadow=0)
+    inp = synth.make_stage_inputs(one, n_microbatches=1)
+    p = L.unpack_layer(inp["own_w"][0].astype(np.float64), sc.hidden, sc.ffn)
+    x = inp["x"][0].astype(np.float64)
+    g = inp["gz"][0].astype(np.float64)
+    t0 = time.perf_counter()
+    y, cache = L.layer_fwd(sc.arch, p, x, sc.micro_batch, sc.seq, sc.heads)
+    t1 = time.perf_counter()
+    L.layer_bwd(sc.arch, p, cache, g)
+    t2 = time.perf_counter()
+    t_f, t_b = t1 - t0, t2 - t1
+    t_iter = sc.M * (sc.n_own * (t_f + t_b) + sc.n_shadow * t_f)
+    try:
+        import threadpoolctl
+        cores = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": sc.M * sc.micro_batch / t_iter, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "fp64 oracle, 1 layer forward (%.2f s) + backward (%.2f s) on 1 micro-batch of %s, "
+                      "extrapolated to the FRC-on iteration (%d micro-batches x (%d own fwd+bwd + %d replica fwd))"
+                      % (t_f, t_b, sc.name, sc.M, sc.n_own, sc.n_shadow)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert_large_stage")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-modes", action="store_true", help="time mode B only (for profiler runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one stage on ONE GPU; --gpus %d is not supported (no collectives, no second "
+              "GPU in this build)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2204_12013_amd import binding as B, synth
+    from paper_2204_12013_amd.harness import StageHarness
+    if not torch.cuda.is_available():
+        print("no GPU visible: the HIP path cannot run (there is no CPU fallback)", file=sys.stderr)
+        return 3
+    sc = synth.CONFIGS[args.workload]
+    dev = torch.device("cuda:0")
+    act = torch.bfloat16 if sc.dtype == 1 else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(sc.seed)
+
+    def layer_stack(n):
+        """n layers drawn on the device with the workload's distributions."""
+        H, F = sc.hidden, sc.ffn
+        out = []
+        for _ in range(n):
+            for name in synth.PARAM_NAMES:
+                shp = synth.param_shapes(H, F)[name]
+                numel = 1
+                for s_ in shp:
+                    numel *= s_
+                v = torch.randn(numel, generator=gen, device=dev, dtype=torch.float32) * 0.02
+                if name in ("g1", "g2"):
+                    v += 1.0
+                out.append(v.to(act))
+        return torch.cat(out)
+
+    cfg = B.make_cfg(sc, frc_enabled=True)
+    st = B.Stage(cfg, layer_stack(sc.n_own), layer_stack(sc.n_shadow))
+    T, H, M = sc.tokens, sc.hidden, sc.M
+    x = [torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32).to(act) for _ in range(M)]
+    gy = [(torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32) / (T * H) ** 0.5).to(act)
+          for _ in range(M)]
+    torch.cuda.synchronize()
+    hz = StageHarness(st, x, gz=gy, gy_table=gy)
+    prog_on = st.stage_schedule()
+    prog_off = [i for i in prog_on if i[0] != B.FRC]
+
+    def run_iters(prog, n, us_per_tick=0.0):
+        hz.us_per_tick = us_per_tick
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            hz.begin_iteration(zero_grads=True)
+            hz.run(prog)
+        hz.sync()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / max(n, 1)
+
+    run_iters(prog_on, args.warmup)
+    ms_on = run_iters(prog_on, args.steps)                       # mode B: the headline
+    out = {"metric": "stage samples/s (FRC on/off), FRC overhead %, MFMA util vs bf16 peak",
+           "value": M * sc.micro_batch / (ms_on * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_on, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16" if sc.dtype == 1 else "f32", "data": "synthetic",
+           "config": {"workload": sc.name, "arch": "post-LN encoder" if sc.arch == 0 else "pre-LN causal decoder",
+                      "hidden": sc.hidden, "heads": sc.heads, "ffn": sc.ffn, "seq": sc.seq,
+                      "micro_batch": sc.micro_batch, "micro_batches": M, "own_layers": sc.n_own,
+                      "replica_layers": sc.n_shadow, "pipeline_depth": sc.P, "stage_id": sc.stage_id,
+                      "mode": "B: FRC on, no simulated bubbles"}}
+    flops_on = _iteration_flops(sc, True)
+    out["mfma_util_end_to_end"] = flops_on / (ms_on * 1e-3) / PEAK["mfma_bf16"]
+
+    if not args.no_extra_modes:
+        run_iters(prog_off, 1)
+        ms_off = run_iters(prog_off, args.steps)                 # mode A
+        out["samples_per_s_frc_off"] = M * sc.micro_batch / (ms_off * 1e-3)
+        out["ms_per_step_frc_off"] = ms_off
+        out["frc_overhead_pct_no_bubbles"] = 100.0 * (ms_on - ms_off) / ms_off
+        # mode C: bubbles sized from the failure-free forward time (one tick = one forward)
+        n_fwd_bwd = M * (cfg.tick_F + cfg.tick_B)
+        us_per_tick = ms_off * 1e3 / n_fwd_bwd
+        k_c = max(2, min(args.steps, 5))
+        ms_c_off = run_iters(prog_off, k_c, us_per_tick)
+        ms_c_on = run_iters(prog_on, k_c, us_per_tick)
+        out["bubble_mode"] = {"us_per_tick": us_per_tick, "ms_per_step_frc_off": ms_c_off,
+                              "ms_per_step_frc_on": ms_c_on,
+                              "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
+
+    # per-kernel-class roofline: the same iteration with an event pair around every launch
+    st.stage_profile(True)
+    k_p = max(1, min(args.steps, 3))
+    run_iters(prog_on, k_p)
+    classes = {}
+    for i, name in enumerate(B.KERNEL_CLASSES):
+        ms, n, work = st.stage_profile_read(i)
+        if n:
+            classes[name] = {"launches": n, "avg_us": ms * 1e3 / n, "total_ms_per_step": ms / k_p,
+                             "rate": work / (ms * 1e-3), "work_per_launch": work / n}
+    st.stage_profile(False)
+    gemm = [classes[c] for c in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if c in classes]
+    g_ms = sum(c["avg_us"] * c["launches"] for c in gemm) * 1e-3
+    g_work = sum(c["work_per_launch"] * c["launches"] for c in gemm)
+    g_n = sum(c["launches"] for c in gemm)
+    achieved = g_work / (g_ms * 1e-3) / 1e12
+    out["roofline"] = {"kernel": "stage GEMMs (forward, input-gradient, weight-gradient launches)", "bound": "mfma",
+                       "achieved": achieved, "peak": PEAK["mfma_bf16"] / 1e12, "unit": "TFLOP/s",
+                       "frac": achieved * 1e12 / PEAK["mfma_bf16"], "traffic": None,
+                       "launches_per_step": g_n // k_p, "avg_launch_us": g_ms * 1e3 / g_n,
+                       "flops_per_launch": g_work / g_n}
+    out["mfma_util_stage_gemms"] = out["roofline"]["frac"]
+    out["kernel_classes"] = {
+        k: {"avg_us": v["avg_us"], "launches_per_step": v["launches"] // k_p, "ms_per_step": v["total_ms_per_step"],
+            ("TFLOP/s" if k.startswith(("gemm", "attn")) else "GB/s"):
+                v["rate"] / (1e12 if k.startswith(("gemm", "attn")) else 1e9)}
+        for k, v in classes.items()}
+    st.stage_destroy()
+    del st, hz
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(sc)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -64,7 +64,7 @@ typedef struct {
   int32_t arch;        /* enum bamboo_arch */
   int32_t dtype;       /* enum bamboo_dtype */
   int32_t hidden;      /* H, multiple of 8 */
-  int32_t heads;       /* divides H; H/heads in {32, 64, 128} */
+  int32_t heads;       /* divides H; head size H/heads <= 128 */
   int32_t ffn;         /* F, multiple of 8 */
   int32_t seq;         /* S */
   int32_t micro_batch; /* samples per micro-batch */
@@ -212,6 +212,26 @@ int stage_join(bamboo_stage_t* st);
 
 /* JOIN and block the host until both lanes are idle. */
 int stage_sync(bamboo_stage_t* st);
+
+/* Per-kernel-class timing for roofline measurements (not part of the method).
+ * stage_profile(st, 1) clears earlier records and brackets every later kernel
+ * launch with a HIP event pair on the launch's own stream; stage_profile(st, 0)
+ * stops.  stage_profile_read synchronises, then reports for one class the summed
+ * launch durations in ms, the number of launches and the summed algorithmic work
+ * (flops for GEMM and attention classes, bytes for the others). */
+enum bamboo_kernel_class {
+  BAMBOO_K_GEMM_FWD = 0,   /* Y = X W (+bias, residual, GELU) */
+  BAMBOO_K_GEMM_DGRAD = 1, /* dX = dY W^T */
+  BAMBOO_K_GEMM_WGRAD = 2, /* dW += X^T dY */
+  BAMBOO_K_ATTN_FWD = 3,
+  BAMBOO_K_ATTN_BWD = 4,
+  BAMBOO_K_LN_FWD = 5,
+  BAMBOO_K_LN_BWD = 6,
+  BAMBOO_K_COLSUM = 7,
+  BAMBOO_K_COUNT = 8
+};
+int stage_profile(bamboo_stage_t* st, int enable);
+int stage_profile_read(bamboo_stage_t* st, int32_t kernel_class, double* total_ms, int64_t* launches, double* work);
 
 int stage_destroy(bamboo_stage_t* st);
 

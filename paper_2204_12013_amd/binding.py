@@ -22,6 +22,7 @@ lib = C.CDLL(LIB_PATH)
 
 OK, E_BADCFG, E_BADMB, E_STATE, E_HIP, E_ARG, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 (RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, FWD, BWD, FRC, BRC, BUBBLE, JOIN, ALLREDUCE, APPLY) = range(12)
+KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")
 
 
 class Cfg(C.Structure):
@@ -66,6 +67,8 @@ _SIGS = {
     "stage_join": (C.c_int, [_vp]),
     "stage_sync": (C.c_int, [_vp]),
     "stage_destroy": (C.c_int, [_vp]),
+    "stage_profile": (C.c_int, [_vp, C.c_int]),
+    "stage_profile_read": (C.c_int, [_vp, _i32, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]),
     "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
     "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
     "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 4),
@@ -211,6 +214,16 @@ class Stage:
 
     def stage_sync(self):
         _check(lib.stage_sync(self._h), "stage_sync")
+
+    def stage_profile(self, enable):
+        _check(lib.stage_profile(self._h, int(enable)), "stage_profile")
+
+    def stage_profile_read(self, kernel_class):
+        """(total ms, launches, algorithmic work) of one kernel class."""
+        ms, n, w = C.c_double(), C.c_int64(), C.c_double()
+        _check(lib.stage_profile_read(self._h, kernel_class, C.byref(ms), C.byref(n), C.byref(w)),
+               "stage_profile_read")
+        return ms.value, n.value, w.value
 
     def stage_destroy(self):
         if self._h:

@@ -154,6 +154,11 @@ struct bamboo_stage {
   std::vector<hipEvent_t> ev_fwd, ev_frc;
   hipEvent_t ev_join;
   int last_frc_on_lane1;
+  // optional per-kernel-class timing: an event pair around every launch
+  bool prof_on;
+  struct ProfRec { int cls; double work; hipEvent_t a, b; };
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
 };
 
 namespace {
@@ -169,7 +174,82 @@ namespace {
     }                                                                                         \
   } while (0)
 
+// Brackets one launch (or a short fixed group of launches of one class) with an
+// event pair on its stream when profiling is on.
+struct ProfScope {
+  bamboo_stage* st;
+  hipStream_t s;
+  hipEvent_t b;
+  ProfScope(bamboo_stage* st_, int cls, hipStream_t s_, double work) : st(st_), s(s_), b(nullptr) {
+    if (!st->prof_on) return;
+    hipEvent_t ev[2] = {nullptr, nullptr};
+    for (int i = 0; i < 2; ++i) {
+      if (!st->prof_pool.empty()) {
+        ev[i] = st->prof_pool.back();
+        st->prof_pool.pop_back();
+      } else if (hipEventCreate(&ev[i]) != hipSuccess) {
+        (void)hipGetLastError();
+        return;
+      }
+    }
+    if (hipEventRecord(ev[0], s) != hipSuccess) (void)hipGetLastError();
+    st->prof_recs.push_back({cls, work, ev[0], ev[1]});
+    b = ev[1];
+  }
+  ~ProfScope() {
+    if (b && hipEventRecord(b, s) != hipSuccess) (void)hipGetLastError();
+  }
+};
+
+double gemm_flops(const GemmDesc& d) { return 2.0 * d.M * d.N * d.K; }
+
 uint64_t esize(const bamboo_stage* st) { return st->cfg.dtype == BAMBOO_BF16 ? 2 : 4; }
+
+
+#define BBCHK(expr)                 \
+  do {                              \
+    const int rc_ = (expr);         \
+    if (rc_ != BAMBOO_OK) return rc_; \
+  } while (0)
+
+enum KernelClass { K_GEMM_FWD = 0, K_GEMM_DGRAD, K_GEMM_WGRAD, K_ATTN_FWD, K_ATTN_BWD, K_LN_FWD, K_LN_BWD, K_COLSUM, K_COUNT };
+
+int p_gemm(bamboo_stage* st, hipStream_t s, const GemmDesc& d) {
+  const int cls = d.epi == EPI_ACC_F32 ? K_GEMM_WGRAD : (d.b_sn == 1 ? K_GEMM_FWD : K_GEMM_DGRAD);
+  ProfScope ps(st, cls, s, gemm_flops(d));
+  HIPCHK(launch_gemm(s, st->cfg.dtype, d));
+  return BAMBOO_OK;
+}
+double attn_fwd_flops(const AttnDesc& a) {
+  return 4.0 * a.B * a.heads * (double)a.S * a.S * a.d * (a.causal ? 0.5 : 1.0);
+}
+int p_attn_fwd(bamboo_stage* st, hipStream_t s, const AttnDesc& a) {
+  ProfScope ps(st, K_ATTN_FWD, s, attn_fwd_flops(a));
+  HIPCHK(launch_attention_fwd(s, st->cfg.dtype, a));
+  return BAMBOO_OK;
+}
+int p_attn_bwd(bamboo_stage* st, hipStream_t s, const AttnDesc& a) {
+  ProfScope ps(st, K_ATTN_BWD, s, 2.5 * attn_fwd_flops(a));
+  HIPCHK(launch_attention_bwd(s, st->cfg.dtype, a));
+  return BAMBOO_OK;
+}
+int p_ln_fwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* r, const void* g, const void* b, void* y,
+             float* stats) {
+  ProfScope ps(st, K_LN_FWD, s, (double)T * (2.0 * H * esize(st) + 8.0));
+  HIPCHK(launch_layernorm_fwd(s, st->cfg.dtype, T, H, st->cfg.ln_eps, r, g, b, y, stats));
+  return BAMBOO_OK;
+}
+int p_ln_bwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* dout, const void* r, const float* stats,
+             const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta, float* partial) {
+  ProfScope ps(st, K_LN_BWD, s, (double)T * ((add ? 4.0 : 3.0) * H * esize(st) + 8.0));
+  HIPCHK(launch_layernorm_bwd(s, st->cfg.dtype, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial));
+  return BAMBOO_OK;
+}
+int p_colsum(bamboo_stage* st, hipStream_t s, int T, int N, const void* a, float* out, float* partial) {
+  ProfScope ps(st, K_COLSUM, s, (double)T * N * esize(st));
+  HIPCHK(launch_colsum_acc(s, st->cfg.dtype, T, N, a, out, partial));
+  return BAMBOO_OK;
+}
 
 GemmDesc gemm_nn(const void* X, const void* W, void* Y, int T, int N, int K, int epi) {
   GemmDesc d;
@@ -199,7 +279,7 @@ GemmDesc gemm_tn(const void* X, const void* dY, float* dW, int T, int Kw, int Nw
 int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x, void* y) {
   const bamboo_cfg_t& c = st->cfg;
   const int n = kind == 0 ? c.n_own : c.n_shadow;
-  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn;
   const uint64_t es = esize(st);
   hipStream_t s = st->lane[lane_id];
   (void)hipGetLastError();  // do not inherit an unrelated earlier error of this thread
@@ -220,38 +300,38 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
     a.qkv = rec + r.qkv; a.ctx = rec + r.ctx; a.lse = (float*)(rec + r.lse);
     GemmDesc d;
     if (c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL)
-      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.x, P(st->po.g1), P(st->po.be1), rec + r.ain,
+      BBCHK(p_ln_fwd(st, s, T, H, rec + r.x, P(st->po.g1), P(st->po.be1), rec + r.ain,
                                   (float*)(rec + r.ln1)));
     d = gemm_nn(rec + r.ain, P(st->po.Wqkv), rec + r.qkv, T, 3 * H, H, EPI_BIAS);
     d.bias = P(st->po.bqkv);
-    HIPCHK(launch_gemm(s, dt, d));
-    HIPCHK(launch_attention_fwd(s, dt, a));
+    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_attn_fwd(st, s, a));
     d = gemm_nn(rec + r.ctx, P(st->po.Wo), rec + r.r1, T, H, H, EPI_BIAS_RES);
     d.bias = P(st->po.bo);
     d.res = rec + r.x;
-    HIPCHK(launch_gemm(s, dt, d));
+    BBCHK(p_gemm(st, s, d));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER)
-      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r1, P(st->po.g1), P(st->po.be1), rec + r.fin,
+      BBCHK(p_ln_fwd(st, s, T, H, rec + r.r1, P(st->po.g1), P(st->po.be1), rec + r.fin,
                                   (float*)(rec + r.ln1)));
     else
-      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r1, P(st->po.g2), P(st->po.be2), rec + r.fin,
+      BBCHK(p_ln_fwd(st, s, T, H, rec + r.r1, P(st->po.g2), P(st->po.be2), rec + r.fin,
                                   (float*)(rec + r.ln2)));
     d = gemm_nn(rec + r.fin, P(st->po.W1), rec + r.h, T, F, H, EPI_BIAS_GELU);
     d.bias = P(st->po.b1);
     d.aux_out = gbuf;
-    HIPCHK(launch_gemm(s, dt, d));
+    BBCHK(p_gemm(st, s, d));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nn(gbuf, P(st->po.W2), rec + r.r2, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.fin;
-      HIPCHK(launch_gemm(s, dt, d));
-      HIPCHK(launch_layernorm_fwd(s, dt, T, H, c.ln_eps, rec + r.r2, P(st->po.g2), P(st->po.be2), out,
+      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_ln_fwd(st, s, T, H, rec + r.r2, P(st->po.g2), P(st->po.be2), out,
                                   (float*)(rec + r.ln2)));
     } else {
       d = gemm_nn(gbuf, P(st->po.W2), out, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.r1;
-      HIPCHK(launch_gemm(s, dt, d));
+      BBCHK(p_gemm(st, s, d));
     }
   }
   return BAMBOO_OK;
@@ -261,7 +341,7 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
 int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx) {
   const bamboo_cfg_t& c = st->cfg;
   const int n = kind == 0 ? c.n_own : c.n_shadow;
-  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn, dt = c.dtype;
+  const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn;
   const uint64_t es = esize(st);
   hipStream_t s = st->lane[0];
   (void)hipGetLastError();
@@ -293,51 +373,51 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     GemmDesc d;
     const void* df;     // gradient at the FFN output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
-      HIPCHK(launch_layernorm_bwd(s, dt, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
+      BBCHK(p_ln_bwd(st, s, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
                                   G + st->po.g2, G + st->po.be2, partial));
       df = d1;
     } else {
       df = dy;
     }
     // f = g W2 + b2
-    HIPCHK(launch_colsum_acc(s, dt, T, H, df, G + st->po.b2, partial));
+    BBCHK(p_colsum(st, s, T, H, df, G + st->po.b2, partial));
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_DGELU);
     d.aux_in = rec + r.h;
     d.aux_out = gbuf;
-    HIPCHK(launch_gemm(s, dt, d));
-    HIPCHK(launch_gemm(s, dt, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
+    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
     // h = fin W1 + b1
-    HIPCHK(launch_colsum_acc(s, dt, T, F, dh, G + st->po.b1, partial));
-    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
+    BBCHK(p_colsum(st, s, T, F, dh, G + st->po.b1, partial));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
       d.res = d1;
-      HIPCHK(launch_gemm(s, dt, d));
-      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
+      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_ln_bwd(st, s, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
                                   G + st->po.g1, G + st->po.be1, partial));
       da = d1;
     } else {
-      HIPCHK(launch_gemm(s, dt, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
-      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
+      BBCHK(p_gemm(st, s, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
+      BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
                                   G + st->po.g2, G + st->po.be2, partial));   // + residual branch of y = x1 + f
       da = d2;
     }
     // a = ctx Wo + bo
-    HIPCHK(launch_colsum_acc(s, dt, T, H, da, G + st->po.bo, partial));
-    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
-    HIPCHK(launch_gemm(s, dt, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
-    HIPCHK(launch_attention_bwd(s, dt, a));
+    BBCHK(p_colsum(st, s, T, H, da, G + st->po.bo, partial));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
+    BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
+    BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
-    HIPCHK(launch_colsum_acc(s, dt, T, 3 * H, dqkv, G + st->po.bqkv, partial));
-    HIPCHK(launch_gemm(s, dt, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
+    BBCHK(p_colsum(st, s, T, 3 * H, dqkv, G + st->po.bqkv, partial));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
       d.res = da;
-      HIPCHK(launch_gemm(s, dt, d));
+      BBCHK(p_gemm(st, s, d));
     } else {
-      HIPCHK(launch_gemm(s, dt, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
-      HIPCHK(launch_layernorm_bwd(s, dt, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
+      BBCHK(p_gemm(st, s, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
+      BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
                                   G + st->po.g1, G + st->po.be1, partial));   // + residual branch of x1 = x + a
     }
     dy = dx;
@@ -465,6 +545,7 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     st->ev_frc.assign(cfg->M, nullptr);
     st->ev_join = nullptr;
     st->last_frc_on_lane1 = -1;
+    st->prof_on = false;
   } catch (const std::bad_alloc&) {
     delete st;
     return BAMBOO_E_NOMEM;
@@ -599,8 +680,45 @@ int stage_sync(bamboo_stage_t* st) {
   return BAMBOO_OK;
 }
 
+int stage_profile(bamboo_stage_t* st, int enable) {
+  if (!st) return BAMBOO_E_ARG;
+  for (auto& r : st->prof_recs) {
+    st->prof_pool.push_back(r.a);
+    st->prof_pool.push_back(r.b);
+  }
+  st->prof_recs.clear();
+  st->prof_on = enable != 0;
+  return BAMBOO_OK;
+}
+
+int stage_profile_read(bamboo_stage_t* st, int32_t kernel_class, double* total_ms, int64_t* launches, double* work) {
+  if (!st || !total_ms || !launches || !work) return BAMBOO_E_ARG;
+  if (kernel_class < 0 || kernel_class >= K_COUNT) return BAMBOO_E_ARG;
+  const int rc = stage_sync(st);
+  if (rc != BAMBOO_OK) return rc;
+  double ms = 0.0, w = 0.0;
+  int64_t n = 0;
+  for (auto& r : st->prof_recs) {
+    if (r.cls != kernel_class) continue;
+    float t = 0.f;
+    HIPCHK(hipEventElapsedTime(&t, r.a, r.b));
+    ms += t;
+    w += r.work;
+    ++n;
+  }
+  *total_ms = ms;
+  *launches = n;
+  *work = w;
+  return BAMBOO_OK;
+}
+
 int stage_destroy(bamboo_stage_t* st) {
   if (!st) return BAMBOO_E_ARG;
+  for (auto& r : st->prof_recs) {
+    (void)hipEventDestroy(r.a);
+    (void)hipEventDestroy(r.b);
+  }
+  for (hipEvent_t e : st->prof_pool) (void)hipEventDestroy(e);
   for (hipEvent_t e : st->ev_fwd)
     if (e) (void)hipEventDestroy(e);
   for (hipEvent_t e : st->ev_frc)
