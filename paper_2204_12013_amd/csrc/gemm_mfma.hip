@@ -1,4 +1,341 @@
+// bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32
+// accumulation, fused epilogues.  One kernel template covers the three forms
+// the layer needs:
+//   forward          Y  = X W      A K-contiguous,  B N-contiguous
+//   input gradient   dX = dY W^T   A K-contiguous,  B K-contiguous
+//   weight gradient  dW += X^T dY  A M-contiguous,  B N-contiguous
+//
+// A workgroup of 4 wavefronts (2 x 2) owns a (64*WM) x (64*WN) output tile and
+// walks K in slices of 64.  Each slice is copied global -> registers -> LDS with
+// 16-byte accesses, double-buffered so that the loads of slice i+1 are in flight
+// while slice i feeds the MFMAs.  Operands whose contraction index is contiguous
+// in memory are kept as [row][k] in LDS and read with ds_read_b128; operands
+// whose contraction index is strided are kept in their memory order [k][row]
+// and read with the transposing LDS load (ds_read_b64_tr_b16), which hands each
+// lane four consecutive k of its row, so no operand is ever transposed in
+// registers or re-laid-out in HBM.  The accumulators leave through a
+// wavefront-private LDS staging area so that bias / residual / GELU inputs are
+// read and results written with 16-byte row-contiguous accesses.
+#include <type_traits>
+
 #include "common.h"
+
 namespace bamboo {
-hipError_t launch_gemm_mfma(hipStream_t, const GemmDesc&) { return hipErrorNotSupported; }
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) short short4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int BK = 64;          // k-slice
+constexpr int KROW = BK + 8;    // LDS row length (elements) of a k-contiguous operand: 144 B, conflict-free b128 reads
+
+template <int ROWS>
+struct MnMajor {                 // LDS row length (elements) of an operand stored [k][row]
+  static constexpr int LD = ROWS + 16;   // +32 B: the 4 k-rows of a transposing read fall in distinct banks
+};
+
+template <int WM, int WN, bool A_K, bool B_K>
+struct Smem {
+  static constexpr int BM = 64 * WM, BN = 64 * WN;
+  static constexpr int A_ELEMS = A_K ? BM * KROW : BK * MnMajor<BM>::LD;
+  static constexpr int B_ELEMS = B_K ? BN * KROW : BK * MnMajor<BN>::LD;
+  static constexpr int STAGE = A_ELEMS + B_ELEMS;                       // elements per pipeline stage
+  static constexpr int EPI_LD = 32 * WN + 4;                             // floats per staged output row
+  static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;                  // 4 waves x 32 rows
+  static constexpr int MAIN_BYTES = 2 * STAGE * 2;
+  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+};
+
+// ---- global -> register -> LDS copies of one operand slice --------------------
+// K-contiguous operand: ROWS rows x 64 k.  Element (row, k) at g[row*ld + k].
+template <int ROWS>
+struct LoadK {
+  static constexpr int N = ROWS / 32;    // 16-byte chunks per thread
+  bf16x8 v[N];
+  __device__ __forceinline__ void fetch(const bf16_t* g, long ld, int row0, int row_lim, int k0, int K) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int row = c >> 3, kc = (c & 7) * 8;
+      bf16x8 t = {};
+      if (row0 + row < row_lim && k0 + kc < K) t = *(const bf16x8*)(g + (long)(row0 + row) * ld + k0 + kc);
+      v[i] = t;
+    }
+  }
+  __device__ __forceinline__ void stash(bf16_t* s) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      *(bf16x8*)(s + (c >> 3) * KROW + (c & 7) * 8) = v[i];
+    }
+  }
+};
+// Row-contiguous operand: 64 k-rows x ROWS.  Element (row, k) at g[k*ld + row].
+template <int ROWS>
+struct LoadMN {
+  static constexpr int N = ROWS / 32;
+  static constexpr int CPR = ROWS / 8;   // chunks per k-row
+  bf16x8 v[N];
+  __device__ __forceinline__ void fetch(const bf16_t* g, long ld, int row0, int row_lim, int k0, int K) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int kr = c / CPR, rc = (c % CPR) * 8;
+      bf16x8 t = {};
+      if (k0 + kr < K && row0 + rc < row_lim) t = *(const bf16x8*)(g + (long)(k0 + kr) * ld + row0 + rc);
+      v[i] = t;
+    }
+  }
+  __device__ __forceinline__ void stash(bf16_t* s) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      *(bf16x8*)(s + (c / CPR) * MnMajor<ROWS>::LD + (c % CPR) * 8) = v[i];
+    }
+  }
+};
+
+// ---- LDS -> MFMA operand fragments ------------------------------------------------
+// Fragment of a 32-row block for k-step ks (16 k): lane l holds row l%32,
+// k = 8*(l/32) .. +7.
+__device__ __forceinline__ bf16x8 frag_k(const bf16_t* s, int row_base, int ks) {
+  const int l = threadIdx.x & 63;
+  return *(const bf16x8*)(s + (row_base + (l & 31)) * KROW + ks * 16 + (l >> 5) * 8);
 }
+template <int ROWS>
+__device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks) {
+  // transposing read: within 16 lanes, lane i addresses k-row i/4, columns 4*(i%4)..+3,
+  // and receives rows k..k+3 of column i
+  const int l = threadIdx.x & 63, i = l & 15;
+  const int col = row_base + ((l >> 4) & 1) * 16 + (i & 3) * 4;
+  const int k = ks * 16 + (l >> 5) * 8 + (i >> 2);
+  const bf16_t* p = s + k * MnMajor<ROWS>::LD + col;
+  typedef __attribute__((address_space(3))) short4_t* lds_ptr;
+  const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * MnMajor<ROWS>::LD));
+  union { short4_t s4[2]; bf16x8 b; } u;
+  u.s4[0] = lo;
+  u.s4[1] = hi;
+  return u.b;
+}
+
+// ---- epilogue on 8 consecutive outputs of one row ---------------------------------------
+template <int EPI>
+__device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8]) {
+  const long i = (long)m * d.N + n;
+  if (EPI == EPI_ACC_F32) {
+    float* c = (float*)d.C + i;
+    f32x4 a = *(f32x4*)c, b = *(f32x4*)(c + 4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { a[j] += acc[j]; b[j] += acc[4 + j]; }
+    *(f32x4*)c = a;
+    *(f32x4*)(c + 4) = b;
+    return;
+  }
+  float v[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = acc[j];
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+    const bf16x8 b = *(const bf16x8*)((const bf16_t*)d.bias + n);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += (float)b[j];
+  }
+  if (EPI == EPI_BIAS_RES || EPI == EPI_RES) {
+    const bf16x8 r = *(const bf16x8*)((const bf16_t*)d.res + i);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] += (float)r[j];
+  }
+  bf16x8 o;
+  if (EPI == EPI_DGELU) {
+    const bf16x8 h = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
+    bf16x8 g;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float hf = (float)h[j];
+      o[j] = (bf16_t)(v[j] * gelu_grad_f(hf));
+      g[j] = (bf16_t)gelu_f(hf);
+    }
+    *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (bf16_t)v[j];
+  }
+  *(bf16x8*)((bf16_t*)d.C + i) = o;
+  if (EPI == EPI_BIAS_GELU) {
+    bf16x8 g;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g[j] = (bf16_t)gelu_f((float)o[j]);   // GELU of the stored (rounded) h
+    *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
+  }
+}
+
+// Tile order: consecutive workgroup ids are spread round-robin over the 8 XCDs,
+// each with its own L2.  Give every XCD a contiguous range of tiles, and inside
+// the range walk down GROUP rows of tiles before moving to the next column, so
+// that the tiles an XCD works on at one time share operand slices in its L2.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int* tm, int* tn) {
+  const int nb = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  const int per = nb / 8;
+  if (pid < per * 8) pid = (pid % 8) * per + pid / 8;
+  constexpr int GROUP = 8;
+  const int width = GROUP * tiles_n;
+  const int group = pid / width;
+  const int first_m = group * GROUP;
+  const int rows = min(tiles_m - first_m, GROUP);
+  *tm = first_m + (pid % width) % rows;
+  *tn = (pid % width) / rows;
+}
+
+template <int WM, int WN, bool A_K, bool B_K, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
+  typedef Smem<WM, WN, A_K, B_K> SM;
+  constexpr int BM = SM::BM, BN = SM::BN;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;       // 2 x 2 wavefronts
+  int tile_m, tile_n;
+  tile_of_block((d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const bf16_t* A = (const bf16_t*)d.A;
+  const bf16_t* B = (const bf16_t*)d.B;
+  const long lda = A_K ? d.a_sm : d.a_sk;
+  const long ldb = B_K ? d.b_sn : d.b_sk;
+
+  typename std::conditional<A_K, LoadK<BM>, LoadMN<BM>>::type la;
+  typename std::conditional<B_K, LoadK<BN>, LoadMN<BN>>::type lb;
+
+  f32x16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (d.K + BK - 1) / BK;
+  la.fetch(A, lda, m0, d.M, 0, d.K);
+  lb.fetch(B, ldb, n0, d.N, 0, d.K);
+  la.stash(smem);
+  lb.stash(smem + SM::A_ELEMS);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16_t* sa = smem + (kt & 1) * SM::STAGE;
+    const bf16_t* sb = sa + SM::A_ELEMS;
+    const bool more = kt + 1 < nk;
+    if (more) {
+      la.fetch(A, lda, m0, d.M, (kt + 1) * BK, d.K);
+      lb.fetch(B, ldb, n0, d.N, (kt + 1) * BK, d.K);
+    }
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[WM], fb[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+        fa[i] = A_K ? frag_k(sa, wm * 32 * WM + i * 32, ks) : frag_mn<BM>(sa, wm * 32 * WM + i * 32, ks);
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        fb[j] = B_K ? frag_k(sb, wn * 32 * WN + j * 32, ks) : frag_mn<BN>(sb, wn * 32 * WN + j * 32, ks);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      bf16_t* na = smem + ((kt + 1) & 1) * SM::STAGE;
+      la.stash(na);
+      lb.stash(na + SM::A_ELEMS);
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue: accumulators -> wavefront-private LDS rows -> 16-byte global accesses
+  float* stage = (float*)smem_raw + wave * 32 * SM::EPI_LD;
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    // D[row][col]: lane holds col = lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SM::EPI_LD + j * 32 + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the wave's own LDS writes have landed
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CHUNKS = 4 * WN;        // 8-float chunks per staged row
+#pragma unroll
+    for (int it = 0; it < 32 * CHUNKS / 64; ++it) {
+      const int idx = lane + it * 64;
+      const int row = idx / CHUNKS, ch = idx % CHUNKS;
+      const int m = m0 + wm * 32 * WM + i * 32 + row;
+      const int n = n0 + wn * 32 * WN + ch * 8;
+      const f32x4 lo = *(const f32x4*)(stage + row * SM::EPI_LD + ch * 8);
+      const f32x4 hi = *(const f32x4*)(stage + row * SM::EPI_LD + ch * 8 + 4);
+      if (m < d.M && n < d.N) {
+        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        epilogue8<EPI>(d, m, n, v);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
+  }
+}
+
+template <int WM, int WN, bool A_K, bool B_K, int EPI>
+static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
+  typedef Smem<WM, WN, A_K, B_K> SM;
+  static bool attr_set = false;
+  auto kern = gemm_mfma_kernel<WM, WN, A_K, B_K, EPI>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles = ((d.M + SM::BM - 1) / SM::BM) * ((d.N + SM::BN - 1) / SM::BN);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
+  return hipGetLastError();
+}
+
+template <bool A_K, bool B_K, int EPI>
+static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
+  // tile choice: the largest tile that still gives every CU work
+  const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
+  if (t128 >= 4 * 256 && d.M >= 256 && d.N >= 256) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
+  if (t128 >= 2 * 256 && d.M >= 256) return launch_cfg<4, 2, A_K, B_K, EPI>(s, d);
+  return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
+}
+
+hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {
+  const bool a_k = d.a_sk == 1, b_k = d.b_sk == 1;
+  if (!a_k && d.a_sm != 1) return hipErrorNotSupported;
+  if (!b_k && d.b_sn != 1) return hipErrorNotSupported;
+  // 16-byte accesses everywhere: dimensions and leading dimensions in multiples of 8
+  const long lda = a_k ? d.a_sm : d.a_sk, ldb = b_k ? d.b_sn : d.b_sk;
+  if (d.M % 8 || d.N % 8 || d.K % 8 || lda % 8 || ldb % 8) return hipErrorNotSupported;
+  auto misaligned = [](const void* p) { return p != nullptr && ((uintptr_t)p & 15) != 0; };
+  if (misaligned(d.A) || misaligned(d.B) || misaligned(d.C) || misaligned(d.bias) || misaligned(d.res) ||
+      misaligned(d.aux_in) || misaligned(d.aux_out))
+    return hipErrorNotSupported;
+  if (a_k && !b_k) {           // forward
+    switch (d.epi) {
+      case EPI_BIAS: return launch_form<true, false, EPI_BIAS>(s, d);
+      case EPI_BIAS_RES: return launch_form<true, false, EPI_BIAS_RES>(s, d);
+      case EPI_BIAS_GELU: return launch_form<true, false, EPI_BIAS_GELU>(s, d);
+      default: return hipErrorNotSupported;
+    }
+  }
+  if (a_k && b_k) {            // input gradient
+    switch (d.epi) {
+      case EPI_STORE: return launch_form<true, true, EPI_STORE>(s, d);
+      case EPI_RES: return launch_form<true, true, EPI_RES>(s, d);
+      case EPI_DGELU: return launch_form<true, true, EPI_DGELU>(s, d);
+      default: return hipErrorNotSupported;
+    }
+  }
+  if (!a_k && !b_k && d.epi == EPI_ACC_F32) return launch_form<false, false, EPI_ACC_F32>(s, d);
+  return hipErrorNotSupported;
+}
+
+}  // namespace bamboo

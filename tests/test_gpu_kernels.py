@@ -34,6 +34,10 @@ def _empty(shape, dtype):
 
 IMPLS = [(0, 1), (1, 1), (1, 0)]          # (dtype, impl)
 GEMM_SHAPES = [(32, 64, 64), (200, 136, 72), (333, 520, 264), (512, 768, 256)]
+# shapes for the MFMA kernel alone: every tile configuration (128x128, 256x128,
+# 256x256 output tiles), ragged edges in all three dimensions, K tails
+MFMA_SHAPES = [(8, 8, 8), (136, 264, 72), (520, 392, 200), (1024, 1024, 512), (4096, 2048, 192),
+               (4096, 4096, 128), (4104, 4040, 72), (2048, 1600, 320)]
 
 
 @pytest.mark.parametrize("dtype,impl", IMPLS)
@@ -52,6 +56,27 @@ def test_linear_forward_variants(B, dtype, impl, T, N, K):
     B.bk_linear_fwd(_dev(B, X, dtype), _dev(B, W, dtype), _dev(B, b, dtype), Y, gelu_out=G, impl=impl)
     assert rel_l2(B.to_host(Y), ref) <= TOL[dtype]
     assert rel_l2(B.to_host(G), L.gelu(ref)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("T,N,K", MFMA_SHAPES)
+def test_linear_forward_mfma(B, T, N, K):
+    test_linear_forward_variants(B, 1, 2, T, N, K)
+
+
+@pytest.mark.parametrize("T,N,K", MFMA_SHAPES)
+def test_linear_backward_mfma(B, T, N, K):
+    test_linear_backward_variants(B, 1, 2, T, N, K)
+
+
+def test_mfma_kernel_refuses_what_it_does_not_cover(B):
+    X, W, b = _empty((12, 16), 1), _empty((16, 24), 1), _empty((24,), 1)
+    with pytest.raises(B.BambooError) as e:
+        B.bk_linear_fwd(X, W, b, _empty((12, 24), 1), impl=2)        # 12 rows: not a multiple of 8
+    assert e.value.status == B.E_STATE
+    Xf, Wf, bf = _empty((16, 16), 0), _empty((16, 24), 0), _empty((24,), 0)
+    with pytest.raises(B.BambooError) as e:
+        B.bk_linear_fwd(Xf, Wf, bf, _empty((16, 24), 0), impl=2)     # fp32 has no MFMA kernel here
+    assert e.value.status == B.E_STATE
 
 
 @pytest.mark.parametrize("dtype,impl", IMPLS)
@@ -117,15 +142,16 @@ def test_layernorm_forward_backward(B, dtype, T, H):
     assert rel_l2(dg.cpu().numpy(), 2 * dg_ref) <= 1e-4
 
 
-ATTN_CASES = [(2, 16, 2, 32), (1, 100, 3, 64), (2, 200, 2, 128), (3, 77, 2, 40), (1, 512, 2, 64), (1, 300, 1, 128)]
+ATTN_CASES = [(2, 16, 2, 32), (1, 100, 3, 64), (2, 200, 2, 128), (3, 77, 2, 40), (1, 512, 2, 64), (1, 300, 1, 128),
+              (1, 1, 1, 64), (1, 129, 2, 64), (1, 8, 1, 128)]
 
 
-@pytest.mark.parametrize("dtype,impl", IMPLS)
+@pytest.mark.parametrize("dtype,impl", IMPLS + [(1, 2)])
 @pytest.mark.parametrize("causal", [0, 1])
 @pytest.mark.parametrize("batch,seq,heads,d", ATTN_CASES)
 def test_attention_forward_backward(B, dtype, impl, causal, batch, seq, heads, d):
-    if impl == 0 and d not in (64, 128):
-        pytest.skip("automatic choice equals the vector-ALU kernel for this head size")
+    if impl in (0, 2) and d not in (64, 128):
+        pytest.skip("the MFMA kernel covers head sizes 64 and 128 only")
     rng = np.random.default_rng(seq + d + causal)
     H, T = heads * d, batch * seq
     qkv = _mk(rng, (T, 3 * H), dtype)
