@@ -16,6 +16,8 @@
 // registers or re-laid-out in HBM.  The accumulators leave through a
 // wavefront-private LDS staging area so that bias / residual / GELU inputs are
 // read and results written with 16-byte row-contiguous accesses.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "common.h"
@@ -121,6 +123,86 @@ __device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks)
   return u.b;
 }
 
+
+// ---- direct global -> LDS copies (global_load_lds_dwordx4) -----------------------
+// The load writes 16 bytes per lane to consecutive LDS addresses starting at a
+// wavefront-uniform base, so a slice cannot be padded per row.  Bank conflicts
+// are avoided instead by choosing WHICH 16-byte chunk of global memory each
+// lane fetches: chunks are XOR-swizzled inside their LDS row, and the fragment
+// readers apply the same XOR.  Out-of-range rows are clamped to a valid row (they
+// only feed output rows/columns that are never stored); K must be a multiple of
+// the 64-wide slice.
+// Written as inline assembly so that the compiler's wait-count insertion does
+// not see an LDS write that "may alias" every later LDS read and serialise the
+// copy with the MFMAs; the kernel waits for vmcnt(0) itself before the barrier
+// that publishes a slice.  M0 carries the wavefront-uniform LDS base.
+__device__ __forceinline__ void load16_to_lds(const bf16_t* src, bf16_t* lds_wave_base) {
+  const unsigned lds_addr =
+      __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(src)
+               : "memory", "m0");
+}
+// K-contiguous operand, ROWS x 64: LDS row r = 128 bytes, chunk c stored at position c ^ (r % 8).
+template <int ROWS>
+struct DlK {
+  static constexpr int ELEMS = ROWS * BK;
+  __device__ static __forceinline__ void issue(const bf16_t* g, long ld, int row0, int row_lim, int k0, bf16_t* s) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < ROWS / 32; ++i) {
+      const int c = i * 256 + wave * 64 + lane;
+      const int r = c >> 3, p = c & 7;
+      const int row = min(row0 + r, row_lim - 1);
+      load16_to_lds(g + (long)row * ld + k0 + ((p ^ (r & 7)) << 3), s + (i * 256 + wave * 64) * 8);
+    }
+  }
+  __device__ static __forceinline__ bf16x8 frag(const bf16_t* s, int row_base, int ks) {
+    const int l = threadIdx.x & 63;
+    const int r = row_base + (l & 31), kc = 2 * ks + (l >> 5);
+    return *(const bf16x8*)(s + r * BK + ((kc ^ (r & 7)) << 3));
+  }
+};
+// Row-contiguous operand, 64 k-rows x ROWS: chunk c of k-row k stored at position c ^ (2 * (k % 4)),
+// which spreads the four k-rows of a transposing read over distinct banks.
+template <int ROWS>
+struct DlMN {
+  static constexpr int ELEMS = ROWS * BK;
+  static constexpr int CPR = ROWS / 8;
+  __device__ static __forceinline__ void issue(const bf16_t* g, long ld, int row0, int row_lim, int k0, bf16_t* s) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < ROWS / 32; ++i) {
+      const int c = i * 256 + wave * 64 + lane;
+      const int kr = c / CPR, p = c % CPR;
+      const int col = min(row0 + ((p ^ (2 * (kr & 3))) << 3), row_lim - 8);
+      load16_to_lds(g + (long)(k0 + kr) * ld + col, s + (i * 256 + wave * 64) * 8);
+    }
+  }
+  __device__ static __forceinline__ bf16x8 frag(const bf16_t* s, int row_base, int ks) {
+    const int l = threadIdx.x & 63, i = l & 15;
+    const int col = row_base + ((l >> 4) & 1) * 16 + (i & 3) * 4;
+    const int k = ks * 16 + (l >> 5) * 8 + (i >> 2);
+    const bf16_t* p = s + k * ROWS + ((((col >> 3) ^ (2 * (k & 3)))) << 3) + (col & 7);
+    typedef __attribute__((address_space(3))) short4_t* lds_ptr;
+    union { short4_t s4[2]; bf16x8 b; } u;
+    u.s4[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    u.s4[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ROWS));
+    return u.b;
+  }
+};
+
+template <int WM, int WN>
+struct SmemDl {
+  static constexpr int BM = 64 * WM, BN = 64 * WN;
+  static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
+  static constexpr int EPI_LD = 32 * WN + 4;
+  static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
+  static constexpr int MAIN_BYTES = 2 * STAGE * 2;
+  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+};
+
 // ---- epilogue on 8 consecutive outputs of one row ---------------------------------------
 template <int EPI>
 __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8]) {
@@ -153,9 +235,10 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
     bf16x8 g;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const float hf = (float)h[j];
-      o[j] = (bf16_t)(v[j] * gelu_grad_f(hf));
-      g[j] = (bf16_t)gelu_f(hf);
+      float gv, dgv;
+      gelu_pair_fast((float)h[j], &gv, &dgv);
+      o[j] = (bf16_t)(v[j] * dgv);
+      g[j] = (bf16_t)gv;
     }
     *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
   } else {
@@ -166,8 +249,46 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
   if (EPI == EPI_BIAS_GELU) {
     bf16x8 g;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) g[j] = (bf16_t)gelu_f((float)o[j]);   // GELU of the stored (rounded) h
+    for (int j = 0; j < 8; ++j) {   // GELU of the stored (rounded) h
+      float gv, dgv;
+      gelu_pair_fast((float)o[j], &gv, &dgv);
+      g[j] = (bf16_t)gv;
+    }
     *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
+  }
+}
+
+// Accumulators -> wavefront-private LDS rows -> 16-byte global accesses.
+template <int WM, int WN, int EPI, int EPI_LD>
+__device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][WN], float* stage_all, int m0, int n0) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  float* stage = stage_all + wave * 32 * EPI_LD;
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    // D[row][col]: lane holds col = lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EPI_LD + j * 32 + (lane & 31)] = acc[i][j][r];
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the wave's own LDS writes have landed
+    __builtin_amdgcn_wave_barrier();
+    constexpr int CHUNKS = 4 * WN;        // 8-float chunks per staged row
+#pragma unroll
+    for (int it = 0; it < 32 * CHUNKS / 64; ++it) {
+      const int idx = lane + it * 64;
+      const int row = idx / CHUNKS, ch = idx % CHUNKS;
+      const int m = m0 + wm * 32 * WM + i * 32 + row;
+      const int n = n0 + wn * 32 * WN + ch * 8;
+      const f32x4 lo = *(const f32x4*)(stage + row * EPI_LD + ch * 8);
+      const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
+      if (m < d.M && n < d.N) {
+        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        epilogue8<EPI>(d, m, n, v);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
   }
 }
 
@@ -216,19 +337,31 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Pipeline: while slice kt feeds the MFMAs from one LDS buffer, slice kt+1
+  // (fetched during the previous iteration) is written to the other buffer and
+  // the global loads of slice kt+2 are issued, so a load has a whole iteration
+  // to land before anything waits for it.
   const int nk = (d.K + BK - 1) / BK;
   la.fetch(A, lda, m0, d.M, 0, d.K);
   lb.fetch(B, ldb, n0, d.N, 0, d.K);
   la.stash(smem);
   lb.stash(smem + SM::A_ELEMS);
+  if (nk > 1) {
+    la.fetch(A, lda, m0, d.M, BK, d.K);
+    lb.fetch(B, ldb, n0, d.N, BK, d.K);
+  }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const bf16_t* sa = smem + (kt & 1) * SM::STAGE;
     const bf16_t* sb = sa + SM::A_ELEMS;
-    const bool more = kt + 1 < nk;
-    if (more) {
-      la.fetch(A, lda, m0, d.M, (kt + 1) * BK, d.K);
-      lb.fetch(B, ldb, n0, d.N, (kt + 1) * BK, d.K);
+    if (kt + 1 < nk) {
+      bf16_t* na = smem + ((kt + 1) & 1) * SM::STAGE;
+      la.stash(na);
+      lb.stash(na + SM::A_ELEMS);
+    }
+    if (kt + 2 < nk) {
+      la.fetch(A, lda, m0, d.M, (kt + 2) * BK, d.K);
+      lb.fetch(B, ldb, n0, d.N, (kt + 2) * BK, d.K);
     }
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
@@ -245,46 +378,87 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
         for (int j = 0; j < WN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
-      bf16_t* na = smem + ((kt + 1) & 1) * SM::STAGE;
-      la.stash(na);
-      lb.stash(na + SM::A_ELEMS);
-    }
     __syncthreads();
   }
 
-  // ---- epilogue: accumulators -> wavefront-private LDS rows -> 16-byte global accesses
-  float* stage = (float*)smem_raw + wave * 32 * SM::EPI_LD;
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
+}
+
+// Same tiling with direct global -> LDS loads (K a multiple of 64).
+template <int WM, int WN, bool A_K, bool B_K, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_dl_kernel(GemmDesc d) {
+  typedef SmemDl<WM, WN> SM;
+  constexpr int BM = SM::BM, BN = SM::BN;
+  typedef typename std::conditional<A_K, DlK<BM>, DlMN<BM>>::type OpA;
+  typedef typename std::conditional<B_K, DlK<BN>, DlMN<BN>>::type OpB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* smem = (bf16_t*)smem_raw;
+  const int wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of_block((d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const bf16_t* A = (const bf16_t*)d.A;
+  const bf16_t* B = (const bf16_t*)d.B;
+  const long lda = A_K ? d.a_sm : d.a_sk;
+  const long ldb = B_K ? d.b_sn : d.b_sk;
+
+  f32x16 acc[WM][WN];
 #pragma unroll
-  for (int i = 0; i < WM; ++i) {
-    // D[row][col]: lane holds col = lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
+  for (int i = 0; i < WM; ++i)
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * SM::EPI_LD + j * 32 + (lane & 31)] = acc[i][j][r];
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the wave's own LDS writes have landed
-    __builtin_amdgcn_wave_barrier();
-    constexpr int CHUNKS = 4 * WN;        // 8-float chunks per staged row
-#pragma unroll
-    for (int it = 0; it < 32 * CHUNKS / 64; ++it) {
-      const int idx = lane + it * 64;
-      const int row = idx / CHUNKS, ch = idx % CHUNKS;
-      const int m = m0 + wm * 32 * WM + i * 32 + row;
-      const int n = n0 + wn * 32 * WN + ch * 8;
-      const f32x4 lo = *(const f32x4*)(stage + row * SM::EPI_LD + ch * 8);
-      const f32x4 hi = *(const f32x4*)(stage + row * SM::EPI_LD + ch * 8 + 4);
-      if (m < d.M && n < d.N) {
-        const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI>(d, m, n, v);
-      }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = d.K / BK;
+  OpA::issue(A, lda, m0, d.M, 0, smem);
+  OpB::issue(B, ldb, n0, d.N, 0, smem + SM::A_ELEMS);
+  __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0): this wave's slice has landed in LDS
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const bf16_t* sa = smem + (kt & 1) * SM::STAGE;
+    const bf16_t* sb = sa + SM::A_ELEMS;
+    if (kt + 1 < nk) {                    // next slice streams into the other buffer while this one is consumed
+      bf16_t* na = smem + ((kt + 1) & 1) * SM::STAGE;
+      OpA::issue(A, lda, m0, d.M, (kt + 1) * BK, na);
+      OpB::issue(B, ldb, n0, d.N, (kt + 1) * BK, na + SM::A_ELEMS);
     }
-    __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[WM], fb[WN];
+#pragma unroll
+      for (int i = 0; i < WM; ++i) fa[i] = OpA::frag(sa, wm * 32 * WM + i * 32, ks);
+#pragma unroll
+      for (int j = 0; j < WN; ++j) fb[j] = OpB::frag(sb, wn * 32 * WN + j * 32, ks);
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0f70);
+    __syncthreads();
   }
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI>
 static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
+  const int tiles = ((d.M + 64 * WM - 1) / (64 * WM)) * ((d.N + 64 * WN - 1) / (64 * WN));
+  static const bool no_direct = getenv("BAMBOO_GEMM_NO_DIRECT") != nullptr;   // tuning knob
+  if (d.K % BK == 0 && !no_direct) {
+    typedef SmemDl<WM, WN> SM;
+    static bool attr_set = false;
+    auto kern = gemm_mfma_dl_kernel<WM, WN, A_K, B_K, EPI>;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
+    return hipGetLastError();
+  }
   typedef Smem<WM, WN, A_K, B_K> SM;
   static bool attr_set = false;
   auto kern = gemm_mfma_kernel<WM, WN, A_K, B_K, EPI>;
@@ -293,18 +467,26 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int tiles = ((d.M + SM::BM - 1) / SM::BM) * ((d.N + SM::BN - 1) / SM::BN);
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
   return hipGetLastError();
 }
 
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
-  // tile choice: the largest tile that still gives every CU work
+  // (BAMBOO_GEMM_TILE=1|3|4 forces 128x128 | 256x256 | 64x64 output tiles for tuning runs)
+  static const int forced = getenv("BAMBOO_GEMM_TILE") ? atoi(getenv("BAMBOO_GEMM_TILE")) : 0;
+  if (forced == 1) return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
+  if (forced == 3) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
+  if (forced == 4) return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
+  // Tile choice.  256x256 tiles have the best MFMA : LDS ratio but only pay when
+  // they still come in at least two rounds over the 256 CUs; 128x128 tiles (two
+  // workgroups per CU) are the default; outputs too small to give every CU a
+  // 128x128 tile use 64x64 tiles.
+  const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
   const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
-  if (t128 >= 4 * 256 && d.M >= 256 && d.N >= 256) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
-  if (t128 >= 2 * 256 && d.M >= 256) return launch_cfg<4, 2, A_K, B_K, EPI>(s, d);
-  return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
+  if (t256 >= 2 * 256) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
+  if (t128 >= 192) return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
+  return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
 }
 
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {
