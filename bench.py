@@ -71,6 +71,8 @@ def main():
     ap.add_argument("--workload", default="bert_large_stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-modes", action="store_true", help="time mode B only (for profiler runs)")
+    ap.add_argument("--profile-frc-off", action="store_true",
+                    help="run the per-kernel-class pass without FRC (one lane: kernel times free of contention)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one stage on ONE GPU; --gpus %d is not supported (no collectives, no second "
@@ -160,7 +162,7 @@ def main():
     # per-kernel-class roofline: the same iteration with an event pair around every launch
     st.stage_profile(True)
     k_p = max(1, min(args.steps, 3))
-    run_iters(prog_on, k_p)
+    run_iters(prog_off if args.profile_frc_off else prog_on, k_p)
     classes = {}
     for i, name in enumerate(B.KERNEL_CLASSES):
         ms, n, work = st.stage_profile_read(i)

@@ -34,9 +34,11 @@ int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const
 int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY, const void* W, const void* res,
                         const void* h_in, void* dX, void* gelu_out, void* stream);
 
-/* dW[K,N] (fp32) += X[T,K]^T dY[T,N]. */
+/* dW[K,N] (fp32) += X[T,K]^T dY[T,N]; if db != NULL also db[N] (fp32) += sum over
+ * tokens of dY (the bias gradient of the same linear layer), with
+ * partial = fp32 scratch of bk_colsum_scratch_floats(N) floats. */
 int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X, const void* dY, float* dW,
-                         void* stream);
+                         float* db, float* partial, void* stream);
 
 /* out[N] (fp32) += sum over tokens of A[T,N]; partial: fp32 scratch of
  * bk_colsum_scratch_floats(N) floats.  Fixed summation order. */

@@ -71,7 +71,7 @@ _SIGS = {
     "stage_profile_read": (C.c_int, [_vp, _i32, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]),
     "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
     "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
-    "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 4),
+    "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
     "bk_colsum_acc": (C.c_int, [C.c_int] * 3 + [_vp] * 4),
     "bk_colsum_scratch_floats": (C.c_uint64, [C.c_int]),
     "bk_attention_fwd": (C.c_int, [C.c_int] * 7 + [_vp] * 4),
@@ -264,11 +264,16 @@ def bk_linear_bwd_input(dY, W, dX, res=None, h_in=None, gelu_out=None, impl=0, s
                                    _ptr(gelu_out), _stream(stream)), "bk_linear_bwd_input")
 
 
-def bk_linear_bwd_weight(X, dY, dW, impl=0, stream=None):
+def bk_linear_bwd_weight(X, dY, dW, db=None, impl=0, stream=None):
+    import torch
     T, K = X.shape
     N = dY.shape[1]
-    _check(lib.bk_linear_bwd_weight(_dt(X), impl, T, K, N, _ptr(X), _ptr(dY), _ptr(dW), _stream(stream)),
-           "bk_linear_bwd_weight")
+    partial = None
+    if db is not None:
+        partial = torch.empty(int(lib.bk_colsum_scratch_floats(N)), dtype=torch.float32, device=X.device)
+    _check(lib.bk_linear_bwd_weight(_dt(X), impl, T, K, N, _ptr(X), _ptr(dY), _ptr(dW), _ptr(db), _ptr(partial),
+                                    _stream(stream)), "bk_linear_bwd_weight")
+    return partial
 
 
 def bk_colsum_acc(A, out, stream=None):

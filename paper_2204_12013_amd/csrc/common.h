@@ -81,6 +81,11 @@ struct GemmDesc {
   const void* res;      // [M,N]
   const void* aux_in;   // [M,N]
   void* aux_out;        // [M,N]
+  // weight-gradient form only (honoured by launch_gemm, not by the kernels):
+  // colsum_out[n] (fp32) += sum_k B(k,n), i.e. the bias gradient that belongs to
+  // the same dY; colsum_partial is scratch of colsum_partial_floats(N) floats
+  float* colsum_out;
+  float* colsum_partial;
 };
 
 // dtype: 0 fp32, 1 bf16 (enum bamboo_dtype).  All launchers return hipError_t
@@ -120,6 +125,8 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const vo
                                 float* dbeta, float* partial);
 // out[n] (fp32) += sum_t a[t,n]; partial: fp32 scratch of colsum_partial_floats(N)
 hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial);
+// out[n] += sum over the first `parts` rows of partial[parts][N], in order
+hipError_t launch_colsum_final(hipStream_t s, int N, int parts, const float* partial, float* out);
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);

@@ -101,6 +101,10 @@ hipError_t launch_gemm_simple(hipStream_t s, int dtype, const GemmDesc& d) {
 }
 
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d) {
+  if (d.colsum_out != nullptr) {   // bias gradient: dY is the B operand [K rows, N] of the weight-gradient form
+    hipError_t e = launch_colsum_acc(s, dtype, d.K, d.N, d.B, d.colsum_out, d.colsum_partial);
+    if (e != hipSuccess) return e;
+  }
   if (dtype == 1) {
     hipError_t e = launch_gemm_mfma(s, d);
     if (e != hipErrorNotSupported) return e;

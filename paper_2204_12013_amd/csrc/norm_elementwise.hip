@@ -1,9 +1,10 @@
 // LayerNorm forward/backward, column reductions (bias and gain/shift
 // gradients) and the simulated-bubble kernel.  All HBM-bound: one wavefront per
-// token row, 16-byte vector loads, wavefront reductions; the later passes over a
-// row hit L2.  Reductions over tokens are two-stage with a fixed order, so the
-// results are bitwise reproducible (needed for FRC == FNC and for
-// failover == failure-free gradients).
+// token row, 16-byte vector accesses, rows held in registers between the
+// statistics pass and the output pass, wavefront reductions.  Reductions over
+// tokens are two-stage with a fixed order (per-workgroup partial sums, then one
+// ordered sum), so results are bitwise reproducible -- needed for FRC == FNC
+// and for failover == failure-free gradients.
 #include "common.h"
 
 namespace bamboo {
@@ -11,22 +12,23 @@ namespace bamboo {
 template <typename T> struct Vec;
 template <> struct Vec<float> {
   static constexpr int N = 4;
-  typedef float4 raw;
-  __device__ static void load(const float* p, float (&v)[4]) {
+  __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
     const float4 t = *(const float4*)p;
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
   }
-  __device__ static void store(float* p, const float (&v)[4]) { *(float4*)p = make_float4(v[0], v[1], v[2], v[3]); }
+  __device__ static __forceinline__ void store(float* p, const float (&v)[4]) {
+    *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+  }
 };
 template <> struct Vec<bf16_t> {
   static constexpr int N = 8;
   typedef __attribute__((ext_vector_type(8))) __bf16 raw;
-  __device__ static void load(const bf16_t* p, float (&v)[8]) {
+  __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
     const raw t = *(const raw*)p;
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
   }
-  __device__ static void store(bf16_t* p, const float (&v)[8]) {
+  __device__ static __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
     raw t;
 #pragma unroll
     for (int i = 0; i < 8; ++i) t[i] = (bf16_t)v[i];
@@ -34,11 +36,64 @@ template <> struct Vec<bf16_t> {
   }
 };
 
+constexpr int kMaxPartials = 256;   // workgroups contributing partial column sums
+
 // ------------------------------------------------------------ LayerNorm forward
-template <typename T>
+// NCH = vector chunks a lane keeps in registers (row length <= NCH * 64 * V).
+template <typename T, int NCH>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int T_rows, int H, float eps, const T* __restrict__ r,
                                                             const T* __restrict__ gamma, const T* __restrict__ beta,
                                                             T* __restrict__ y, float* __restrict__ stats) {
+  constexpr int V = Vec<T>::N;
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T_rows) return;
+  const T* rr = r + (long)row * H;
+  const int nvec = H / V;
+  float v[NCH][V];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+      Vec<T>::load(rr + c * V, v[j]);
+#pragma unroll
+      for (int i = 0; i < V; ++i) s += v[j][i];
+    }
+  }
+  const float mean = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j)
+    if (lane + 64 * j < nvec) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) q += (v[j][i] - mean) * (v[j][i] - mean);
+    }
+  const float rstd = rsqrtf(wave_sum(q) / (float)H + eps);
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane + 64 * j;
+    if (c < nvec) {
+      float g[V], b[V], o[V];
+      Vec<T>::load(gamma + c * V, g);
+      Vec<T>::load(beta + c * V, b);
+#pragma unroll
+      for (int i = 0; i < V; ++i) o[i] = g[i] * ((v[j][i] - mean) * rstd) + b[i];
+      Vec<T>::store(y + (long)row * H + c * V, o);
+    }
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
+// any row length: three passes over the row (the later ones hit L2)
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_long_kernel(int T_rows, int H, float eps, const T* __restrict__ r,
+                                                                 const T* __restrict__ gamma,
+                                                                 const T* __restrict__ beta, T* __restrict__ y,
+                                                                 float* __restrict__ stats) {
   constexpr int V = Vec<T>::N;
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -76,20 +131,116 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int T_rows, int H, f
   }
 }
 
-hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, int T, int H, float eps, const void* r, const void* gamma,
-                                const void* beta, void* y, float* stats) {
-  dim3 grid((T + 3) / 4);
-  if (dtype == 0)
-    hipLaunchKernelGGL(layernorm_fwd_kernel<float>, grid, dim3(256), 0, s, T, H, eps, (const float*)r,
-                       (const float*)gamma, (const float*)beta, (float*)y, stats);
-  else
-    hipLaunchKernelGGL(layernorm_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, T, H, eps, (const bf16_t*)r,
-                       (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, stats);
+template <typename T>
+static hipError_t ln_fwd_impl(hipStream_t s, int T_rows, int H, float eps, const void* r, const void* gamma,
+                              const void* beta, void* y, float* stats) {
+  constexpr int V = Vec<T>::N;
+  dim3 grid((T_rows + 3) / 4);
+  const int nch = (H / V + 63) / 64;
+#define LN_FWD(K)                                                                                              \
+  hipLaunchKernelGGL(K, grid, dim3(256), 0, s, T_rows, H, eps, (const T*)r, (const T*)gamma, (const T*)beta, \
+                     (T*)y, stats)
+  if (nch <= 1) LN_FWD((layernorm_fwd_kernel<T, 1>));
+  else if (nch <= 2) LN_FWD((layernorm_fwd_kernel<T, 2>));
+  else if (nch <= 4) LN_FWD((layernorm_fwd_kernel<T, 4>));
+  else if (nch <= 8) LN_FWD((layernorm_fwd_kernel<T, 8>));
+  else LN_FWD(layernorm_fwd_long_kernel<T>);
+#undef LN_FWD
   return hipGetLastError();
 }
 
+hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, int T, int H, float eps, const void* r, const void* gamma,
+                                const void* beta, void* y, float* stats) {
+  return dtype == 0 ? ln_fwd_impl<float>(s, T, H, eps, r, gamma, beta, y, stats)
+                    : ln_fwd_impl<bf16_t>(s, T, H, eps, r, gamma, beta, y, stats);
+}
+
 // ----------------------------------------------------------- LayerNorm backward
-// dr = (dhat - mean(dhat) - rhat * mean(dhat * rhat)) * rstd, dhat = dout * gamma
+// dr = (dhat - mean(dhat) - rhat * mean(dhat * rhat)) * rstd, dhat = dout * gamma.
+// Fused variant: the workgroup also accumulates its rows' contributions to the
+// gain and shift gradients (sum dout*rhat, sum dout) and writes one partial row
+// per workgroup; lane-owned columns stay in registers across rows.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, int H, int rows_per_block,
+                                                                  const T* __restrict__ dout, const T* __restrict__ r,
+                                                                  const float* __restrict__ stats,
+                                                                  const T* __restrict__ gamma,
+                                                                  const T* __restrict__ add, T* __restrict__ dr,
+                                                                  float* __restrict__ pg, float* __restrict__ pb) {
+  constexpr int V = Vec<T>::N;
+  extern __shared__ float red[];                 // [4][H]
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int nvec = H / V;
+  float g[NCH][V], ag[NCH][V], ab[NCH][V];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane + 64 * j;
+#pragma unroll
+    for (int i = 0; i < V; ++i) { g[j][i] = 0.f; ag[j][i] = 0.f; ab[j][i] = 0.f; }
+    if (c < nvec) Vec<T>::load(gamma + c * V, g[j]);
+  }
+  const int row_end = min(T_rows, (int)(blockIdx.x + 1) * rows_per_block);
+  for (int row = blockIdx.x * rows_per_block + w; row < row_end; row += 4) {
+    const long off = (long)row * H;
+    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
+    float d[NCH][V], xh[NCH][V];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float x[V];
+        Vec<T>::load(dout + off + c * V, d[j]);
+        Vec<T>::load(r + off + c * V, x);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          xh[j][i] = (x[i] - mean) * rstd;
+          ag[j][i] += d[j][i] * xh[j][i];
+          ab[j][i] += d[j][i];
+          d[j][i] *= g[j][i];                      // dhat
+          s1 += d[j][i];
+          s2 += d[j][i] * xh[j][i];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)H;
+    const float m2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+        float o[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = (d[j][i] - m1 - xh[j][i] * m2) * rstd;
+        if (add != nullptr) {
+          float a[V];
+          Vec<T>::load(add + off + c * V, a);
+#pragma unroll
+          for (int i = 0; i < V; ++i) o[i] += a[i];
+        }
+        Vec<T>::store(dr + off + c * V, o);
+      }
+    }
+  }
+  // ordered reduction of the four wavefronts, gain gradient then shift gradient
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = lane + 64 * j;
+      if (c < nvec) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) red[w * H + c * V + i] = which == 0 ? ag[j][i] : ab[j][i];
+      }
+    }
+    __syncthreads();
+    float* out = (which == 0 ? pg : pb) + (long)blockIdx.x * H;
+    for (int c = threadIdx.x; c < H; c += 256) out[c] = ((red[c] + red[H + c]) + red[2 * H + c]) + red[3 * H + c];
+  }
+}
+
+// dr only (any row length); gain/shift gradients come from colreduce_kernel<.,1>
 template <typename T>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(int T_rows, int H, const T* __restrict__ dout,
                                                             const T* __restrict__ r, const float* __restrict__ stats,
@@ -135,107 +286,168 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(int T_rows, int H, c
 }
 
 // ------------------------------------------------------------ column reductions
-// MODE 0: p0[y][c] = sum over the block's rows of a[t,c]
+// A workgroup covers 64*V columns (one 16-byte vector per lane) and a contiguous
+// range of rows, interleaved over its four wavefronts.
+// MODE 0: p0[y][c] = sum a[t,c]
 // MODE 1: p0 = sum a[t,c] * rhat[t,c] (gain gradient), p1 = sum a[t,c] (shift gradient)
-constexpr int kRowSplits = 32;
-
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void colreduce_kernel(int T_rows, int N, const T* __restrict__ a,
-                                                        const T* __restrict__ r, const float* __restrict__ stats,
-                                                        float* __restrict__ p0, float* __restrict__ p1) {
-  __shared__ float red[4][2][128];
+__global__ __launch_bounds__(256) void colreduce_kernel(int T_rows, int N, int rows_per_block,
+                                                        const T* __restrict__ a, const T* __restrict__ r,
+                                                        const float* __restrict__ stats, float* __restrict__ p0,
+                                                        float* __restrict__ p1) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[2][4][64 * V];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c = blockIdx.x * 128 + lane * 2;
-  float s0[2] = {0.f, 0.f}, s1[2] = {0.f, 0.f};
+  const int c = (blockIdx.x * 64 + lane) * V;
+  float s0[V], s1[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
   if (c < N) {
-    for (int t = blockIdx.y * 4 + w; t < T_rows; t += gridDim.y * 4) {
-      const long i = (long)t * N + c;
-      const float a0 = to_f32<T>(a[i]), a1 = to_f32<T>(a[i + 1]);
+    const int row_end = min(T_rows, (int)(blockIdx.y + 1) * rows_per_block);
+#pragma unroll 4
+    for (int t = blockIdx.y * rows_per_block + w; t < row_end; t += 4) {
+      float v[V];
+      Vec<T>::load(a + (long)t * N + c, v);
       if (MODE == 0) {
-        s0[0] += a0;
-        s0[1] += a1;
+#pragma unroll
+        for (int i = 0; i < V; ++i) s0[i] += v[i];
       } else {
+        float x[V];
+        Vec<T>::load(r + (long)t * N + c, x);
         const float mean = stats[2 * t], rstd = stats[2 * t + 1];
-        s0[0] += a0 * ((to_f32<T>(r[i]) - mean) * rstd);
-        s0[1] += a1 * ((to_f32<T>(r[i + 1]) - mean) * rstd);
-        s1[0] += a0;
-        s1[1] += a1;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          s0[i] += v[i] * ((x[i] - mean) * rstd);
+          s1[i] += v[i];
+        }
       }
     }
   }
-  red[w][0][lane * 2] = s0[0];
-  red[w][0][lane * 2 + 1] = s0[1];
-  red[w][1][lane * 2] = s1[0];
-  red[w][1][lane * 2 + 1] = s1[1];
-  __syncthreads();
-  if (w == 0 && c < N) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int cc = lane * 2 + j;
-      p0[(long)blockIdx.y * N + c + j] = ((red[0][0][cc] + red[1][0][cc]) + red[2][0][cc]) + red[3][0][cc];
-      if (MODE == 1)
-        p1[(long)blockIdx.y * N + c + j] = ((red[0][1][cc] + red[1][1][cc]) + red[2][1][cc]) + red[3][1][cc];
+  for (int i = 0; i < V; ++i) {
+    red[0][w][lane * V + i] = s0[i];
+    if (MODE == 1) red[1][w][lane * V + i] = s1[i];
+  }
+  __syncthreads();
+  for (int j = threadIdx.x; j < 64 * V; j += 256) {
+    const int col = blockIdx.x * 64 * V + j;
+    if (col < N) {
+      p0[(long)blockIdx.y * N + col] = ((red[0][0][j] + red[0][1][j]) + red[0][2][j]) + red[0][3][j];
+      if (MODE == 1) p1[(long)blockIdx.y * N + col] = ((red[1][0][j] + red[1][1][j]) + red[1][2][j]) + red[1][3][j];
     }
   }
 }
 
-// out[c] += sum_y p[y][c] in the fixed order y = 0, 1, ...
-__global__ void colreduce_final_kernel(int N, int splits, const float* __restrict__ p0, float* __restrict__ out0,
-                                       const float* __restrict__ p1, float* __restrict__ out1) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= N) return;
-  float s = 0.f;
-  for (int y = 0; y < splits; ++y) s += p0[(long)y * N + c];
-  out0[c] += s;
-  if (p1 != nullptr) {
-    float q = 0.f;
-    for (int y = 0; y < splits; ++y) q += p1[(long)y * N + c];
-    out1[c] += q;
+// out[c] += sum_y p[y][c]: 16 wavefronts each sum a contiguous sixteenth of the
+// partial rows in order, then the sixteen sums are added in order.
+constexpr int kFinalWaves = 16;
+__global__ __launch_bounds__(1024) void colreduce_final_kernel(int N, int splits, const float* __restrict__ p0,
+                                                               float* __restrict__ out0,
+                                                               const float* __restrict__ p1,
+                                                               float* __restrict__ out1) {
+  __shared__ float red[2][kFinalWaves][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  const int per = (splits + kFinalWaves - 1) / kFinalWaves;
+  float s = 0.f, q = 0.f;
+  if (c < N) {
+    const int y_end = min(splits, (w + 1) * per);
+#pragma unroll 8
+    for (int y = w * per; y < y_end; ++y) s += p0[(long)y * N + c];
+    if (p1 != nullptr) {
+#pragma unroll 8
+      for (int y = w * per; y < y_end; ++y) q += p1[(long)y * N + c];
+    }
+  }
+  red[0][w][lane] = s;
+  red[1][w][lane] = q;
+  __syncthreads();
+  if (w == 0 && c < N) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int k = 0; k < kFinalWaves; ++k) {
+      a += red[0][k][lane];
+      b += red[1][k][lane];
+    }
+    out0[c] += a;
+    if (p1 != nullptr) out1[c] += b;
   }
 }
 
-static int row_splits(int T) {
-  int s = (T + 3) / 4;
-  return s < kRowSplits ? (s < 1 ? 1 : s) : kRowSplits;
+// rows per workgroup and number of workgroups along the token axis
+static void split_rows(int T, int max_blocks, int* rows_per_block, int* blocks) {
+  int rpb = (T + max_blocks - 1) / max_blocks;
+  if (rpb < 4) rpb = 4;
+  *rows_per_block = rpb;
+  *blocks = (T + rpb - 1) / rpb;
 }
-size_t colsum_partial_floats(int N) { return (size_t)kRowSplits * N; }
-size_t ln_bwd_partial_floats(int H) { return (size_t)2 * kRowSplits * H; }
+hipError_t launch_colsum_final(hipStream_t s, int N, int parts, const float* partial, float* out) {
+  hipLaunchKernelGGL(colreduce_final_kernel, dim3((N + 63) / 64), dim3(1024), 0, s, N, parts, partial, out,
+                     (const float*)nullptr, (float*)nullptr);
+  return hipGetLastError();
+}
+size_t colsum_partial_floats(int N) { return (size_t)kMaxPartials * N; }
+size_t ln_bwd_partial_floats(int H) { return (size_t)2 * kMaxPartials * H; }
+
+template <typename T>
+static hipError_t colsum_impl(hipStream_t s, int T_rows, int N, const void* a, float* out, float* partial) {
+  constexpr int V = Vec<T>::N;
+  const int col_blocks = (N + 64 * V - 1) / (64 * V);
+  int max_blocks = 512 / col_blocks;            // about two workgroups per CU in total
+  if (max_blocks > kMaxPartials) max_blocks = kMaxPartials;
+  if (max_blocks < 1) max_blocks = 1;
+  int rpb, rb;
+  split_rows(T_rows, max_blocks, &rpb, &rb);
+  hipLaunchKernelGGL((colreduce_kernel<T, 0>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, N, rpb, (const T*)a,
+                     (const T*)nullptr, (const float*)nullptr, partial, (float*)nullptr);
+  hipLaunchKernelGGL(colreduce_final_kernel, dim3((N + 63) / 64), dim3(1024), 0, s, N, rb, partial, out,
+                     (const float*)nullptr, (float*)nullptr);
+  return hipGetLastError();
+}
 
 hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial) {
-  const int rs = row_splits(T);
-  dim3 grid((N + 127) / 128, rs);
-  if (dtype == 0)
-    hipLaunchKernelGGL((colreduce_kernel<float, 0>), grid, dim3(256), 0, s, T, N, (const float*)a, (const float*)nullptr,
-                       (const float*)nullptr, partial, (float*)nullptr);
-  else
-    hipLaunchKernelGGL((colreduce_kernel<bf16_t, 0>), grid, dim3(256), 0, s, T, N, (const bf16_t*)a,
-                       (const bf16_t*)nullptr, (const float*)nullptr, partial, (float*)nullptr);
-  hipLaunchKernelGGL(colreduce_final_kernel, dim3((N + 255) / 256), dim3(256), 0, s, N, rs, partial, out,
-                     (const float*)nullptr, (float*)nullptr);
+  return dtype == 0 ? colsum_impl<float>(s, T, N, a, out, partial) : colsum_impl<bf16_t>(s, T, N, a, out, partial);
+}
+
+template <typename T>
+static hipError_t ln_bwd_impl(hipStream_t s, int T_rows, int H, const void* dout, const void* r, const float* stats,
+                              const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta,
+                              float* partial) {
+  constexpr int V = Vec<T>::N;
+  float* p0 = partial;
+  float* p1 = partial + (size_t)kMaxPartials * H;
+  const int nch = (H / V + 63) / 64;
+  int rpb, rb;
+  if (nch <= 4 && (size_t)4 * H * sizeof(float) <= 48 * 1024) {
+    split_rows(T_rows, kMaxPartials, &rpb, &rb);
+    const size_t sh = (size_t)4 * H * sizeof(float);
+#define LN_BWD(K)                                                                                                  \
+  hipLaunchKernelGGL(K, dim3(rb), dim3(256), sh, s, T_rows, H, rpb, (const T*)dout, (const T*)r, stats,          \
+                     (const T*)gamma, (const T*)add, (T*)dr, p0, p1)
+    if (nch <= 1) LN_BWD((layernorm_bwd_fused_kernel<T, 1>));
+    else if (nch <= 2) LN_BWD((layernorm_bwd_fused_kernel<T, 2>));
+    else LN_BWD((layernorm_bwd_fused_kernel<T, 4>));
+#undef LN_BWD
+  } else {
+    const int col_blocks = (H + 64 * V - 1) / (64 * V);
+    int max_blocks = 512 / col_blocks;
+    if (max_blocks > kMaxPartials) max_blocks = kMaxPartials;
+    if (max_blocks < 1) max_blocks = 1;
+    split_rows(T_rows, max_blocks, &rpb, &rb);
+    hipLaunchKernelGGL((colreduce_kernel<T, 1>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, H, rpb, (const T*)dout,
+                       (const T*)r, stats, p0, p1);
+    hipLaunchKernelGGL(layernorm_bwd_kernel<T>, dim3((T_rows + 3) / 4), dim3(256), 0, s, T_rows, H, (const T*)dout,
+                       (const T*)r, stats, (const T*)gamma, (const T*)add, (T*)dr);
+  }
+  hipLaunchKernelGGL(colreduce_final_kernel, dim3((H + 63) / 64), dim3(1024), 0, s, H, rb, p0, dgamma, p1, dbeta);
   return hipGetLastError();
 }
 
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const void* dout, const void* r,
                                 const float* stats, const void* gamma, const void* add, void* dr, float* dgamma,
                                 float* dbeta, float* partial) {
-  const int rs = row_splits(T);
-  dim3 grid((T + 3) / 4);
-  dim3 cgrid((H + 127) / 128, rs);
-  float* p0 = partial;
-  float* p1 = partial + (size_t)kRowSplits * H;
-  if (dtype == 0) {
-    hipLaunchKernelGGL((colreduce_kernel<float, 1>), cgrid, dim3(256), 0, s, T, H, (const float*)dout, (const float*)r,
-                       stats, p0, p1);
-    hipLaunchKernelGGL(layernorm_bwd_kernel<float>, grid, dim3(256), 0, s, T, H, (const float*)dout, (const float*)r,
-                       stats, (const float*)gamma, (const float*)add, (float*)dr);
-  } else {
-    hipLaunchKernelGGL((colreduce_kernel<bf16_t, 1>), cgrid, dim3(256), 0, s, T, H, (const bf16_t*)dout,
-                       (const bf16_t*)r, stats, p0, p1);
-    hipLaunchKernelGGL(layernorm_bwd_kernel<bf16_t>, grid, dim3(256), 0, s, T, H, (const bf16_t*)dout,
-                       (const bf16_t*)r, stats, (const bf16_t*)gamma, (const bf16_t*)add, (bf16_t*)dr);
-  }
-  hipLaunchKernelGGL(colreduce_final_kernel, dim3((H + 255) / 256), dim3(256), 0, s, H, rs, p0, dgamma, p1, dbeta);
-  return hipGetLastError();
+  return dtype == 0 ? ln_bwd_impl<float>(s, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial)
+                    : ln_bwd_impl<bf16_t>(s, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial);
 }
 
 // ------------------------------------------------------------------- bubble

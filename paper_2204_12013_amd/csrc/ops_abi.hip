@@ -55,12 +55,20 @@ int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY
 }
 
 int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X, const void* dY, float* dW,
-                         void* stream) {
+                         float* db, float* partial, void* stream) {
+  if (db != nullptr && partial == nullptr) return BAMBOO_E_ARG;
   GemmDesc d;
   memset(&d, 0, sizeof(d));
   d.A = X; d.B = dY; d.C = dW; d.M = K; d.N = N; d.K = T;
   d.a_sm = 1; d.a_sk = K; d.b_sk = N; d.b_sn = 1;
   d.epi = EPI_ACC_F32;
+  d.colsum_out = db; d.colsum_partial = partial;
+  if (impl != 0 && db != nullptr) {   // a forced kernel bypasses launch_gemm: the column sum is launched here
+    (void)hipGetLastError();
+    const int rc = finish(launch_colsum_acc((hipStream_t)stream, dtype, T, N, dY, db, partial));
+    if (rc != BAMBOO_OK) return rc;
+    d.colsum_out = nullptr;
+  }
   return run_gemm(dtype, impl, d, stream);
 }
 

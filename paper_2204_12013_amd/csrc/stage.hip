@@ -267,11 +267,13 @@ GemmDesc gemm_nt(const void* dY, const void* W, void* dX, int T, int Kw, int Nw,
   return d;
 }
 // dW[Kw,Nw] += X[T,Kw]^T * dY[T,Nw]
-GemmDesc gemm_tn(const void* X, const void* dY, float* dW, int T, int Kw, int Nw) {
+// and, in the same pass over dY, db[Nw] += column sums of dY
+GemmDesc gemm_tn(const void* X, const void* dY, float* dW, float* db, float* partial, int T, int Kw, int Nw) {
   GemmDesc d;
   memset(&d, 0, sizeof(d));
   d.A = X; d.B = dY; d.C = dW; d.M = Kw; d.N = Nw; d.K = T;
   d.a_sm = 1; d.a_sk = Kw; d.b_sk = Nw; d.b_sn = 1; d.epi = EPI_ACC_F32;
+  d.colsum_out = db; d.colsum_partial = partial;
   return d;
 }
 
@@ -379,16 +381,14 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     } else {
       df = dy;
     }
-    // f = g W2 + b2
-    BBCHK(p_colsum(st, s, T, H, df, G + st->po.b2, partial));
+    // f = g W2 + b2 (the bias gradients ride along with the weight-gradient GEMMs)
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_DGELU);
     d.aux_in = rec + r.h;
     d.aux_out = gbuf;
     BBCHK(p_gemm(st, s, d));
-    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
+    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, G + st->po.b2, partial, T, F, H)));
     // h = fin W1 + b1
-    BBCHK(p_colsum(st, s, T, F, dh, G + st->po.b1, partial));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, G + st->po.b1, partial, T, H, F)));
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
@@ -404,13 +404,11 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
       da = d2;
     }
     // a = ctx Wo + bo
-    BBCHK(p_colsum(st, s, T, H, da, G + st->po.bo, partial));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, G + st->po.bo, partial, T, H, H)));
     BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
     BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
-    BBCHK(p_colsum(st, s, T, 3 * H, dqkv, G + st->po.bqkv, partial));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, G + st->po.bqkv, partial, T, H, 3 * H)));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
       d.res = da;

@@ -98,10 +98,14 @@ def test_linear_backward_variants(B, dtype, impl, T, N, K):
     # weight gradient accumulates into fp32
     dW0 = rng.standard_normal((K, N)).astype(np.float32)
     dW = torch.from_numpy(dW0.copy()).to(DEV)
+    db0 = rng.standard_normal(N).astype(np.float32)
+    db = torch.from_numpy(db0.copy()).to(DEV)
     B.bk_linear_bwd_weight(_dev(B, X, dtype), _dev(B, dY, dtype), dW, impl=impl)
-    B.bk_linear_bwd_weight(_dev(B, X, dtype), _dev(B, dY, dtype), dW, impl=impl)
+    B.bk_linear_bwd_weight(_dev(B, X, dtype), _dev(B, dY, dtype), dW, db=db, impl=impl)
     want = 2 * (X.astype(np.float64).T @ dY.astype(np.float64))
     assert rel_l2(dW.cpu().numpy().astype(np.float64) - dW0, want) <= TOL[dtype]
+    # the bias gradient of the same linear layer
+    assert rel_l2(db.cpu().numpy().astype(np.float64) - db0, dY.astype(np.float64).sum(0)) <= 1e-4
 
 
 @pytest.mark.parametrize("dtype", [0, 1])
