@@ -33,6 +33,19 @@ def _iteration_flops(sc, frc):
     return sc.M * (sc.n_own * (fwd + bwd) + (sc.n_shadow * fwd if frc else 0.0))
 
 
+def _profiled_traffic(workload):
+    """HBM bytes per stage-GEMM launch from the committed rocprofv3 counter summary
+    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel yardstick), or None."""
+    path = os.path.join(ROOT, "profiles", "%s_pmc_traffic.txt" % workload)
+    try:
+        for line in open(path):
+            if line.startswith("stage_gemm_traffic_bytes_per_launch="):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def _cpu_baseline(sc, seconds_hint=20.0):
     """The oracle as it stands, timed on the host: one layer forward + backward
     for one micro-batch of this workload, extrapolated linearly to an iteration
@@ -73,6 +86,8 @@ def main():
     ap.add_argument("--no-extra-modes", action="store_true", help="time mode B only (for profiler runs)")
     ap.add_argument("--profile-frc-off", action="store_true",
                     help="run the per-kernel-class pass without FRC (one lane: kernel times free of contention)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one 256 MiB device copy (yardstick for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one stage on ONE GPU; --gpus %d is not supported (no collectives, no second "
@@ -177,7 +192,7 @@ def main():
     achieved = g_work / (g_ms * 1e-3) / 1e12
     out["roofline"] = {"kernel": "stage GEMMs (forward, input-gradient, weight-gradient launches)", "bound": "mfma",
                        "achieved": achieved, "peak": PEAK["mfma_bf16"] / 1e12, "unit": "TFLOP/s",
-                       "frac": achieved * 1e12 / PEAK["mfma_bf16"], "traffic": None,
+                       "frac": achieved * 1e12 / PEAK["mfma_bf16"], "traffic": _profiled_traffic(sc.name),
                        "launches_per_step": g_n // k_p, "avg_launch_us": g_ms * 1e3 / g_n,
                        "flops_per_launch": g_work / g_n}
     out["mfma_util_stage_gemms"] = out["roofline"]["frac"]
@@ -186,6 +201,14 @@ def main():
             ("TFLOP/s" if k.startswith(("gemm", "attn")) else "GB/s"):
                 v["rate"] / (1e12 if k.startswith(("gemm", "attn")) else 1e9)}
         for k, v in classes.items()}
+    if args.calibration_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        a.fill_(1)
+        torch.cuda.synchronize()
+        B.bk_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
     st.stage_destroy()
     del st, hz
     torch.cuda.empty_cache()

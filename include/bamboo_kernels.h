@@ -67,6 +67,11 @@ int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, c
                      const void* add, void* dr, float* dgamma, float* dbeta, float* partial, void* stream);
 uint64_t bk_layernorm_bwd_scratch_floats(int H);
 
+/* Measurement aid (not part of the method): plain device copy of `bytes` bytes
+ * (multiple of 16, 16-byte aligned pointers).  Its known traffic calibrates the
+ * HBM byte counters read for the other kernels. */
+int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,6 +79,7 @@ _SIGS = {
     "bk_layernorm_fwd": (C.c_int, [C.c_int] * 3 + [_f32] + [_vp] * 6),
     "bk_layernorm_bwd": (C.c_int, [C.c_int] * 3 + [_vp] * 10),
     "bk_layernorm_bwd_scratch_floats": (C.c_uint64, [C.c_int]),
+    "bk_copy": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -312,6 +313,11 @@ def bk_layernorm_bwd(dout, r, stats, gamma, dr, dgamma, dbeta, add=None, stream=
     _check(lib.bk_layernorm_bwd(_dt(r), T, H, _ptr(dout), _ptr(r), _ptr(stats), _ptr(gamma), _ptr(add), _ptr(dr),
                                 _ptr(dgamma), _ptr(dbeta), _ptr(partial), _stream(stream)), "bk_layernorm_bwd")
     return partial
+
+
+def bk_copy(src, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(lib.bk_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "bk_copy")
 
 
 # ---- numpy <-> device helpers (storage conversion only) ------------------------

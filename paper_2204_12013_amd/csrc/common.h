@@ -130,5 +130,6 @@ hipError_t launch_colsum_final(hipStream_t s, int N, int parts, const float* par
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);
+hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 
 }  // namespace bamboo

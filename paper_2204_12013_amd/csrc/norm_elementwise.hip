@@ -450,6 +450,21 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const vo
                     : ln_bwd_impl<bf16_t>(s, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial);
 }
 
+// --------------------------------------------------------------------- copy
+// Plain 16-byte-per-lane copy of a known size: the yardstick that the HBM
+// traffic counters of the other kernels are scaled by.
+__global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, long n16) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256) dst[i] = src[i];
+}
+hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  const long n16 = (long)(bytes / 16);
+  if (n16 == 0) return hipSuccess;
+  long blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float4*)src, (float4*)dst, n16);
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------- bubble
 // One wavefront waits on the constant-rate device clock.  The wait always ends:
 // the clock advances on its own, and an iteration cap bounds it regardless.

@@ -133,4 +133,10 @@ int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, c
 }
 uint64_t bk_layernorm_bwd_scratch_floats(int H) { return ln_bwd_partial_floats(H); }
 
+int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
+  if (!src || !dst || bytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_copy((hipStream_t)stream, src, dst, (size_t)bytes));
+}
+
 }  // extern "C"
