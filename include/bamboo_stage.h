@@ -145,6 +145,19 @@ int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr
  * on a bad index. */
 int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot, int32_t layer);
 
+/* Byte offsets of the tensors inside one stash record (everything the backward
+ * of one layer needs for one micro-batch), so that a caller can inspect the stash:
+ * out[0] x      layer input [T,H]
+ * out[1] ain    attention input [T,H] (pre-LN: LN1(x); post-LN: same offset as x)
+ * out[2] qkv    [T,3H]      out[3] ctx [T,H] (attention output before Wo)
+ * out[4] r1     x + attention block [T,H]
+ * out[5] fin    FFN input [T,H] (post-LN: LN1(r1); pre-LN: LN2(r1))
+ * out[6] h      FFN pre-activation [T,F]
+ * out[7] r2     post-LN only: fin + ffn [T,H] (0 otherwise)
+ * out[8] lse    fp32 [batch,heads,seq]   out[9], out[10] LN1, LN2 (mean, rstd) fp32 [T,2]
+ * out[11] rec_bytes.  Activations are in the storage dtype.  host pointers. */
+int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[12]);
+
 const char* stage_strerror(int status);
 
 /* ---- stage object --------------------------------------------------------- */

@@ -55,6 +55,7 @@ _SIGS = {
     "stage_failover_program": (C.c_int, [_cfgp, _i32, _insp, _i32]),
     "stage_record_offset": (_i64, [_cfgp, _i32, _i32, _i32]),
     "stage_strerror": (C.c_char_p, [C.c_int]),
+    "stage_record_fields": (C.c_int, [_cfgp, C.POINTER(C.c_uint64)]),
     "stage_init": (C.c_int, [_cfgp, _szp] + [_vp] * 9 + [C.POINTER(_vp)]),
     "stage_schedule": (C.c_int, [_vp, _insp, _i32]),
     "stage_begin_iteration": (C.c_int, [_vp]),
@@ -131,6 +132,15 @@ def stage_record_offset(cfg, kind, slot, layer):
     return _check(lib.stage_record_offset(C.byref(cfg), kind, slot, layer), "stage_record_offset")
 
 
+RECORD_FIELDS = ("x", "ain", "qkv", "ctx", "r1", "fin", "h", "r2", "lse", "ln1", "ln2", "rec_bytes")
+
+
+def stage_record_fields(cfg):
+    arr = (C.c_uint64 * 12)()
+    _check(lib.stage_record_fields(C.byref(cfg), arr), "stage_record_fields")
+    return dict(zip(RECORD_FIELDS, [int(v) for v in arr]))
+
+
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
 
@@ -171,6 +181,21 @@ class Stage:
                               _ptr(self.shadow_stash) if cfg.n_shadow > 0 else None, _ptr(self.workspace),
                               C.c_void_p(self.stream_main.cuda_stream), C.c_void_p(self.stream_frc.cuda_stream),
                               C.byref(self._h)), "stage_init")
+
+    def stash_tensor(self, kind, slot, layer, field):
+        """View of one tensor of a stash record (kind 0 own, 1 shadow)."""
+        torch = self.torch
+        cfg = self.cfg
+        f = stage_record_fields(cfg)
+        base = stage_record_offset(cfg, kind, slot, layer) + f[field]
+        arena = self.own_stash if kind == 0 else self.shadow_stash
+        T, H, F = self.T, cfg.hidden, cfg.ffn
+        es = 2 if cfg.dtype == 1 else 4
+        if field in ("lse", "ln1", "ln2"):
+            n = cfg.micro_batch * cfg.heads * cfg.seq if field == "lse" else 2 * T
+            return arena[base:base + 4 * n].view(torch.float32)
+        cols = {"qkv": 3 * H, "h": F}.get(field, H)
+        return arena[base:base + es * T * cols].view(self.act_dtype).view(T, cols)
 
     def new_act(self):
         return self.torch.empty(self.T, self.H, dtype=self.act_dtype, device=self.device)

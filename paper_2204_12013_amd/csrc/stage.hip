@@ -500,6 +500,16 @@ int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot,
   return (int64_t)(((uint64_t)slot * n + layer) * sz.rec_bytes);
 }
 
+int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[12]) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (!out) return BAMBOO_E_ARG;
+  const RecordLayout r = record_layout(*cfg);
+  const uint64_t f[12] = {r.x, r.ain, r.qkv, r.ctx, r.r1, r.fin, r.h, r.r2, r.lse, r.ln1, r.ln2, r.bytes};
+  memcpy(out, f, sizeof(f));
+  return BAMBOO_OK;
+}
+
 int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void* own_w, const void* shadow_w,
                void* own_g, void* shadow_g, void* own_stash, void* shadow_stash, void* workspace, void* stream_main,
                void* stream_frc, bamboo_stage_t** out) {

@@ -1,0 +1,217 @@
+"""Parity at the full sizes of the workload table, in the launch configuration
+bench.py times (GPU only).
+
+* BERT-large- and GPT-2-shaped stages: micro-batch 0 through all own and replica
+  layers against the full oracle (outputs, input gradients, every parameter
+  gradient tensor), plus the paper's invariants over the iteration, bitwise.
+* Large-layer stage (hidden 12288): the oracle cannot run a whole layer in
+  reasonable time, so every step of layer 0 is checked on sampled rows / heads
+  with the oracle fed the GPU's own layer inputs from the stash, and the
+  invariants are checked bitwise.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer as L
+from oracle import schedule as S
+from paper_2204_12013_amd import synth
+from util import TOL, check_grads, oracle_layers, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2204_12013_amd import binding
+    return binding
+
+
+def _stages(B, sc, inp):
+    st = B.Stage(B.make_cfg(sc), B.to_device(inp["own_w"].reshape(-1), sc.dtype),
+                 B.to_device(inp["shadow_w"].reshape(-1), sc.dtype))
+    scs = sc.replace(n_own=sc.n_shadow, n_shadow=0, stage_id=sc.stage_id + 1)
+    succ = B.Stage(B.make_cfg(scs, frc_enabled=False), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype), None)
+    return st, succ
+
+
+@pytest.mark.parametrize("name", ["bert_large_stage", "gpt2_1p5b_stage"])
+def test_microbatch0_matches_oracle_at_full_size(B, name):
+    sc = synth.CONFIGS[name]
+    tol = TOL[sc.dtype]
+    inp = synth.make_stage_inputs(sc, n_microbatches=1)
+    st, succ = _stages(B, sc, inp)
+    x = B.to_device(inp["x"][0], sc.dtype)
+    gz = B.to_device(inp["gz"][0], sc.dtype)
+    y, z, zs, gy, gx = (st.new_act() for _ in range(5))
+    torch.cuda.synchronize()
+    st.stage_begin_iteration()
+    succ.stage_begin_iteration()
+    st.zero_grads()
+    succ.zero_grads()
+    st.stage_fwd(0, x, y)
+    st.shadow_fwd_frc(0, y, z)
+    succ.stream_main.wait_stream(st.stream_main)
+    succ.stage_fwd(0, y, zs)
+    succ.stage_bwd(0, gz, gy)
+    st.stream_main.wait_stream(succ.stream_main)
+    st.stage_bwd(0, gy, gx)
+    st.stage_sync()
+    succ.stage_sync()
+    assert torch.equal(z, zs)                                   # FRC == successor's forward, bitwise
+
+    own = oracle_layers(inp["own_w"], sc.hidden, sc.ffn)
+    shadow = oracle_layers(inp["shadow_w"], sc.hidden, sc.ffn)
+    args = (sc.micro_batch, sc.seq, sc.heads)
+    y_ref, c_own = L.stack_fwd(sc.arch, own, inp["x"][0].astype(np.float64), *args)
+    z_ref, c_sh = L.stack_fwd(sc.arch, shadow, y_ref, *args)
+    gy_ref, g_sh = L.stack_bwd(sc.arch, shadow, c_sh, inp["gz"][0].astype(np.float64))
+    del c_sh
+    gx_ref, g_own = L.stack_bwd(sc.arch, own, c_own, gy_ref)
+    del c_own
+    assert rel_l2(B.to_host(y), y_ref) <= tol
+    assert rel_l2(B.to_host(z), z_ref) <= tol
+    assert rel_l2(B.to_host(gy), gy_ref) <= tol
+    assert rel_l2(B.to_host(gx), gx_ref) <= tol
+    check_grads(st.own_g.cpu().numpy(), g_own, sc.hidden, sc.ffn, tol, "own")
+    check_grads(succ.own_g.cpu().numpy(), g_sh, sc.hidden, sc.ffn, tol, "successor")
+    st.stage_destroy()
+    succ.stage_destroy()
+
+
+def _device_inputs(B, sc, seed):
+    """Inputs of the workload's distributions drawn on the device (the invariant
+    tests compare GPU results with GPU results, so no host copy is needed)."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    act = torch.bfloat16 if sc.dtype == 1 else torch.float32
+
+    def stack(n):
+        parts = []
+        for _ in range(n):
+            for nm in synth.PARAM_NAMES:
+                numel = int(np.prod(synth.param_shapes(sc.hidden, sc.ffn)[nm]))
+                v = torch.randn(numel, generator=gen, device=DEV) * 0.02
+                if nm in ("g1", "g2"):
+                    v += 1.0
+                parts.append(v.to(act))
+        return torch.cat(parts)
+    T, H = sc.tokens, sc.hidden
+    own, shadow = stack(sc.n_own), stack(sc.n_shadow)
+    x = [torch.randn(T, H, generator=gen, device=DEV).to(act) for _ in range(sc.M)]
+    gz = [(torch.randn(T, H, generator=gen, device=DEV) / (T * H) ** 0.5).to(act) for _ in range(sc.M)]
+    return own, shadow, x, gz
+
+
+def _run(B, sc, own, shadow, x, gz, k_fail=None):
+    from paper_2204_12013_amd.harness import StageHarness, split_at_failure
+    st = B.Stage(B.make_cfg(sc), own, shadow)
+    scs = sc.replace(n_own=sc.n_shadow, n_shadow=0, stage_id=sc.stage_id + 1)
+    succ = B.Stage(B.make_cfg(scs, frc_enabled=False), shadow, None)
+    torch.cuda.synchronize()
+    hz = StageHarness(st, x, gz, successor=succ)
+    hz.begin_iteration()
+    prog = st.stage_schedule()
+    assert prog == S.stage_program(sc.P, sc.stage_id, sc.M)
+    if k_fail is None:
+        hz.run(prog)
+    else:
+        hz.run(split_at_failure(prog, k_fail))
+        succ.stage_sync()
+        succ.own_g.zero_()                         # the victim's gradients are gone
+        merged = st.failover_merge(k_fail)
+        assert merged == S.failover_program(sc.P, sc.stage_id, sc.M, k_fail)
+        hz.run(merged)
+    hz.sync()
+    return st, succ, hz
+
+
+@pytest.mark.parametrize("name,k_fail", [("bert_large_stage", synth.FAILOVER_K), ("large_layer_stage", 7)])
+def test_invariants_over_the_iteration_at_full_size(B, name, k_fail):
+    """FRC(k) == successor forward(k) for every micro-batch, and after the
+    successor is lost at k_fail the iteration still ends with the failure-free
+    gradients (own, replica/successor, every g_x) -- all bitwise."""
+    sc = synth.CONFIGS[name]
+    own, shadow, x, gz = _device_inputs(B, sc, sc.seed)
+    st0, succ0, hz0 = _run(B, sc, own, shadow, x, gz)
+    for k in range(sc.M):
+        assert torch.equal(hz0.z_frc[k], hz0.z_succ[k]), k
+        assert bool(torch.isfinite(hz0.gx[k].float()).all())
+    own_g0, succ_g0 = st0.own_g.clone(), succ0.own_g.clone()
+    gx0 = [g.clone() for g in hz0.gx]
+    assert float(own_g0.abs().max()) > 0 and float(succ_g0.abs().max()) > 0
+    for s_ in (st0, succ0):
+        s_.stage_destroy()
+    del st0, succ0, hz0
+    torch.cuda.empty_cache()
+    st, succ, hz = _run(B, sc, own, shadow, x, gz, k_fail=k_fail)
+    assert torch.equal(st.own_g, own_g0)
+    assert torch.equal(st.shadow_g, succ_g0)
+    for k in range(sc.M):
+        assert torch.equal(hz.gx[k], gx0[k]), k
+    for s_ in (st, succ):
+        s_.stage_destroy()
+
+
+def test_large_layer_stage_steps_match_oracle_on_samples(B):
+    """hidden 12288, 96 heads of 128, FFN 49152, seq 2048: one forward + backward
+    of layer 0 at full size; each step checked on sampled rows / heads with the
+    oracle fed the GPU's own inputs to that step (read back from the stash)."""
+    sc = synth.CONFIGS["large_layer_stage"].replace(n_own=1, n_shadow=0, M=1)
+    tol = TOL[sc.dtype]
+    H, F, T, S_, nh = sc.hidden, sc.ffn, sc.tokens, sc.seq, sc.heads
+    d = H // nh
+    inp = synth.make_stage_inputs(sc, n_microbatches=1)
+    p = L.unpack_layer(inp["own_w"][0].astype(np.float64), H, F)
+    st = B.Stage(B.make_cfg(sc), B.to_device(inp["own_w"].reshape(-1), sc.dtype), None)
+    x = B.to_device(inp["x"][0], sc.dtype)
+    gy = B.to_device(inp["gz"][0], sc.dtype)
+    y, gx = st.new_act(), st.new_act()
+    torch.cuda.synchronize()
+    st.stage_begin_iteration()
+    st.zero_grads()
+    st.stage_fwd(0, x, y)
+    st.stage_sync()
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(T, 48, replace=False))
+    rec = {f: st.stash_tensor(0, 0, 0, f) for f in ("x", "ain", "qkv", "ctx", "r1", "fin", "h", "lse", "ln1", "ln2")}
+    host = lambda t, r=rows: t[torch.from_numpy(r).to(DEV)].float().cpu().numpy().astype(np.float64)
+    # pre-LN: u = LN1(x)
+    u_ref, _ = L.layernorm_fwd(host(rec["x"]), p["g1"], p["be1"], 1e-5)
+    assert rel_l2(host(rec["ain"]), u_ref) <= tol
+    # qkv = u Wqkv + b
+    assert rel_l2(host(rec["qkv"]), host(rec["ain"]) @ p["Wqkv"] + p["bqkv"]) <= tol
+    # attention for three sampled heads, from the GPU's own qkv
+    qkv_all = rec["qkv"].float().cpu().numpy().astype(np.float64)
+    ctx_all = rec["ctx"].float().cpu().numpy().astype(np.float64)
+    for h in (0, 41, nh - 1):
+        sub = np.concatenate([qkv_all[:, h * d:(h + 1) * d], qkv_all[:, H + h * d:H + (h + 1) * d],
+                              qkv_all[:, 2 * H + h * d:2 * H + (h + 1) * d]], axis=1)
+        ctx_ref, _ = L.attention_fwd(sub, sc.micro_batch, S_, 1, causal=True)
+        assert rel_l2(ctx_all[:, h * d:(h + 1) * d], ctx_ref) <= tol, h
+    # x1 = x + ctx Wo + bo ; v = LN2(x1) ; h = v W1 + b1 ; y = x1 + gelu(h) W2 + b2
+    assert rel_l2(host(rec["r1"]), host(rec["x"]) + host(rec["ctx"]) @ p["Wo"] + p["bo"]) <= tol
+    v_ref, _ = L.layernorm_fwd(host(rec["r1"]), p["g2"], p["be2"], 1e-5)
+    assert rel_l2(host(rec["fin"]), v_ref) <= tol
+    assert rel_l2(host(rec["h"]), host(rec["fin"]) @ p["W1"] + p["b1"]) <= tol
+    assert rel_l2(host(y), host(rec["r1"]) + L.gelu(host(rec["h"])) @ p["W2"] + p["b2"]) <= tol
+    # backward: the gradients that have closed forms in terms of stashed tensors
+    st.stage_bwd(0, gy, gx)
+    st.stage_sync()
+    off = synth.param_offsets(H, F)
+    G = st.own_g
+
+    def grad(name, row_idx=None):
+        o, shp = off[name]
+        t = G[o:o + int(np.prod(shp))].view(*shp)
+        if row_idx is not None:
+            t = t[torch.from_numpy(row_idx).to(DEV)]
+        return t.cpu().numpy().astype(np.float64)
+    dy = inp["gz"][0].astype(np.float64)
+    assert rel_l2(grad("b2"), dy.sum(0)) <= 1e-3
+    frows = np.sort(rng.choice(F, 32, replace=False))
+    g_cols = L.gelu(rec["h"][:, torch.from_numpy(frows).to(DEV)].float().cpu().numpy().astype(np.float64))
+    assert rel_l2(grad("W2", frows), g_cols.T @ dy) <= tol          # dW2 = gelu(h)^T dy
+    assert bool(torch.isfinite(gx.float()).all()) and bool(torch.isfinite(G).all())
+    st.stage_destroy()
