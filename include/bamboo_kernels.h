@@ -72,6 +72,13 @@ uint64_t bk_layernorm_bwd_scratch_floats(int H);
  * HBM byte counters read for the other kernels. */
 int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream);
 
+/* Tuning and test aid (not part of the method): choose the output tile of the MFMA
+ * GEMM kernel for all later calls in this process.  code = 10*WM + WN selects a
+ * (64*WM) x (64*WN) tile, one of 44, 42, 24, 22, 11; 0 restores the automatic
+ * choice.  Returns the previous code, or BAMBOO_E_ARG for a code that is not
+ * offered.  Not thread-safe against concurrent launches. */
+int bk_gemm_tile(int code);
+
 #ifdef __cplusplus
 }
 #endif

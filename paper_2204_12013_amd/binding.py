@@ -81,6 +81,7 @@ _SIGS = {
     "bk_layernorm_bwd": (C.c_int, [C.c_int] * 3 + [_vp] * 10),
     "bk_layernorm_bwd_scratch_floats": (C.c_uint64, [C.c_int]),
     "bk_copy": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
+    "bk_gemm_tile": (C.c_int, [C.c_int]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -343,6 +344,11 @@ def bk_layernorm_bwd(dout, r, stats, gamma, dr, dgamma, dbeta, add=None, stream=
 def bk_copy(src, dst, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(lib.bk_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "bk_copy")
+
+
+def bk_gemm_tile(code):
+    """Force the MFMA GEMM output tile (10*WM + WN; 0 = automatic); returns the previous code."""
+    return _check(lib.bk_gemm_tile(code), "bk_gemm_tile")
 
 
 # ---- numpy <-> device helpers (storage conversion only) ------------------------

@@ -94,6 +94,9 @@ hipError_t launch_gemm_simple(hipStream_t s, int dtype, const GemmDesc& d);
 // bf16 MFMA path; returns hipErrorNotSupported when the shape is not covered.
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d);
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
+// output tile of the MFMA kernel: 10*WM + WN forces (64*WM) x (64*WN), 0 = automatic; returns the previous code
+bool gemm_tile_code_valid(int code);
+int set_gemm_tile(int code);
 
 // ---- attention ---------------------------------------------------------------
 // qkv [T,3H] (queries | keys | values), ctx [T,H], lse fp32 [B,heads,S]

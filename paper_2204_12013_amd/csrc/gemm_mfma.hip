@@ -6,9 +6,10 @@
 //   weight gradient  dW += X^T dY  A M-contiguous,  B N-contiguous
 //
 // A workgroup of 4 wavefronts (2 x 2) owns a (64*WM) x (64*WN) output tile and
-// walks K in slices of 64.  Each slice is copied global -> registers -> LDS with
-// 16-byte accesses, double-buffered so that the loads of slice i+1 are in flight
-// while slice i feeds the MFMAs.  Operands whose contraction index is contiguous
+// walks K in slices of 64, double-buffered in LDS.  The main kernel streams the
+// slices global -> LDS directly and runs a hand-ordered, software-pipelined loop
+// (see gemm_mfma_pl_kernel); a register-staged variant covers K that is not a
+// multiple of 64.  Operands whose contraction index is contiguous
 // in memory are kept as [row][k] in LDS and read with ds_read_b128; operands
 // whose contraction index is strided are kept in their memory order [k][row]
 // and read with the transposing LDS load (ds_read_b64_tr_b16), which hands each
@@ -132,76 +133,10 @@ __device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks)
 // readers apply the same XOR.  Out-of-range rows are clamped to a valid row (they
 // only feed output rows/columns that are never stored); K must be a multiple of
 // the 64-wide slice.
-// Written as inline assembly so that the compiler's wait-count insertion does
+// The load is inline assembly so that the compiler's wait-count insertion does
 // not see an LDS write that "may alias" every later LDS read and serialise the
-// copy with the MFMAs; the kernel waits for vmcnt(0) itself before the barrier
+// copy with the MFMAs; the kernel waits on vmcnt itself before the barrier
 // that publishes a slice.  M0 carries the wavefront-uniform LDS base.
-__device__ __forceinline__ void load16_to_lds(const bf16_t* src, bf16_t* lds_wave_base) {
-  const unsigned lds_addr =
-      __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)lds_wave_base);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :
-               : "s"(lds_addr), "v"(src)
-               : "memory", "m0");
-}
-// K-contiguous operand, ROWS x 64: LDS row r = 128 bytes, chunk c stored at position c ^ (r % 8).
-template <int ROWS>
-struct DlK {
-  static constexpr int ELEMS = ROWS * BK;
-  __device__ static __forceinline__ void issue(const bf16_t* g, long ld, int row0, int row_lim, int k0, bf16_t* s) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-#pragma unroll
-    for (int i = 0; i < ROWS / 32; ++i) {
-      const int c = i * 256 + wave * 64 + lane;
-      const int r = c >> 3, p = c & 7;
-      const int row = min(row0 + r, row_lim - 1);
-      load16_to_lds(g + (long)row * ld + k0 + ((p ^ (r & 7)) << 3), s + (i * 256 + wave * 64) * 8);
-    }
-  }
-  __device__ static __forceinline__ bf16x8 frag(const bf16_t* s, int row_base, int ks) {
-    const int l = threadIdx.x & 63;
-    const int r = row_base + (l & 31), kc = 2 * ks + (l >> 5);
-    return *(const bf16x8*)(s + r * BK + ((kc ^ (r & 7)) << 3));
-  }
-};
-// Row-contiguous operand, 64 k-rows x ROWS: chunk c of k-row k stored at position c ^ (2 * (k % 4)),
-// which spreads the four k-rows of a transposing read over distinct banks.
-template <int ROWS>
-struct DlMN {
-  static constexpr int ELEMS = ROWS * BK;
-  static constexpr int CPR = ROWS / 8;
-  __device__ static __forceinline__ void issue(const bf16_t* g, long ld, int row0, int row_lim, int k0, bf16_t* s) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-#pragma unroll
-    for (int i = 0; i < ROWS / 32; ++i) {
-      const int c = i * 256 + wave * 64 + lane;
-      const int kr = c / CPR, p = c % CPR;
-      const int col = min(row0 + ((p ^ (2 * (kr & 3))) << 3), row_lim - 8);
-      load16_to_lds(g + (long)(k0 + kr) * ld + col, s + (i * 256 + wave * 64) * 8);
-    }
-  }
-  __device__ static __forceinline__ bf16x8 frag(const bf16_t* s, int row_base, int ks) {
-    const int l = threadIdx.x & 63, i = l & 15;
-    const int col = row_base + ((l >> 4) & 1) * 16 + (i & 3) * 4;
-    const int k = ks * 16 + (l >> 5) * 8 + (i >> 2);
-    const bf16_t* p = s + k * ROWS + ((((col >> 3) ^ (2 * (k & 3)))) << 3) + (col & 7);
-    typedef __attribute__((address_space(3))) short4_t* lds_ptr;
-    union { short4_t s4[2]; bf16x8 b; } u;
-    u.s4[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-    u.s4[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ROWS));
-    return u.b;
-  }
-};
-
-template <int WM, int WN>
-struct SmemDl {
-  static constexpr int BM = 64 * WM, BN = 64 * WN;
-  static constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK, STAGE = A_ELEMS + B_ELEMS;
-  static constexpr int EPI_LD = 32 * WN + 4;
-  static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
-  static constexpr int MAIN_BYTES = 2 * STAGE * 2;
-  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
-};
 
 // ---- epilogue on 8 consecutive outputs of one row ---------------------------------------
 template <int EPI>
@@ -384,24 +319,201 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
 }
 
-// Same tiling with direct global -> LDS loads (K a multiple of 64).
-template <int WM, int WN, bool A_K, bool B_K, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_dl_kernel(GemmDesc d) {
-  typedef SmemDl<WM, WN> SM;
+// ---- software-pipelined kernel with direct global -> LDS loads (K a multiple of 64) ------
+// Per-thread address tables are set up once; inside the K loop a slice costs
+// one scalar pointer bump per operand.  The instruction order of the loop body
+// is fixed by hand (scheduling barriers between the groups):
+//   k-step s of a slice issues its MFMAs interleaved with the LDS reads of the
+//   fragments of k-step s+1 (two fragment register sets), so no MFMA waits on LDS;
+//   all LDS reads of a slice are complete after k-step 2, where the one
+//   workgroup barrier of the slice sits; k-step 3 then runs its MFMAs
+//   interleaved with the fragment reads of the next slice (other buffer) and
+//   with the global -> LDS loads of the slice after that (into the buffer just
+//   vacated), which therefore have a whole slice of MFMA time to land.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(3))) const bf16x8* lds_bf16x8_ptr;
+typedef __attribute__((address_space(3))) short4_t* lds_short4_ptr;
+
+__device__ __forceinline__ void gload_lds16(unsigned voff, const void* sbase, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(voff), "s"(sbase), "s"(lds_addr)
+               : "memory", "m0");
+}
+
+// K-contiguous operand, ROWS x 64 per slice; LDS row r = 128 bytes, 16-byte chunk c at position c ^ (r % 8).
+template <int ROWS>
+struct PlK {
+  static constexpr int NLOAD = ROWS / 32;
+  static constexpr int BYTES = ROWS * BK * 2;
+  // byte offsets of this thread's chunks relative to row row0, k 0 of the slice
+  __device__ static __forceinline__ void load_offsets(unsigned (&off)[NLOAD], long ld, int row0, int row_lim) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int r = i * 32 + (tid >> 3), p = tid & 7;
+      const int row = min(row0 + r, row_lim - 1) - row0;
+      off[i] = (unsigned)((long)row * ld * 2 + ((p ^ (r & 7)) << 4));
+    }
+  }
+  __device__ static __forceinline__ const char* base(const bf16_t* g, long ld, int row0) {
+    return (const char*)(g + (long)row0 * ld);
+  }
+  __device__ static __forceinline__ long slice_bytes(long ld) { return BK * 2; }
+  // fragment address table: entry ks = address (within the operand's LDS area) of block 0 for k-step ks
+  __device__ static __forceinline__ void frag_table(unsigned (&t)[4], int wave_row0) {
+    const int l = threadIdx.x & 63;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      t[ks] = (unsigned)((wave_row0 + (l & 31)) * (BK * 2) + (((2 * ks + (l >> 5)) ^ (l & 7)) << 4));
+  }
+  __device__ static __forceinline__ bf16x8 frag(const unsigned (&t)[4], unsigned lds_base, int blk, int ks) {
+    return *(lds_bf16x8_ptr)(lds_base + t[ks] + blk * 32 * BK * 2);
+  }
+};
+// Row-contiguous operand, 64 k-rows x ROWS per slice; chunk c of k-row k at position c ^ (2 * (k % 4)).
+template <int ROWS>
+struct PlMN {
+  static constexpr int NLOAD = ROWS / 32;
+  static constexpr int BYTES = ROWS * BK * 2;
+  static constexpr int CPR = ROWS / 8;
+  __device__ static __forceinline__ void load_offsets(unsigned (&off)[NLOAD], long ld, int row0, int row_lim) {
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int c = i * 256 + tid;
+      const int kr = c / CPR, p = c % CPR;
+      const int col = min(row0 + ((p ^ (2 * (kr & 3))) << 3), row_lim - 8) - row0;
+      off[i] = (unsigned)((long)kr * ld * 2 + col * 2);
+    }
+  }
+  __device__ static __forceinline__ const char* base(const bf16_t* g, long ld, int row0) {
+    return (const char*)(g + row0);
+  }
+  __device__ static __forceinline__ long slice_bytes(long ld) { return BK * ld * 2; }
+  // entry blk = address of k-step 0 for 32-row block blk
+  __device__ static __forceinline__ void frag_table(unsigned (&t)[4], int wave_row0) {
+    const int l = threadIdx.x & 63, i = l & 15;
+    const int k = (l >> 5) * 8 + (i >> 2);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int col = wave_row0 + b * 32 + ((l >> 4) & 1) * 16 + (i & 3) * 4;
+      t[b] = (unsigned)(k * ROWS * 2 + ((((col >> 3) ^ (2 * (k & 3)))) << 4) + (col & 7) * 2);
+    }
+  }
+  __device__ static __forceinline__ bf16x8 frag(const unsigned (&t)[4], unsigned lds_base, int blk, int ks) {
+    const unsigned a = lds_base + t[blk] + ks * 16 * ROWS * 2;
+    union { short4_t s4[2]; bf16x8 b; } u;
+    u.s4[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(a));
+    u.s4[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(a + 4 * ROWS * 2));
+    return u.b;
+  }
+};
+
+template <int WM, int WN>
+struct SmemPl {
+  static constexpr int BM = 64 * WM, BN = 64 * WN;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int EPI_LD = 32 * WN + 4;
+  static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
+  static constexpr int MAIN_BYTES = 2 * STAGE_BYTES;
+  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+};
+
+#define BAMBOO_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int WM, int WN, bool A_K, bool B_K>
+struct PlLoop {
+  typedef SmemPl<WM, WN> SM;
+  typedef typename std::conditional<A_K, PlK<SM::BM>, PlMN<SM::BM>>::type OpA;
+  typedef typename std::conditional<B_K, PlK<SM::BN>, PlMN<SM::BN>>::type OpB;
+  static constexpr int NLA = OpA::NLOAD, NLB = OpB::NLOAD, NL = NLA + NLB;
+
+  unsigned offA[NLA], offB[NLB];      // per-thread global byte offsets
+  unsigned tabA[4], tabB[4];          // per-thread LDS fragment addresses
+  const char* gA;                     // wavefront-uniform slice pointers
+  const char* gB;
+  long stepA, stepB;
+  unsigned lds0;                      // LDS address of stage 0
+  unsigned wave_lds;                  // wave * 1024: where this wave's lanes of a 256-chunk group land
+
+  __device__ __forceinline__ void issue_one(int n, unsigned stage) const {
+    // n-th load of a slice: A chunks first, then B chunks
+    if (n < NLA) gload_lds16(offA[n], gA, lds0 + stage + n * 4096 + wave_lds);
+    else gload_lds16(offB[n - NLA], gB, lds0 + stage + SM::A_BYTES + (n - NLA) * 4096 + wave_lds);
+  }
+  __device__ __forceinline__ void issue_slice(unsigned stage) {
+#pragma unroll
+    for (int n = 0; n < NL; ++n) issue_one(n, stage);
+    gA += stepA;
+    gB += stepB;
+  }
+  __device__ __forceinline__ void read_one(int n, unsigned stage, int ks, bf16x8 (&fa)[WM], bf16x8 (&fb)[WN]) const {
+    if (n < WM) fa[n] = OpA::frag(tabA, lds0 + stage, n, ks);
+    else fb[n - WM] = OpB::frag(tabB, lds0 + stage + SM::A_BYTES, n - WM, ks);
+  }
+  // One k-step: MFMAs on (ca, cb); if READ, the fragments (na, nb) of k-step ks_next of the slice
+  // in `rstage` are fetched meanwhile; if LOAD, the global loads of a slice into `lstage` are issued too.
+  template <bool READ, bool LOAD>
+  __device__ __forceinline__ void kstep(f32x16 (&acc)[WM][WN], const bf16x8 (&ca)[WM], const bf16x8 (&cb)[WN],
+                                        bf16x8 (&na)[WM], bf16x8 (&nb)[WN], unsigned rstage, int ks_next,
+                                        unsigned lstage) {
+    constexpr int NMFMA = WM * WN;
+    constexpr int HALF = NMFMA >= 2 ? NMFMA / 2 : 1;
+    constexpr int LPM = (NL + HALF - 1) / HALF;                 // loads per MFMA over the first half of the MFMAs
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        const int n = i * WN + j;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+        if (LOAD) {
+#pragma unroll
+          for (int q = 0; q < LPM; ++q)
+            if (n * LPM + q < NL) issue_one(n * LPM + q, lstage);
+        }
+        if (READ) {
+          if (NMFMA >= WM + WN) {
+            if (n < WM + WN) read_one(n, rstage, ks_next, na, nb);
+          } else {   // fewer MFMAs than fragments (1x1 waves): two reads after each
+            if (2 * n < WM + WN) read_one(2 * n, rstage, ks_next, na, nb);
+            if (2 * n + 1 < WM + WN) read_one(2 * n + 1, rstage, ks_next, na, nb);
+          }
+        }
+        BAMBOO_SCHED_FENCE();
+      }
+    if (LOAD) {
+      gA += stepA;
+      gB += stepB;
+    }
+  }
+};
+
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int MINB>
+__global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
+  typedef SmemPl<WM, WN> SM;
+  typedef PlLoop<WM, WN, A_K, B_K> Loop;
   constexpr int BM = SM::BM, BN = SM::BN;
-  typedef typename std::conditional<A_K, DlK<BM>, DlMN<BM>>::type OpA;
-  typedef typename std::conditional<B_K, DlK<BN>, DlMN<BN>>::type OpB;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* smem = (bf16_t*)smem_raw;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
   tile_of_block((d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const bf16_t* A = (const bf16_t*)d.A;
-  const bf16_t* B = (const bf16_t*)d.B;
   const long lda = A_K ? d.a_sm : d.a_sk;
   const long ldb = B_K ? d.b_sn : d.b_sk;
+
+  Loop L;
+  Loop::OpA::load_offsets(L.offA, lda, m0, d.M);
+  Loop::OpB::load_offsets(L.offB, ldb, n0, d.N);
+  Loop::OpA::frag_table(L.tabA, wm * 32 * WM);
+  Loop::OpB::frag_table(L.tabB, wn * 32 * WN);
+  L.gA = Loop::OpA::base((const bf16_t*)d.A, lda, m0);
+  L.gB = Loop::OpB::base((const bf16_t*)d.B, ldb, n0);
+  L.stepA = Loop::OpA::slice_bytes(lda);
+  L.stepB = Loop::OpB::slice_bytes(ldb);
+  L.lds0 = (unsigned)(uintptr_t)(lds_void_ptr)smem_raw;
+  L.wave_lds = wave * 1024;
 
   f32x16 acc[WM][WN];
 #pragma unroll
@@ -412,34 +524,47 @@ __global__ __launch_bounds__(256) void gemm_mfma_dl_kernel(GemmDesc d) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = d.K / BK;
-  OpA::issue(A, lda, m0, d.M, 0, smem);
-  OpB::issue(B, ldb, n0, d.N, 0, smem + SM::A_ELEMS);
-  __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0): this wave's slice has landed in LDS
+  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
+  L.issue_slice(0);
+  L.issue_slice(SM::STAGE_BYTES);
+  // the oldest Loop::NL loads (slice 0) have landed; gfx9 encoding of vmcnt: bits 3:0 and 15:14
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (Loop::NL & 15) | ((Loop::NL >> 4) << 14));
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const bf16_t* sa = smem + (kt & 1) * SM::STAGE;
-    const bf16_t* sb = sa + SM::A_ELEMS;
-    if (kt + 1 < nk) {                    // next slice streams into the other buffer while this one is consumed
-      bf16_t* na = smem + ((kt + 1) & 1) * SM::STAGE;
-      OpA::issue(A, lda, m0, d.M, (kt + 1) * BK, na);
-      OpB::issue(B, ldb, n0, d.N, (kt + 1) * BK, na + SM::A_ELEMS);
-    }
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[WM], fb[WN];
-#pragma unroll
-      for (int i = 0; i < WM; ++i) fa[i] = OpA::frag(sa, wm * 32 * WM + i * 32, ks);
-#pragma unroll
-      for (int j = 0; j < WN; ++j) fb[j] = OpB::frag(sb, wn * 32 * WN + j * 32, ks);
-#pragma unroll
-      for (int i = 0; i < WM; ++i)
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+  for (int n = 0; n < WM + WN; ++n) L.read_one(n, 0, 0, fa0, fb0);
+
+  // nk >= 2 (checked by the launcher).  The last two slices are peeled so that the loop body has
+  // no branch: slice nk-2 issues no global loads, slice nk-1 neither loads nor reads ahead.
+  for (int kt = 0; kt < nk - 2; ++kt) {
+    const unsigned cur = (kt & 1) ? SM::STAGE_BYTES : 0, nxt = SM::STAGE_BYTES - cur;
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 1, 0);
+    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, cur, 2, 0);
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 3, 0);
+    // every LDS read of this slice has been issued: once they have returned (and this wave's part
+    // of the next slice has landed) the buffer may be overwritten
+    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
     __syncthreads();
+    BAMBOO_SCHED_FENCE();
+    L.template kstep<true, true>(acc, fa1, fb1, fa0, fb0, nxt, 0, cur);
   }
+  {
+    const unsigned cur = (nk & 1) ? SM::STAGE_BYTES : 0, nxt = SM::STAGE_BYTES - cur;   // slice nk-2
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 1, 0);
+    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, cur, 2, 0);
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 3, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    BAMBOO_SCHED_FENCE();
+    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, nxt, 0, 0);
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, nxt, 1, 0);                   // slice nk-1
+    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, nxt, 2, 0);
+    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, nxt, 3, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    __syncthreads();
+    BAMBOO_SCHED_FENCE();
+    L.template kstep<false, false>(acc, fa1, fb1, fa0, fb0, 0, 0, 0);
+  }
+  // no LDS read is outstanding after the last slice's barrier: the staging area may reuse the buffers
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
 }
 
@@ -447,10 +572,10 @@ template <int WM, int WN, bool A_K, bool B_K, int EPI>
 static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
   const int tiles = ((d.M + 64 * WM - 1) / (64 * WM)) * ((d.N + 64 * WN - 1) / (64 * WN));
   static const bool no_direct = getenv("BAMBOO_GEMM_NO_DIRECT") != nullptr;   // tuning knob
-  if (d.K % BK == 0 && !no_direct) {
-    typedef SmemDl<WM, WN> SM;
+  if (d.K % BK == 0 && d.K >= 2 * BK && !no_direct) {
+    typedef SmemPl<WM, WN> SM;
     static bool attr_set = false;
-    auto kern = gemm_mfma_dl_kernel<WM, WN, A_K, B_K, EPI>;
+    auto kern = gemm_mfma_pl_kernel<WM, WN, A_K, B_K, EPI, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
       if (e != hipSuccess) return e;
@@ -471,22 +596,34 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
   return hipGetLastError();
 }
 
+static int g_forced_tile = 0;
+bool gemm_tile_code_valid(int code) { return code == 0 || code == 44 || code == 42 || code == 24 || code == 22 || code == 11; }
+int set_gemm_tile(int code) {
+  const int prev = g_forced_tile;
+  g_forced_tile = code;
+  return prev;
+}
+
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
-  // (BAMBOO_GEMM_TILE=1|3|4 forces 128x128 | 256x256 | 64x64 output tiles for tuning runs)
-  static const int forced = getenv("BAMBOO_GEMM_TILE") ? atoi(getenv("BAMBOO_GEMM_TILE")) : 0;
-  if (forced == 1) return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
-  if (forced == 3) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
-  if (forced == 4) return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
-  // Tile choice.  256x256 tiles have the best MFMA : LDS ratio but only pay when
-  // they still come in at least two rounds over the 256 CUs; 128x128 tiles (two
-  // workgroups per CU) are the default; outputs too small to give every CU a
-  // 128x128 tile use 64x64 tiles.
-  const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
-  const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
-  if (t256 >= 2 * 256) return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
-  if (t128 >= 192) return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
-  return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
+  int pick = g_forced_tile;
+  if (pick == 0) {
+    // Tile choice.  256x256 tiles have the best MFMA : LDS ratio but only pay when
+    // they still come in at least two rounds over the 256 CUs; 128x128 tiles (two
+    // workgroups per CU) are the default; outputs too small to give every CU a
+    // 128x128 tile use 64x64 tiles.
+    const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
+    const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
+    pick = t256 >= 2 * 256 ? 44 : (t128 >= 192 ? 22 : 11);
+  }
+  switch (pick) {
+    case 44: return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
+    case 42: return launch_cfg<4, 2, A_K, B_K, EPI>(s, d);
+    case 24: return launch_cfg<2, 4, A_K, B_K, EPI>(s, d);
+    case 22: return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
+    case 11: return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {

@@ -139,4 +139,9 @@ int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
   return finish(launch_copy((hipStream_t)stream, src, dst, (size_t)bytes));
 }
 
+int bk_gemm_tile(int code) {
+  if (!gemm_tile_code_valid(code)) return BAMBOO_E_ARG;
+  return set_gemm_tile(code);
+}
+
 }  // extern "C"
