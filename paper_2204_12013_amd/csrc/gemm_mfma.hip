@@ -36,7 +36,7 @@ constexpr int KROW = BK + 8;    // LDS row length (elements) of a k-contiguous o
 
 template <int ROWS>
 struct MnMajor {                 // LDS row length (elements) of an operand stored [k][row]
-  static constexpr int LD = ROWS + 16;   // +32 B: the 4 k-rows of a transposing read fall in distinct banks
+  static constexpr int LD = ROWS + 32;   // +64 B: the 4 k-rows x 64 B of a transposing read fall in distinct banks
 };
 
 template <int WM, int WN, bool A_K, bool B_K>
@@ -341,7 +341,10 @@ __device__ __forceinline__ void gload_lds16(unsigned voff, const void* sbase, un
                : "memory", "m0");
 }
 
-// K-contiguous operand, ROWS x 64 per slice; LDS row r = 128 bytes, 16-byte chunk c at position c ^ (r % 8).
+// K-contiguous operand, ROWS x 64 per slice; LDS row r = 128 bytes, 16-byte chunk c at position
+// c ^ ((r / 2) % 8).  The LDS has 64 four-byte banks and serves a 16-byte read for 16 lanes per
+// cycle: 16 consecutive rows then cover every bank exactly once (rows 2j and 2j+1 share a position
+// in the two 128-byte halves of the 256-byte bank line).
 template <int ROWS>
 struct PlK {
   static constexpr int NLOAD = ROWS / 32;
@@ -353,7 +356,7 @@ struct PlK {
     for (int i = 0; i < NLOAD; ++i) {
       const int r = i * 32 + (tid >> 3), p = tid & 7;
       const int row = min(row0 + r, row_lim - 1) - row0;
-      off[i] = (unsigned)((long)row * ld * 2 + ((p ^ (r & 7)) << 4));
+      off[i] = (unsigned)((long)row * ld * 2 + ((p ^ ((r >> 1) & 7)) << 4));
     }
   }
   __device__ static __forceinline__ const char* base(const bf16_t* g, long ld, int row0) {
@@ -365,25 +368,28 @@ struct PlK {
     const int l = threadIdx.x & 63;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      t[ks] = (unsigned)((wave_row0 + (l & 31)) * (BK * 2) + (((2 * ks + (l >> 5)) ^ (l & 7)) << 4));
+      t[ks] = (unsigned)((wave_row0 + (l & 31)) * (BK * 2) + (((2 * ks + (l >> 5)) ^ ((l >> 1) & 7)) << 4));
   }
   __device__ static __forceinline__ bf16x8 frag(const unsigned (&t)[4], unsigned lds_base, int blk, int ks) {
     return *(lds_bf16x8_ptr)(lds_base + t[ks] + blk * 32 * BK * 2);
   }
 };
-// Row-contiguous operand, 64 k-rows x ROWS per slice; chunk c of k-row k at position c ^ (2 * (k % 4)).
+// Row-contiguous operand, 64 k-rows x ROWS per slice; chunk c of k-row k at position c ^ swz(k).
+// A transposing 8-byte read is served for 32 lanes per cycle, which address 4 consecutive k-rows x
+// 64 bytes: swz moves those four 64-byte pieces to distinct quarters of the 256-byte bank line.
 template <int ROWS>
 struct PlMN {
   static constexpr int NLOAD = ROWS / 32;
   static constexpr int BYTES = ROWS * BK * 2;
   static constexpr int CPR = ROWS / 8;
+  __device__ static __forceinline__ int swz(int k) { return ROWS >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
   __device__ static __forceinline__ void load_offsets(unsigned (&off)[NLOAD], long ld, int row0, int row_lim) {
     const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int c = i * 256 + tid;
       const int kr = c / CPR, p = c % CPR;
-      const int col = min(row0 + ((p ^ (2 * (kr & 3))) << 3), row_lim - 8) - row0;
+      const int col = min(row0 + ((p ^ swz(kr)) << 3), row_lim - 8) - row0;
       off[i] = (unsigned)((long)kr * ld * 2 + col * 2);
     }
   }
@@ -398,7 +404,7 @@ struct PlMN {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int col = wave_row0 + b * 32 + ((l >> 4) & 1) * 16 + (i & 3) * 4;
-      t[b] = (unsigned)(k * ROWS * 2 + ((((col >> 3) ^ (2 * (k & 3)))) << 4) + (col & 7) * 2);
+      t[b] = (unsigned)(k * ROWS * 2 + (((col >> 3) ^ swz(k)) << 4) + (col & 7) * 2);
     }
   }
   __device__ static __forceinline__ bf16x8 frag(const unsigned (&t)[4], unsigned lds_base, int blk, int ks) {
