@@ -79,6 +79,12 @@ int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream);
  * offered.  Not thread-safe against concurrent launches. */
 int bk_gemm_tile(int code);
 
+/* Tuning and test hook: force the depth of the LDS slice ring of the pipelined MFMA
+ * GEMM kernel (2, 3 or 4 buffers; a depth that does not fit the tile's LDS budget
+ * or exceeds the number of K slices falls back to the next smaller one); 0 restores
+ * the automatic choice.  Returns the previous value, or BAMBOO_E_ARG. */
+int bk_gemm_stages(int n);
+
 #ifdef __cplusplus
 }
 #endif

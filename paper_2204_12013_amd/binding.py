@@ -82,6 +82,7 @@ _SIGS = {
     "bk_layernorm_bwd_scratch_floats": (C.c_uint64, [C.c_int]),
     "bk_copy": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
     "bk_gemm_tile": (C.c_int, [C.c_int]),
+    "bk_gemm_stages": (C.c_int, [C.c_int]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -349,6 +350,11 @@ def bk_copy(src, dst, stream=None):
 def bk_gemm_tile(code):
     """Force the MFMA GEMM output tile (10*WM + WN; 0 = automatic); returns the previous code."""
     return _check(lib.bk_gemm_tile(code), "bk_gemm_tile")
+
+
+def bk_gemm_stages(n):
+    """Force the LDS ring depth of the pipelined MFMA GEMM (2..4; 0 = automatic); returns the previous value."""
+    return _check(lib.bk_gemm_stages(n), "bk_gemm_stages")
 
 
 # ---- numpy <-> device helpers (storage conversion only) ------------------------

@@ -97,6 +97,8 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
 // output tile of the MFMA kernel: 10*WM + WN forces (64*WM) x (64*WN), 0 = automatic; returns the previous code
 bool gemm_tile_code_valid(int code);
 int set_gemm_tile(int code);
+// LDS ring depth of the pipelined MFMA kernel: 2, 3 or 4 forces it where it fits, 0 = automatic; returns the previous value
+int set_gemm_stages(int n);
 
 // ---- attention ---------------------------------------------------------------
 // qkv [T,3H] (queries | keys | values), ctx [T,H], lse fp32 [B,heads,S]

@@ -138,13 +138,60 @@ __device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks)
 // copy with the MFMAs; the kernel waits on vmcnt itself before the barrier
 // that publishes a slice.  M0 carries the wavefront-uniform LDS base.
 
-// ---- epilogue on 8 consecutive outputs of one row ---------------------------------------
-template <int EPI>
-__device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8]) {
+// ---- epilogue ---------------------------------------------------------------------------
+// The accumulators leave through a wavefront-private LDS staging area; afterwards lane l of a wave
+// owns, for row block i and pass `it`, the 8 consecutive outputs of chunk idx = l + 64 * it of the
+// staged 32 x (32 * WN) block (row idx / CHUNKS, columns 8 * (idx % CHUNKS) ..).  What the epilogue
+// has to read from memory for those outputs (residual, stored pre-activation, fp32 gradient to add
+// to) can therefore be fetched long before the accumulators are final: EpiOperands::issue is
+// called ahead of the last slices of the main loop, so the latency is covered by MFMAs.
+template <int WM, int WN, int EPI>
+struct EpiOperands {
+  static constexpr int CHUNKS = 4 * WN, ITS = 32 * CHUNKS / 64;
+  // only where the operands fit in 64 registers per lane; larger tiles read them in the epilogue itself
+  static constexpr bool BF = (EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_DGELU) && WM * ITS * 4 <= 64;
+  static constexpr bool F32 = EPI == EPI_ACC_F32 && WM * ITS * 8 <= 64;
+  static constexpr bool NEEDS = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_DGELU || EPI == EPI_ACC_F32;
+  static constexpr bool PRE = BF || F32;
+  static constexpr int NLOADS = BF ? WM * ITS : (F32 ? 2 * WM * ITS : 0);   // load instructions per lane
+  bf16x8 b[BF ? WM : 1][BF ? ITS : 1];
+  f32x4 f[F32 ? WM : 1][F32 ? ITS : 1][2];
+  // Rows / columns past the edge are clamped to the last valid ones (their values are never used), so
+  // that every lane issues exactly NLOADS loads: the main loop counts them in its vmcnt waits.
+  __device__ __forceinline__ void issue(const GemmDesc& d, int m0, int n0) {
+    if (!BF && !F32) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const void* src = EPI == EPI_DGELU ? d.aux_in : (F32 ? (const void*)d.C : d.res);
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int it = 0; it < ITS; ++it) {
+        const int idx = lane + it * 64;
+        const int m = min(m0 + wm * 32 * WM + i * 32 + idx / CHUNKS, d.M - 1);
+        const int n = min(n0 + wn * 32 * WN + (idx % CHUNKS) * 8, d.N - 8);
+        const long e = (long)m * d.N + n;
+        if (BF) b[i][it] = *(const bf16x8*)((const bf16_t*)src + e);
+        if (F32) {
+          f[i][it][0] = *(const f32x4*)((const float*)src + e);
+          f[i][it][1] = *(const f32x4*)((const float*)src + e + 4);
+        }
+      }
+  }
+};
+
+// epilogue on 8 consecutive outputs of one row; `pb_in` / `pf_in` are the prefetched operands (if PRE)
+template <int EPI, bool PRE>
+__device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb_in,
+                                          const f32x4 (&pf_in)[2]) {
   const long i = (long)m * d.N + n;
+  bf16x8 pb = pb_in;
+  if (!PRE && (EPI == EPI_BIAS_RES || EPI == EPI_RES)) pb = *(const bf16x8*)((const bf16_t*)d.res + i);
+  if (!PRE && EPI == EPI_DGELU) pb = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
-    f32x4 a = *(f32x4*)c, b = *(f32x4*)(c + 4);
+    f32x4 a = pf_in[0], b = pf_in[1];
+    if (!PRE) { a = *(f32x4*)c; b = *(f32x4*)(c + 4); }
 #pragma unroll
     for (int j = 0; j < 4; ++j) { a[j] += acc[j]; b[j] += acc[4 + j]; }
     *(f32x4*)c = a;
@@ -160,18 +207,16 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
     for (int j = 0; j < 8; ++j) v[j] += (float)b[j];
   }
   if (EPI == EPI_BIAS_RES || EPI == EPI_RES) {
-    const bf16x8 r = *(const bf16x8*)((const bf16_t*)d.res + i);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] += (float)r[j];
+    for (int j = 0; j < 8; ++j) v[j] += (float)pb[j];
   }
   bf16x8 o;
   if (EPI == EPI_DGELU) {
-    const bf16x8 h = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
     bf16x8 g;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float gv, dgv;
-      gelu_pair_fast((float)h[j], &gv, &dgv);
+      gelu_pair_fast((float)pb[j], &gv, &dgv);
       o[j] = (bf16_t)(v[j] * dgv);
       g[j] = (bf16_t)gv;
     }
@@ -195,7 +240,9 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
 
 // Accumulators -> wavefront-private LDS rows -> 16-byte global accesses.
 template <int WM, int WN, int EPI, int EPI_LD>
-__device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][WN], float* stage_all, int m0, int n0) {
+__device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][WN], float* stage_all, int m0, int n0,
+                                           const EpiOperands<WM, WN, EPI>& ops) {
+  typedef EpiOperands<WM, WN, EPI> Ops;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   float* stage = stage_all + wave * 32 * EPI_LD;
@@ -209,9 +256,9 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
         stage[(8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) * EPI_LD + j * 32 + (lane & 31)] = acc[i][j][r];
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the wave's own LDS writes have landed
     __builtin_amdgcn_wave_barrier();
-    constexpr int CHUNKS = 4 * WN;        // 8-float chunks per staged row
+    constexpr int CHUNKS = Ops::CHUNKS;   // 8-float chunks per staged row
 #pragma unroll
-    for (int it = 0; it < 32 * CHUNKS / 64; ++it) {
+    for (int it = 0; it < Ops::ITS; ++it) {
       const int idx = lane + it * 64;
       const int row = idx / CHUNKS, ch = idx % CHUNKS;
       const int m = m0 + wm * 32 * WM + i * 32 + row;
@@ -220,7 +267,7 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
       const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
       if (m < d.M && n < d.N) {
         const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI>(d, m, n, v);
+        epilogue8<EPI, Ops::PRE>(d, m, n, v, ops.b[Ops::BF ? i : 0][Ops::BF ? it : 0], ops.f[Ops::F32 ? i : 0][Ops::F32 ? it : 0]);
       }
     }
     __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
@@ -316,7 +363,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
     __syncthreads();
   }
 
-  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
+  EpiOperands<WM, WN, EPI> ops;
+  ops.issue(d, m0, n0);
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
 }
 
 // ---- software-pipelined kernel with direct global -> LDS loads (K a multiple of 64) ------
@@ -416,13 +465,13 @@ struct PlMN {
   }
 };
 
-template <int WM, int WN>
+template <int WM, int WN, int NS>
 struct SmemPl {
   static constexpr int BM = 64 * WM, BN = 64 * WN;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int EPI_LD = 32 * WN + 4;
   static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
-  static constexpr int MAIN_BYTES = 2 * STAGE_BYTES;
+  static constexpr int MAIN_BYTES = NS * STAGE_BYTES;
   static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
 };
 
@@ -430,7 +479,7 @@ struct SmemPl {
 
 template <int WM, int WN, bool A_K, bool B_K>
 struct PlLoop {
-  typedef SmemPl<WM, WN> SM;
+  typedef SmemPl<WM, WN, 2> SM;
   typedef typename std::conditional<A_K, PlK<SM::BM>, PlMN<SM::BM>>::type OpA;
   typedef typename std::conditional<B_K, PlK<SM::BN>, PlMN<SM::BN>>::type OpB;
   static constexpr int NLA = OpA::NLOAD, NLB = OpB::NLOAD, NL = NLA + NLB;
@@ -459,47 +508,61 @@ struct PlLoop {
     else fb[n - WM] = OpB::frag(tabB, lds0 + stage + SM::A_BYTES, n - WM, ks);
   }
   // One k-step: MFMAs on (ca, cb); if READ, the fragments (na, nb) of k-step ks_next of the slice
-  // in `rstage` are fetched meanwhile; if LOAD, the global loads of a slice into `lstage` are issued too.
-  template <bool READ, bool LOAD>
+  // in `rstage` are fetched meanwhile, all of them behind the first MFMAs so that they have the
+  // rest of this k-step and all of the next one to return; LOADPART 1 / 2 issues the first / second
+  // half of the global loads of a slice into `lstage`, spread over the MFMAs.
+  template <bool READ, int LOADPART>
   __device__ __forceinline__ void kstep(f32x16 (&acc)[WM][WN], const bf16x8 (&ca)[WM], const bf16x8 (&cb)[WN],
                                         bf16x8 (&na)[WM], bf16x8 (&nb)[WN], unsigned rstage, int ks_next,
                                         unsigned lstage) {
-    constexpr int NMFMA = WM * WN;
-    constexpr int HALF = NMFMA >= 2 ? NMFMA / 2 : 1;
-    constexpr int LPM = (NL + HALF - 1) / HALF;                 // loads per MFMA over the first half of the MFMAs
+    constexpr int NMFMA = WM * WN, NR = WM + WN;
+    constexpr int RSPAN = NMFMA >= 4 ? NMFMA / 2 : 1;           // MFMAs that carry the reads
+    constexpr int RPM = (NR + RSPAN - 1) / RSPAN;               // reads per MFMA
+    constexpr int NLH = (NL + 1) / 2;                           // loads per half
+    constexpr int LPM = (NLH + NMFMA - 1) / NMFMA;              // loads per MFMA
+    constexpr int L0 = LOADPART == 2 ? NLH : 0, L1 = LOADPART == 1 ? NLH : NL;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
       for (int j = 0; j < WN; ++j) {
         const int n = i * WN + j;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
-        if (LOAD) {
+        if (READ) {
+#pragma unroll
+          for (int q = 0; q < RPM; ++q)
+            if (n < RSPAN && n * RPM + q < NR) read_one(n * RPM + q, rstage, ks_next, na, nb);
+        }
+        if (LOADPART != 0) {
 #pragma unroll
           for (int q = 0; q < LPM; ++q)
-            if (n * LPM + q < NL) issue_one(n * LPM + q, lstage);
-        }
-        if (READ) {
-          if (NMFMA >= WM + WN) {
-            if (n < WM + WN) read_one(n, rstage, ks_next, na, nb);
-          } else {   // fewer MFMAs than fragments (1x1 waves): two reads after each
-            if (2 * n < WM + WN) read_one(2 * n, rstage, ks_next, na, nb);
-            if (2 * n + 1 < WM + WN) read_one(2 * n + 1, rstage, ks_next, na, nb);
-          }
+            if (L0 + n * LPM + q < L1) issue_one(L0 + n * LPM + q, lstage);
         }
         BAMBOO_SCHED_FENCE();
       }
-    if (LOAD) {
+    if (LOADPART == 2) {
       gA += stepA;
       gB += stepB;
     }
   }
 };
 
-template <int WM, int WN, bool A_K, bool B_K, int EPI, int MINB>
+// vmcnt(n) lgkmcnt(0): at most n of this wave's global loads still in flight, every LDS read returned
+// (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4 left at its maximum, lgkmcnt 11:8)
+template <int N>
+__device__ __forceinline__ void wait_loads_and_lds() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Slices are kept in NS LDS buffers used round-robin; the global -> LDS loads of slice kt + NS - 1 ... are
+// in flight while slice kt feeds the MFMAs, i.e. a load has NS - 1 slices of MFMA time to land.
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS, int MINB>
 __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
-  typedef SmemPl<WM, WN> SM;
+  typedef SmemPl<WM, WN, NS> SM;
   typedef PlLoop<WM, WN, A_K, B_K> Loop;
-  constexpr int BM = SM::BM, BN = SM::BN;
+  constexpr int BM = SM::BM, BN = SM::BN, NL = Loop::NL;
+  constexpr unsigned STAGE = SM::STAGE_BYTES, RING = NS * STAGE;
+  static_assert((NS - 1) * NL + EpiOperands<WM, WN, EPI>::NLOADS < 64, "too many loads in flight for the vmcnt counter");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -529,49 +592,86 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = d.K / BK;
-  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
-  L.issue_slice(0);
-  L.issue_slice(SM::STAGE_BYTES);
-  // the oldest Loop::NL loads (slice 0) have landed; gfx9 encoding of vmcnt: bits 3:0 and 15:14
-  __builtin_amdgcn_s_waitcnt(0x0f70 | (Loop::NL & 15) | ((Loop::NL >> 4) << 14));
+  const int nk = d.K / BK;                 // nk >= NS (checked by the launcher)
+  // four fragment register sets: k-step s of a slice computes from set s while set (s + 2) % 4 is
+  // filled for the k-step after the next one, so an LDS read has more than a whole k-step to return
+  bf16x8 fa[4][WM], fb[4][WN];
+#pragma unroll
+  for (int j = 0; j < NS; ++j) L.issue_slice(j * STAGE);
+  wait_loads_and_lds<(NS - 1) * NL>();     // slice 0 has landed
   __syncthreads();
 #pragma unroll
-  for (int n = 0; n < WM + WN; ++n) L.read_one(n, 0, 0, fa0, fb0);
+  for (int n = 0; n < WM + WN; ++n) L.read_one(n, 0, 0, fa[0], fb[0]);
+#pragma unroll
+  for (int n = 0; n < WM + WN; ++n) L.read_one(n, 0, 1, fa[1], fb[1]);
 
-  // nk >= 2 (checked by the launcher).  The last two slices are peeled so that the loop body has
-  // no branch: slice nk-2 issues no global loads, slice nk-1 neither loads nor reads ahead.
-  for (int kt = 0; kt < nk - 2; ++kt) {
-    const unsigned cur = (kt & 1) ? SM::STAGE_BYTES : 0, nxt = SM::STAGE_BYTES - cur;
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 1, 0);
-    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, cur, 2, 0);
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 3, 0);
-    // every LDS read of this slice has been issued: once they have returned (and this wave's part
-    // of the next slice has landed) the buffer may be overwritten
-    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0) lgkmcnt(0)
+  // Steady state: slice kt computes from buffer cur.  During its first two k-steps the fragments of
+  // its last two are read, so after them every LDS read of cur has been issued; once they have
+  // returned and slice kt+1 has landed for every wave, the barrier frees cur for the loads of slice
+  // kt+NS (issued between the MFMAs of the last two k-steps) and opens buffer nxt for reading.
+  unsigned cur = 0;
+  for (int kt = 0; kt < nk - NS; ++kt) {
+    const unsigned nxt = cur + STAGE == RING ? 0 : cur + STAGE;
+    L.template kstep<true, 0>(acc, fa[0], fb[0], fa[2], fb[2], cur, 2, 0);
+    L.template kstep<true, 0>(acc, fa[1], fb[1], fa[3], fb[3], cur, 3, 0);
+    wait_loads_and_lds<(NS - 2) * NL>();
     __syncthreads();
     BAMBOO_SCHED_FENCE();
-    L.template kstep<true, true>(acc, fa1, fb1, fa0, fb0, nxt, 0, cur);
+    L.template kstep<true, 1>(acc, fa[2], fb[2], fa[0], fb[0], nxt, 0, cur);
+    L.template kstep<true, 2>(acc, fa[3], fb[3], fa[1], fb[1], nxt, 1, cur);
+    cur = nxt;
   }
-  {
-    const unsigned cur = (nk & 1) ? SM::STAGE_BYTES : 0, nxt = SM::STAGE_BYTES - cur;   // slice nk-2
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 1, 0);
-    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, cur, 2, 0);
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, cur, 3, 0);
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    __syncthreads();
-    BAMBOO_SCHED_FENCE();
-    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, nxt, 0, 0);
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, nxt, 1, 0);                   // slice nk-1
-    L.template kstep<true, false>(acc, fa1, fb1, fa0, fb0, nxt, 2, 0);
-    L.template kstep<true, false>(acc, fa0, fb0, fa1, fb1, nxt, 3, 0);
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    __syncthreads();
-    BAMBOO_SCHED_FENCE();
-    L.template kstep<false, false>(acc, fa1, fb1, fa0, fb0, 0, 0, 0);
+  // The last NS slices issue no slice loads; instead the epilogue's operands are requested now, so
+  // that they arrive under the remaining MFMAs.  They are younger than every slice load, hence
+  // simply add to the number of loads that may still be in flight at the waits below.
+  EpiOperands<WM, WN, EPI> ops;
+  ops.issue(d, m0, n0);
+  constexpr int NEPI = EpiOperands<WM, WN, EPI>::NLOADS;
+  BAMBOO_SCHED_FENCE();
+  // slice nk-1-J still has J slices after it, J-1 of which may be in flight
+  auto tail = [&](auto jc) __attribute__((always_inline)) {
+    constexpr int J = decltype(jc)::value;
+    const unsigned nxt = cur + STAGE == RING ? 0 : cur + STAGE;
+    L.template kstep<true, 0>(acc, fa[0], fb[0], fa[2], fb[2], cur, 2, 0);
+    L.template kstep<true, 0>(acc, fa[1], fb[1], fa[3], fb[3], cur, 3, 0);
+    if (J > 0) {
+      wait_loads_and_lds<(J > 1 ? J - 1 : 0) * NL + NEPI>();
+      __syncthreads();
+      BAMBOO_SCHED_FENCE();
+    }
+    L.template kstep<(J > 0), 0>(acc, fa[2], fb[2], fa[0], fb[0], nxt, 0, 0);
+    L.template kstep<(J > 0), 0>(acc, fa[3], fb[3], fa[1], fb[1], nxt, 1, 0);
+    cur = nxt;
+  };
+  if constexpr (NS >= 4) tail(std::integral_constant<int, 3>());
+  if constexpr (NS >= 3) tail(std::integral_constant<int, 2>());
+  tail(std::integral_constant<int, 1>());
+  tail(std::integral_constant<int, 0>());
+  // every wave is done with the slice buffers before the staging area reuses them
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __syncthreads();
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
+}
+
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
+static hipError_t launch_pl(hipStream_t s, const GemmDesc& d, int tiles) {
+  typedef SmemPl<WM, WN, NS> SM;
+  static bool attr_set = false;
+  auto kern = gemm_mfma_pl_kernel<WM, WN, A_K, B_K, EPI, NS, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
   }
-  // no LDS read is outstanding after the last slice's barrier: the staging area may reuse the buffers
-  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
+  return hipGetLastError();
+}
+
+static int g_forced_stages = 0;
+int set_gemm_stages(int n) {
+  const int prev = g_forced_stages;
+  g_forced_stages = n;
+  return prev;
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI>
@@ -579,16 +679,19 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
   const int tiles = ((d.M + 64 * WM - 1) / (64 * WM)) * ((d.N + 64 * WN - 1) / (64 * WN));
   static const bool no_direct = getenv("BAMBOO_GEMM_NO_DIRECT") != nullptr;   // tuning knob
   if (d.K % BK == 0 && d.K >= 2 * BK && !no_direct) {
-    typedef SmemPl<WM, WN> SM;
-    static bool attr_set = false;
-    auto kern = gemm_mfma_pl_kernel<WM, WN, A_K, B_K, EPI, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
-      if (e != hipSuccess) return e;
-      attr_set = true;
+    // Pipeline depth: two buffers leave room for two workgroups per CU, which hide each other's
+    // stalls; when the launch gives a CU one workgroup anyway, a deeper ring hides the load latency.
+    const int nk = d.K / BK;
+    int ns = g_forced_stages;
+    if (ns == 0) ns = 2;
+    if (ns > nk) ns = nk >= 3 ? 3 : 2;
+    if constexpr (SmemPl<WM, WN, 4>::BYTES <= 160 * 1024) {
+      if (ns == 4) return launch_pl<WM, WN, A_K, B_K, EPI, 4>(s, d, tiles);
     }
-    hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
-    return hipGetLastError();
+    if constexpr (SmemPl<WM, WN, 3>::BYTES <= 160 * 1024) {
+      if (ns >= 3) return launch_pl<WM, WN, A_K, B_K, EPI, 3>(s, d, tiles);
+    }
+    return launch_pl<WM, WN, A_K, B_K, EPI, 2>(s, d, tiles);
   }
   typedef Smem<WM, WN, A_K, B_K> SM;
   static bool attr_set = false;

@@ -144,4 +144,9 @@ int bk_gemm_tile(int code) {
   return set_gemm_tile(code);
 }
 
+int bk_gemm_stages(int n) {
+  if (n != 0 && (n < 2 || n > 4)) return BAMBOO_E_ARG;
+  return set_gemm_stages(n);
+}
+
 }  // extern "C"
