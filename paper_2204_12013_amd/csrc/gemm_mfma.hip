@@ -675,15 +675,12 @@ int set_gemm_stages(int n) {
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI>
-static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d) {
+static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d, int ns) {
   const int tiles = ((d.M + 64 * WM - 1) / (64 * WM)) * ((d.N + 64 * WN - 1) / (64 * WN));
   static const bool no_direct = getenv("BAMBOO_GEMM_NO_DIRECT") != nullptr;   // tuning knob
   if (d.K % BK == 0 && d.K >= 2 * BK && !no_direct) {
-    // Pipeline depth: two buffers leave room for two workgroups per CU, which hide each other's
-    // stalls; when the launch gives a CU one workgroup anyway, a deeper ring hides the load latency.
     const int nk = d.K / BK;
-    int ns = g_forced_stages;
-    if (ns == 0) ns = 2;
+    if (g_forced_stages) ns = g_forced_stages;
     if (ns > nk) ns = nk >= 3 ? 3 : 2;
     if constexpr (SmemPl<WM, WN, 4>::BYTES <= 160 * 1024) {
       if (ns == 4) return launch_pl<WM, WN, A_K, B_K, EPI, 4>(s, d, tiles);
@@ -713,24 +710,63 @@ int set_gemm_tile(int code) {
   return prev;
 }
 
+// Tile and pipeline-depth choice.  Each candidate's run time is estimated as
+//   rounds * (a + b * slices) + c   [microseconds]
+// where rounds = ceil(tiles / (256 CUs * workgroups that fit a CU)) and slices = K / 64; a is the
+// per-tile fill and epilogue cost, b the time of one 64-deep slice, c a launch constant.  The
+// coefficients are least-squares fits to timings of the BERT-large- and GPT-2-shaped stage GEMMs
+// on an MI355X with operands that are not cache-resident (as inside a training iteration): big
+// tiles have the best MFMA : LDS ratio but need enough of them to fill the chip; two buffers leave
+// room for two workgroups per CU, which hide each other's stalls; when a CU gets one workgroup
+// anyway, a deeper ring hides the load latency instead.
+struct TileCost { int code, ns; float a, b, c; };
+static const TileCost kCostStore[] = {     // bf16 output (forward and input-gradient forms)
+    {11, 2, 1.96f, 0.377f, 3.94f}, {11, 4, 1.48f, 0.396f, 5.05f}, {22, 2, 5.04f, 0.949f, 0.35f},
+    {22, 3, 4.52f, 0.545f, 1.60f}, {24, 2, 4.93f, 1.068f, 5.59f}, {24, 3, 7.76f, 0.816f, 1.45f},
+    {42, 2, 1.85f, 1.107f, 8.18f}, {42, 3, 5.44f, 0.874f, 2.50f}, {44, 2, 14.98f, 1.281f, 0.58f}};
+static const TileCost kCostAcc[] = {       // fp32 read-modify-write output (weight-gradient form)
+    {11, 2, 0.f, 0.487f, 1.98f}, {11, 4, 0.f, 0.504f, 0.f}, {22, 2, 0.f, 0.983f, 0.f},
+    {22, 3, 0.f, 0.616f, 2.88f}, {24, 2, 0.f, 1.216f, 6.12f}, {24, 3, 0.f, 1.072f, 1.03f},
+    {42, 2, 0.f, 1.102f, 11.56f}, {42, 3, 0.f, 0.997f, 4.55f}, {44, 2, 0.f, 1.737f, 0.f}};
+
+static void choose_tile(const GemmDesc& d, bool acc_form, int* code, int* ns) {
+  const int nk = d.K / BK;
+  const TileCost* tab = acc_form ? kCostAcc : kCostStore;
+  float best = 0.f;
+  *code = 22;
+  *ns = 2;
+  for (int i = 0; i < 9; ++i) {
+    const TileCost& t = tab[i];
+    if (t.ns > nk && t.ns > 2) continue;
+    const int wm = t.code / 10, wn = t.code % 10;
+    const long tiles = (long)((d.M + 64 * wm - 1) / (64 * wm)) * ((d.N + 64 * wn - 1) / (64 * wn));
+    const long stage = (long)(wm + wn) * 64 * BK * 2, epi = 4L * 32 * (32 * wn + 4) * 4;
+    const long lds = t.ns * stage > epi ? t.ns * stage : epi;
+    const long slots = 256 * (2 * lds <= 160 * 1024 ? 2 : 1);
+    const long rounds = (tiles + slots - 1) / slots;
+    const float cost = rounds * (t.a + t.b * nk) + t.c;
+    if (i == 0 || cost < best) {
+      best = cost;
+      *code = t.code;
+      *ns = t.ns;
+    }
+  }
+}
+
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
-  int pick = g_forced_tile;
-  if (pick == 0) {
-    // Tile choice.  256x256 tiles have the best MFMA : LDS ratio but only pay when
-    // they still come in at least two rounds over the 256 CUs; 128x128 tiles (two
-    // workgroups per CU) are the default; outputs too small to give every CU a
-    // 128x128 tile use 64x64 tiles.
-    const long t256 = (long)((d.M + 255) / 256) * ((d.N + 255) / 256);
-    const long t128 = (long)((d.M + 127) / 128) * ((d.N + 127) / 128);
-    pick = t256 >= 2 * 256 ? 44 : (t128 >= 192 ? 22 : 11);
+  int pick, ns;
+  choose_tile(d, EPI == EPI_ACC_F32, &pick, &ns);
+  if (g_forced_tile) {
+    pick = g_forced_tile;
+    ns = 2;
   }
   switch (pick) {
-    case 44: return launch_cfg<4, 4, A_K, B_K, EPI>(s, d);
-    case 42: return launch_cfg<4, 2, A_K, B_K, EPI>(s, d);
-    case 24: return launch_cfg<2, 4, A_K, B_K, EPI>(s, d);
-    case 22: return launch_cfg<2, 2, A_K, B_K, EPI>(s, d);
-    case 11: return launch_cfg<1, 1, A_K, B_K, EPI>(s, d);
+    case 44: return launch_cfg<4, 4, A_K, B_K, EPI>(s, d, ns);
+    case 42: return launch_cfg<4, 2, A_K, B_K, EPI>(s, d, ns);
+    case 24: return launch_cfg<2, 4, A_K, B_K, EPI>(s, d, ns);
+    case 22: return launch_cfg<2, 2, A_K, B_K, EPI>(s, d, ns);
+    case 11: return launch_cfg<1, 1, A_K, B_K, EPI>(s, d, ns);
     default: return hipErrorInvalidValue;
   }
 }
