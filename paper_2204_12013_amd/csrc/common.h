@@ -132,6 +132,20 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const vo
 hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial);
 // out[n] += sum over the first `parts` rows of partial[parts][N], in order
 hipError_t launch_colsum_final(hipStream_t s, int N, int parts, const float* partial, float* out);
+// The two halves of the calls above, for callers that batch the final sums of several reductions:
+// the *_partials launchers write partial rows only (row count returned through *parts; at most
+// reduce_max_partials() rows of N floats), launch_grad_reduce then adds the ordered sums of up to
+// eight partial sets to their fp32 destinations in one launch.
+hipError_t launch_layernorm_bwd_partials(hipStream_t s, int dtype, int T, int H, const void* dout, const void* r,
+                                         const float* stats, const void* gamma, const void* add, void* dr, float* pg,
+                                         float* pb, float* pc, int* parts);
+hipError_t launch_colsum_partials(hipStream_t s, int dtype, int T, int N, const void* a, float* partial, int* parts);
+struct GradReduceSeg { const float* p0; float* out0; const float* p1; float* out1; int N, parts, block0; };
+struct GradReduceBatch { GradReduceSeg seg[8]; int n; };
+// appends out0[c] += sum_y p0[y][c] (and the same for the optional second pair p1/out1); false when full
+bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, float* out0, const float* p1, float* out1);
+hipError_t launch_grad_reduce(hipStream_t s, const GradReduceBatch& b);
+size_t reduce_max_partials();
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);

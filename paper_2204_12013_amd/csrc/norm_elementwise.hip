@@ -166,17 +166,20 @@ __global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, in
                                                                   const float* __restrict__ stats,
                                                                   const T* __restrict__ gamma,
                                                                   const T* __restrict__ add, T* __restrict__ dr,
-                                                                  float* __restrict__ pg, float* __restrict__ pb) {
+                                                                  float* __restrict__ pg, float* __restrict__ pb,
+                                                                  float* __restrict__ pc) {
   constexpr int V = Vec<T>::N;
   extern __shared__ float red[];                 // [4][H]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nvec = H / V;
-  float g[NCH][V], ag[NCH][V], ab[NCH][V];
+  // pc (optional): column sums of the stored output dr, i.e. the bias gradient of the linear
+  // layer whose output gradient dr is
+  float g[NCH][V], ag[NCH][V], ab[NCH][V], ac[NCH][V];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int c = lane + 64 * j;
 #pragma unroll
-    for (int i = 0; i < V; ++i) { g[j][i] = 0.f; ag[j][i] = 0.f; ab[j][i] = 0.f; }
+    for (int i = 0; i < V; ++i) { g[j][i] = 0.f; ag[j][i] = 0.f; ab[j][i] = 0.f; ac[j][i] = 0.f; }
     if (c < nvec) Vec<T>::load(gamma + c * V, g[j]);
   }
   const int row_end = min(T_rows, (int)(blockIdx.x + 1) * rows_per_block);
@@ -219,23 +222,28 @@ __global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, in
           for (int i = 0; i < V; ++i) o[i] += a[i];
         }
         Vec<T>::store(dr + off + c * V, o);
+        if (pc != nullptr) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) ac[j][i] += round_storage<T>(o[i]);
+        }
       }
     }
   }
-  // ordered reduction of the four wavefronts, gain gradient then shift gradient
+  // ordered reduction of the four wavefronts: gain gradient, shift gradient, output column sums
 #pragma unroll
-  for (int which = 0; which < 2; ++which) {
+  for (int which = 0; which < 3; ++which) {
+    if (which == 2 && pc == nullptr) break;
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = lane + 64 * j;
       if (c < nvec) {
 #pragma unroll
-        for (int i = 0; i < V; ++i) red[w * H + c * V + i] = which == 0 ? ag[j][i] : ab[j][i];
+        for (int i = 0; i < V; ++i) red[w * H + c * V + i] = which == 0 ? ag[j][i] : (which == 1 ? ab[j][i] : ac[j][i]);
       }
     }
     __syncthreads();
-    float* out = (which == 0 ? pg : pb) + (long)blockIdx.x * H;
+    float* out = (which == 0 ? pg : (which == 1 ? pb : pc)) + (long)blockIdx.x * H;
     for (int c = threadIdx.x; c < H; c += 256) out[c] = ((red[c] + red[H + c]) + red[2 * H + c]) + red[3 * H + c];
   }
 }
@@ -374,6 +382,58 @@ __global__ __launch_bounds__(1024) void colreduce_final_kernel(int N, int splits
   }
 }
 
+// The same ordered final sum for up to eight reductions in one launch (the parameter-gradient
+// reductions of one layer's backward): workgroup b serves the segment whose block range holds b.
+__global__ __launch_bounds__(1024) void colreduce_final_batch_kernel(GradReduceBatch batch) {
+  __shared__ float red[2][kFinalWaves][64];
+  int si = 0;
+#pragma unroll
+  for (int k = 1; k < 8; ++k)
+    if (k < batch.n && (int)blockIdx.x >= batch.seg[k].block0) si = k;
+  const GradReduceSeg sg = batch.seg[si];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = ((int)blockIdx.x - sg.block0) * 64 + lane;
+  const int per = (sg.parts + kFinalWaves - 1) / kFinalWaves;
+  float s = 0.f, q = 0.f;
+  if (c < sg.N) {
+    const int y_end = min(sg.parts, (w + 1) * per);
+#pragma unroll 8
+    for (int y = w * per; y < y_end; ++y) s += sg.p0[(long)y * sg.N + c];
+    if (sg.p1 != nullptr) {
+#pragma unroll 8
+      for (int y = w * per; y < y_end; ++y) q += sg.p1[(long)y * sg.N + c];
+    }
+  }
+  red[0][w][lane] = s;
+  red[1][w][lane] = q;
+  __syncthreads();
+  if (w == 0 && c < sg.N) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int k = 0; k < kFinalWaves; ++k) {
+      a += red[0][k][lane];
+      b += red[1][k][lane];
+    }
+    sg.out0[c] += a;
+    if (sg.p1 != nullptr) sg.out1[c] += b;
+  }
+}
+
+bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, float* out0, const float* p1, float* out1) {
+  if (b->n >= 8) return false;
+  GradReduceSeg& sg = b->seg[b->n];
+  sg.p0 = p0; sg.out0 = out0; sg.p1 = p1; sg.out1 = out1; sg.N = N; sg.parts = parts;
+  sg.block0 = b->n == 0 ? 0 : b->seg[b->n - 1].block0 + (b->seg[b->n - 1].N + 63) / 64;
+  ++b->n;
+  return true;
+}
+hipError_t launch_grad_reduce(hipStream_t s, const GradReduceBatch& b) {
+  if (b.n <= 0) return hipSuccess;
+  const int blocks = b.seg[b.n - 1].block0 + (b.seg[b.n - 1].N + 63) / 64;
+  hipLaunchKernelGGL(colreduce_final_batch_kernel, dim3(blocks), dim3(1024), 0, s, b);
+  return hipGetLastError();
+}
+
 // rows per workgroup and number of workgroups along the token axis
 static void split_rows(int T, int max_blocks, int* rows_per_block, int* blocks) {
   int rpb = (T + max_blocks - 1) / max_blocks;
@@ -386,11 +446,12 @@ hipError_t launch_colsum_final(hipStream_t s, int N, int parts, const float* par
                      (const float*)nullptr, (float*)nullptr);
   return hipGetLastError();
 }
+size_t reduce_max_partials() { return kMaxPartials; }
 size_t colsum_partial_floats(int N) { return (size_t)kMaxPartials * N; }
 size_t ln_bwd_partial_floats(int H) { return (size_t)2 * kMaxPartials * H; }
 
 template <typename T>
-static hipError_t colsum_impl(hipStream_t s, int T_rows, int N, const void* a, float* out, float* partial) {
+static hipError_t colsum_partials_impl(hipStream_t s, int T_rows, int N, const void* a, float* partial, int* parts) {
   constexpr int V = Vec<T>::N;
   const int col_blocks = (N + 64 * V - 1) / (64 * V);
   int max_blocks = 512 / col_blocks;            // about two workgroups per CU in total
@@ -400,22 +461,29 @@ static hipError_t colsum_impl(hipStream_t s, int T_rows, int N, const void* a, f
   split_rows(T_rows, max_blocks, &rpb, &rb);
   hipLaunchKernelGGL((colreduce_kernel<T, 0>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, N, rpb, (const T*)a,
                      (const T*)nullptr, (const float*)nullptr, partial, (float*)nullptr);
-  hipLaunchKernelGGL(colreduce_final_kernel, dim3((N + 63) / 64), dim3(1024), 0, s, N, rb, partial, out,
-                     (const float*)nullptr, (float*)nullptr);
+  *parts = rb;
   return hipGetLastError();
 }
 
-hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial) {
-  return dtype == 0 ? colsum_impl<float>(s, T, N, a, out, partial) : colsum_impl<bf16_t>(s, T, N, a, out, partial);
+hipError_t launch_colsum_partials(hipStream_t s, int dtype, int T, int N, const void* a, float* partial, int* parts) {
+  return dtype == 0 ? colsum_partials_impl<float>(s, T, N, a, partial, parts)
+                    : colsum_partials_impl<bf16_t>(s, T, N, a, partial, parts);
 }
 
+hipError_t launch_colsum_acc(hipStream_t s, int dtype, int T, int N, const void* a, float* out, float* partial) {
+  int parts = 0;
+  const hipError_t e = launch_colsum_partials(s, dtype, T, N, a, partial, &parts);
+  if (e != hipSuccess) return e;
+  return launch_colsum_final(s, N, parts, partial, out);
+}
+
+// dr and the partial rows of the gain / shift gradients (pg, pb: kMaxPartials x H floats each) and,
+// if pc != nullptr, of the column sums of dr; the number of partial rows written comes back in *parts
 template <typename T>
-static hipError_t ln_bwd_impl(hipStream_t s, int T_rows, int H, const void* dout, const void* r, const float* stats,
-                              const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta,
-                              float* partial) {
+static hipError_t ln_bwd_partials_impl(hipStream_t s, int T_rows, int H, const void* dout, const void* r,
+                                       const float* stats, const void* gamma, const void* add, void* dr, float* pg,
+                                       float* pb, float* pc, int* parts) {
   constexpr int V = Vec<T>::N;
-  float* p0 = partial;
-  float* p1 = partial + (size_t)kMaxPartials * H;
   const int nch = (H / V + 63) / 64;
   int rpb, rb;
   if (nch <= 4 && (size_t)4 * H * sizeof(float) <= 48 * 1024) {
@@ -423,7 +491,7 @@ static hipError_t ln_bwd_impl(hipStream_t s, int T_rows, int H, const void* dout
     const size_t sh = (size_t)4 * H * sizeof(float);
 #define LN_BWD(K)                                                                                                  \
   hipLaunchKernelGGL(K, dim3(rb), dim3(256), sh, s, T_rows, H, rpb, (const T*)dout, (const T*)r, stats,          \
-                     (const T*)gamma, (const T*)add, (T*)dr, p0, p1)
+                     (const T*)gamma, (const T*)add, (T*)dr, pg, pb, pc)
     if (nch <= 1) LN_BWD((layernorm_bwd_fused_kernel<T, 1>));
     else if (nch <= 2) LN_BWD((layernorm_bwd_fused_kernel<T, 2>));
     else LN_BWD((layernorm_bwd_fused_kernel<T, 4>));
@@ -435,19 +503,35 @@ static hipError_t ln_bwd_impl(hipStream_t s, int T_rows, int H, const void* dout
     if (max_blocks < 1) max_blocks = 1;
     split_rows(T_rows, max_blocks, &rpb, &rb);
     hipLaunchKernelGGL((colreduce_kernel<T, 1>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, H, rpb, (const T*)dout,
-                       (const T*)r, stats, p0, p1);
+                       (const T*)r, stats, pg, pb);
     hipLaunchKernelGGL(layernorm_bwd_kernel<T>, dim3((T_rows + 3) / 4), dim3(256), 0, s, T_rows, H, (const T*)dout,
                        (const T*)r, stats, (const T*)gamma, (const T*)add, (T*)dr);
+    if (pc != nullptr)   // same row split, so all three partial sets have rb rows
+      hipLaunchKernelGGL((colreduce_kernel<T, 0>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, H, rpb,
+                         (const T*)dr, (const T*)nullptr, (const float*)nullptr, pc, (float*)nullptr);
   }
-  hipLaunchKernelGGL(colreduce_final_kernel, dim3((H + 63) / 64), dim3(1024), 0, s, H, rb, p0, dgamma, p1, dbeta);
+  *parts = rb;
   return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd_partials(hipStream_t s, int dtype, int T, int H, const void* dout, const void* r,
+                                         const float* stats, const void* gamma, const void* add, void* dr, float* pg,
+                                         float* pb, float* pc, int* parts) {
+  return dtype == 0 ? ln_bwd_partials_impl<float>(s, T, H, dout, r, stats, gamma, add, dr, pg, pb, pc, parts)
+                    : ln_bwd_partials_impl<bf16_t>(s, T, H, dout, r, stats, gamma, add, dr, pg, pb, pc, parts);
 }
 
 hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const void* dout, const void* r,
                                 const float* stats, const void* gamma, const void* add, void* dr, float* dgamma,
                                 float* dbeta, float* partial) {
-  return dtype == 0 ? ln_bwd_impl<float>(s, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial)
-                    : ln_bwd_impl<bf16_t>(s, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial);
+  float* p0 = partial;
+  float* p1 = partial + (size_t)kMaxPartials * H;
+  int parts = 0;
+  const hipError_t e =
+      launch_layernorm_bwd_partials(s, dtype, T, H, dout, r, stats, gamma, add, dr, p0, p1, nullptr, &parts);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colreduce_final_kernel, dim3((H + 63) / 64), dim3(1024), 0, s, H, parts, p0, dgamma, p1, dbeta);
+  return hipGetLastError();
 }
 
 // --------------------------------------------------------------------- copy

@@ -86,7 +86,10 @@ RecordLayout record_layout(const bamboo_cfg_t& c) {
 // Scratch of one lane.  Lane 1 only ever runs forwards: it needs g (GELU output)
 // and out (where an output the caller does not want is written).
 struct LaneScratch {
-  uint64_t g, out, dh, d1, d2, dctx, ping, pong, dqkv, delta, partial, bytes;
+  uint64_t g, out, dh, d1, d2, dctx, ping, pong, dqkv, delta, bytes;
+  // partial rows of one layer's parameter-gradient reductions (summed by one launch at the layer's end):
+  // LayerNorm 1 and 2 (gain, shift, column sums of the output), and the column sums of dh, dqkv, df
+  uint64_t p_ln[2][3], p_dh, p_dqkv, p_df;
 };
 LaneScratch lane_scratch(const bamboo_cfg_t& c, bool backward) {
   const uint64_t es = c.dtype == BAMBOO_BF16 ? 2 : 4;
@@ -105,10 +108,12 @@ LaneScratch lane_scratch(const bamboo_cfg_t& c, bool backward) {
     w.pong = o; o = align_up(o + T * H * es);
     w.dqkv = o; o = align_up(o + T * 3 * H * es);
     w.delta = o; o = align_up(o + (uint64_t)c.micro_batch * c.heads * c.seq * 4);
-    const uint64_t widest = 3 * H > F ? 3 * H : F;
-    uint64_t pf = colsum_partial_floats((int)widest);
-    if (ln_bwd_partial_floats((int)H) > pf) pf = ln_bwd_partial_floats((int)H);
-    w.partial = o; o = align_up(o + pf * 4);
+    const uint64_t rows = reduce_max_partials();
+    for (int a = 0; a < 2; ++a)
+      for (int b = 0; b < 3; ++b) { w.p_ln[a][b] = o; o = align_up(o + rows * H * 4); }
+    w.p_dh = o; o = align_up(o + rows * F * 4);
+    w.p_dqkv = o; o = align_up(o + rows * 3 * H * 4);
+    w.p_df = o; o = align_up(o + rows * H * 4);
   }
   w.bytes = o;
   return w;
@@ -239,15 +244,36 @@ int p_ln_fwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* r, const
   HIPCHK(launch_layernorm_fwd(s, st->cfg.dtype, T, H, st->cfg.ln_eps, r, g, b, y, stats));
   return BAMBOO_OK;
 }
+// LayerNorm backward: dr, plus partial rows of the gain / shift gradients and (pc != nullptr) of the
+// column sums of dr; their ordered final sums into dgamma / dbeta / dbias are queued in `batch`
 int p_ln_bwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* dout, const void* r, const float* stats,
-             const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta, float* partial) {
+             const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta, float* dbias,
+             const uint64_t (&poff)[3], GradReduceBatch* batch) {
   ProfScope ps(st, K_LN_BWD, s, (double)T * ((add ? 4.0 : 3.0) * H * esize(st) + 8.0));
-  HIPCHK(launch_layernorm_bwd(s, st->cfg.dtype, T, H, dout, r, stats, gamma, add, dr, dgamma, dbeta, partial));
+  float* pg = (float*)(st->wsbase + poff[0]);
+  float* pb = (float*)(st->wsbase + poff[1]);
+  float* pc = dbias ? (float*)(st->wsbase + poff[2]) : nullptr;
+  int parts = 0;
+  HIPCHK(launch_layernorm_bwd_partials(s, st->cfg.dtype, T, H, dout, r, stats, gamma, add, dr, pg, pb, pc, &parts));
+  if (!grad_reduce_add(batch, H, parts, pg, dgamma, pb, dbeta)) return BAMBOO_E_STATE;
+  if (dbias && !grad_reduce_add(batch, H, parts, pc, dbias, nullptr, nullptr)) return BAMBOO_E_STATE;
   return BAMBOO_OK;
 }
-int p_colsum(bamboo_stage* st, hipStream_t s, int T, int N, const void* a, float* out, float* partial) {
+// partial rows of the column sums of a[T,N]; the final sum into `out` is queued in `batch`
+int p_colsum(bamboo_stage* st, hipStream_t s, int T, int N, const void* a, float* out, uint64_t poff,
+             GradReduceBatch* batch) {
   ProfScope ps(st, K_COLSUM, s, (double)T * N * esize(st));
-  HIPCHK(launch_colsum_acc(s, st->cfg.dtype, T, N, a, out, partial));
+  float* p = (float*)(st->wsbase + poff);
+  int parts = 0;
+  HIPCHK(launch_colsum_partials(s, st->cfg.dtype, T, N, a, p, &parts));
+  if (!grad_reduce_add(batch, N, parts, p, out, nullptr, nullptr)) return BAMBOO_E_STATE;
+  return BAMBOO_OK;
+}
+int p_grad_reduce(bamboo_stage* st, hipStream_t s, const GradReduceBatch& batch) {
+  double bytes = 0.0;
+  for (int i = 0; i < batch.n; ++i) bytes += (double)batch.seg[i].parts * batch.seg[i].N * 4.0 * (batch.seg[i].p1 ? 2 : 1);
+  ProfScope ps(st, K_COLSUM, s, bytes);
+  HIPCHK(launch_grad_reduce(s, batch));
   return BAMBOO_OK;
 }
 
@@ -267,13 +293,11 @@ GemmDesc gemm_nt(const void* dY, const void* W, void* dX, int T, int Kw, int Nw,
   return d;
 }
 // dW[Kw,Nw] += X[T,Kw]^T * dY[T,Nw]
-// and, in the same pass over dY, db[Nw] += column sums of dY
-GemmDesc gemm_tn(const void* X, const void* dY, float* dW, float* db, float* partial, int T, int Kw, int Nw) {
+GemmDesc gemm_tn(const void* X, const void* dY, float* dW, int T, int Kw, int Nw) {
   GemmDesc d;
   memset(&d, 0, sizeof(d));
   d.A = X; d.B = dY; d.C = dW; d.M = Kw; d.N = Nw; d.K = T;
   d.a_sm = 1; d.a_sk = Kw; d.b_sk = Nw; d.b_sn = 1; d.epi = EPI_ACC_F32;
-  d.colsum_out = db; d.colsum_partial = partial;
   return d;
 }
 
@@ -355,7 +379,6 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
   void* d2 = ws + w.d2;
   void* dctx = ws + w.dctx;
   void* dqkv = ws + w.dqkv;
-  float* partial = (float*)(ws + w.partial);
   const RecordLayout& r = st->rl;
   char* rec0 = st->stash[kind] + (uint64_t)slot * n * r.bytes;
   const void* dy = gy;
@@ -372,43 +395,51 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     a.causal = c.arch == BAMBOO_ARCH_PRE_LN_CAUSAL;
     a.qkv = rec + r.qkv; a.ctx = rec + r.ctx; a.lse = (float*)(rec + r.lse);
     a.dctx = dctx; a.dqkv = dqkv; a.delta = (float*)(ws + w.delta);
+    // Every reduction over tokens of this layer (LayerNorm gain / shift gradients, the four bias
+    // gradients) leaves partial rows in the workspace; one launch at the end adds their ordered sums
+    // to the gradients.  A bias gradient whose dY comes out of a LayerNorm backward is reduced there.
+    GradReduceBatch batch;
+    batch.n = 0;
     GemmDesc d;
     const void* df;     // gradient at the FFN output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       BBCHK(p_ln_bwd(st, s, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
-                                  G + st->po.g2, G + st->po.be2, partial));
+                     G + st->po.g2, G + st->po.be2, G + st->po.b2, w.p_ln[1], &batch));
       df = d1;
     } else {
       df = dy;
+      BBCHK(p_colsum(st, s, T, H, df, G + st->po.b2, w.p_df, &batch));
     }
-    // f = g W2 + b2 (the bias gradients ride along with the weight-gradient GEMMs)
+    // f = g W2 + b2
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_DGELU);
     d.aux_in = rec + r.h;
     d.aux_out = gbuf;
     BBCHK(p_gemm(st, s, d));
-    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, G + st->po.b2, partial, T, F, H)));
+    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
     // h = fin W1 + b1
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, G + st->po.b1, partial, T, H, F)));
+    BBCHK(p_colsum(st, s, T, F, dh, G + st->po.b1, w.p_dh, &batch));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
       d.res = d1;
       BBCHK(p_gemm(st, s, d));
       BBCHK(p_ln_bwd(st, s, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
-                                  G + st->po.g1, G + st->po.be1, partial));
+                     G + st->po.g1, G + st->po.be1, G + st->po.bo, w.p_ln[0], &batch));
       da = d1;
     } else {
       BBCHK(p_gemm(st, s, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
       BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
-                                  G + st->po.g2, G + st->po.be2, partial));   // + residual branch of y = x1 + f
+                     G + st->po.g2, G + st->po.be2, G + st->po.bo, w.p_ln[1], &batch));   // + residual branch of y = x1 + f
       da = d2;
     }
     // a = ctx Wo + bo
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, G + st->po.bo, partial, T, H, H)));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
     BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
     BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, G + st->po.bqkv, partial, T, H, 3 * H)));
+    BBCHK(p_colsum(st, s, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
       d.res = da;
@@ -416,8 +447,9 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     } else {
       BBCHK(p_gemm(st, s, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
       BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
-                                  G + st->po.g1, G + st->po.be1, partial));   // + residual branch of x1 = x + a
+                     G + st->po.g1, G + st->po.be1, nullptr, w.p_ln[0], &batch));   // + residual branch of x1 = x + a
     }
+    BBCHK(p_grad_reduce(st, s, batch));
     dy = dx;
   }
   return BAMBOO_OK;
