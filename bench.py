@@ -84,8 +84,9 @@ def main():
     ap.add_argument("--workload", default="bert_large_stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-modes", action="store_true", help="time mode B only (for profiler runs)")
-    ap.add_argument("--profile-frc-off", action="store_true",
-                    help="run the per-kernel-class pass without FRC (one lane: kernel times free of contention)")
+    ap.add_argument("--profile-two-lanes", action="store_true",
+                    help="run the per-kernel-class pass with FRC on (two lanes: a kernel's event time then "
+                         "includes the time it shares the GPU with the other lane's kernels)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 256 MiB device copy (yardstick for the HBM byte counters)")
     args = ap.parse_args()
@@ -174,10 +175,12 @@ def main():
                               "ms_per_step_frc_on": ms_c_on,
                               "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
 
-    # per-kernel-class roofline: the same iteration with an event pair around every launch
+    # per-kernel-class roofline: the iteration again with an event pair around every launch, on the
+    # launch's own stream.  By default FRC is left out of this pass: with two lanes active a kernel
+    # shares the GPU with the other lane's kernels and its event time is no longer its own.
     st.stage_profile(True)
     k_p = max(1, min(args.steps, 3))
-    run_iters(prog_off if args.profile_frc_off else prog_on, k_p)
+    run_iters(prog_on if args.profile_two_lanes else prog_off, k_p)
     classes = {}
     for i, name in enumerate(B.KERNEL_CLASSES):
         ms, n, work = st.stage_profile_read(i)
@@ -194,7 +197,10 @@ def main():
                        "achieved": achieved, "peak": PEAK["mfma_bf16"] / 1e12, "unit": "TFLOP/s",
                        "frac": achieved * 1e12 / PEAK["mfma_bf16"], "traffic": _profiled_traffic(sc.name),
                        "launches_per_step": g_n // k_p, "avg_launch_us": g_ms * 1e3 / g_n,
-                       "flops_per_launch": g_work / g_n}
+                       "flops_per_launch": g_work / g_n,
+                       "measured": "HIP event pair around every GEMM launch of %d iteration(s), %s"
+                                   % (k_p, "FRC on (two lanes)" if args.profile_two_lanes else
+                                      "FRC off (one lane, no contention between lanes)")}
     out["mfma_util_stage_gemms"] = out["roofline"]["frac"]
     out["kernel_classes"] = {
         k: {"avg_us": v["avg_us"], "launches_per_step": v["launches"] // k_p, "ms_per_step": v["total_ms_per_step"],
