@@ -23,16 +23,18 @@ extern "C" {
 #endif
 
 /* Y[T,N] = X[T,K] W[K,N] + bias[N] (+ res[T,N] if res != NULL).
- * If gelu_out != NULL: Y holds the pre-activation h (rounded to storage) and
- * gelu_out[T,N] = GELU(h) (erf form) of the stored value. */
+ * If gelu_out != NULL (and res == NULL), with h = X W + bias kept in fp32:
+ * gelu_out[T,N] = GELU(h) (erf form) and Y[T,N] = GELU'(h), the factor the
+ * backward multiplies the incoming gradient by (so GELU is evaluated once, in
+ * the forward, and the pre-activation itself is not kept). */
 int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const void* W, const void* bias,
                   const void* res, void* Y, void* gelu_out, void* stream);
 
 /* dX[T,K] = dY[T,N] W[K,N]^T (+ res[T,K] if res != NULL).
- * If h_in != NULL (and res == NULL): dX = (dY W^T) * GELU'(h_in[T,K]) and
- * gelu_out[T,K] = GELU(h_in). */
+ * If mul != NULL (and res == NULL): dX = (dY W^T) * mul[T,K] elementwise (the
+ * backward through an activation whose derivative the forward stored). */
 int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY, const void* W, const void* res,
-                        const void* h_in, void* dX, void* gelu_out, void* stream);
+                        const void* mul, void* dX, void* stream);
 
 /* dW[K,N] (fp32) += X[T,K]^T dY[T,N]; if db != NULL also db[N] (fp32) += sum over
  * tokens of dY (the bias gradient of the same linear layer), with

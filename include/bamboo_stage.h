@@ -152,11 +152,12 @@ int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot,
  * out[2] qkv    [T,3H]      out[3] ctx [T,H] (attention output before Wo)
  * out[4] r1     x + attention block [T,H]
  * out[5] fin    FFN input [T,H] (post-LN: LN1(r1); pre-LN: LN2(r1))
- * out[6] h      FFN pre-activation [T,F]
- * out[7] r2     post-LN only: fin + ffn [T,H] (0 otherwise)
- * out[8] lse    fp32 [batch,heads,seq]   out[9], out[10] LN1, LN2 (mean, rstd) fp32 [T,2]
- * out[11] rec_bytes.  Activations are in the storage dtype.  host pointers. */
-int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[12]);
+ * out[6] g      GELU(h) [T,F], h = fin W1 + b1 the FFN pre-activation (not kept itself)
+ * out[7] dg     GELU'(h) [T,F]: what the backward multiplies the gradient of g by
+ * out[8] r2     post-LN only: fin + ffn [T,H] (0 otherwise)
+ * out[9] lse    fp32 [batch,heads,seq]   out[10], out[11] LN1, LN2 (mean, rstd) fp32 [T,2]
+ * out[12] rec_bytes.  Activations are in the storage dtype.  host pointers. */
+int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[13]);
 
 const char* stage_strerror(int status);
 

@@ -71,7 +71,7 @@ _SIGS = {
     "stage_profile": (C.c_int, [_vp, C.c_int]),
     "stage_profile_read": (C.c_int, [_vp, _i32, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]),
     "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
-    "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
+    "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
     "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
     "bk_colsum_acc": (C.c_int, [C.c_int] * 3 + [_vp] * 4),
     "bk_colsum_scratch_floats": (C.c_uint64, [C.c_int]),
@@ -134,11 +134,11 @@ def stage_record_offset(cfg, kind, slot, layer):
     return _check(lib.stage_record_offset(C.byref(cfg), kind, slot, layer), "stage_record_offset")
 
 
-RECORD_FIELDS = ("x", "ain", "qkv", "ctx", "r1", "fin", "h", "r2", "lse", "ln1", "ln2", "rec_bytes")
+RECORD_FIELDS = ("x", "ain", "qkv", "ctx", "r1", "fin", "g", "dg", "r2", "lse", "ln1", "ln2", "rec_bytes")
 
 
 def stage_record_fields(cfg):
-    arr = (C.c_uint64 * 12)()
+    arr = (C.c_uint64 * 13)()
     _check(lib.stage_record_fields(C.byref(cfg), arr), "stage_record_fields")
     return dict(zip(RECORD_FIELDS, [int(v) for v in arr]))
 
@@ -196,7 +196,7 @@ class Stage:
         if field in ("lse", "ln1", "ln2"):
             n = cfg.micro_batch * cfg.heads * cfg.seq if field == "lse" else 2 * T
             return arena[base:base + 4 * n].view(torch.float32)
-        cols = {"qkv": 3 * H, "h": F}.get(field, H)
+        cols = {"qkv": 3 * H, "g": F, "dg": F}.get(field, H)
         return arena[base:base + es * T * cols].view(self.act_dtype).view(T, cols)
 
     def new_act(self):
@@ -285,11 +285,11 @@ def bk_linear_fwd(X, W, bias, Y, res=None, gelu_out=None, impl=0, stream=None):
                              _ptr(gelu_out), _stream(stream)), "bk_linear_fwd")
 
 
-def bk_linear_bwd_input(dY, W, dX, res=None, h_in=None, gelu_out=None, impl=0, stream=None):
+def bk_linear_bwd_input(dY, W, dX, res=None, mul=None, impl=0, stream=None):
     T, N = dY.shape
     K = W.shape[0]
-    _check(lib.bk_linear_bwd_input(_dt(dY), impl, T, K, N, _ptr(dY), _ptr(W), _ptr(res), _ptr(h_in), _ptr(dX),
-                                   _ptr(gelu_out), _stream(stream)), "bk_linear_bwd_input")
+    _check(lib.bk_linear_bwd_input(_dt(dY), impl, T, K, N, _ptr(dY), _ptr(W), _ptr(res), _ptr(mul), _ptr(dX),
+                                   _stream(stream)), "bk_linear_bwd_input")
 
 
 def bk_linear_bwd_weight(X, dY, dW, db=None, impl=0, stream=None):

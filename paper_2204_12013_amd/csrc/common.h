@@ -64,9 +64,9 @@ enum Epilogue : int {
   EPI_STORE = 0,      // C = acc
   EPI_BIAS = 1,       // C = acc + bias[n]
   EPI_BIAS_RES = 2,   // C = acc + bias[n] + res[m,n]
-  EPI_BIAS_GELU = 3,  // C = h = acc + bias[n] (stored), aux_out = gelu(stored h)
+  EPI_BIAS_GELU = 3,  // h = acc + bias[n] (fp32): aux_out = gelu(h), C = gelu'(h)
   EPI_RES = 4,        // C = acc + res[m,n]
-  EPI_DGELU = 5,      // C = acc * gelu'(aux_in[m,n]); aux_out = gelu(aux_in[m,n])
+  EPI_MUL = 5,        // C = acc * aux_in[m,n]
   EPI_ACC_F32 = 6     // C (fp32) += acc
 };
 

@@ -142,16 +142,16 @@ __device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks)
 // The accumulators leave through a wavefront-private LDS staging area; afterwards lane l of a wave
 // owns, for row block i and pass `it`, the 8 consecutive outputs of chunk idx = l + 64 * it of the
 // staged 32 x (32 * WN) block (row idx / CHUNKS, columns 8 * (idx % CHUNKS) ..).  What the epilogue
-// has to read from memory for those outputs (residual, stored pre-activation, fp32 gradient to add
-// to) can therefore be fetched long before the accumulators are final: EpiOperands::issue is
+// has to read from memory for those outputs (residual, stored activation derivative, fp32 gradient
+// to add to) can therefore be fetched long before the accumulators are final: EpiOperands::issue is
 // called ahead of the last slices of the main loop, so the latency is covered by MFMAs.
 template <int WM, int WN, int EPI>
 struct EpiOperands {
   static constexpr int CHUNKS = 4 * WN, ITS = 32 * CHUNKS / 64;
   // only where the operands fit in 64 registers per lane; larger tiles read them in the epilogue itself
-  static constexpr bool BF = (EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_DGELU) && WM * ITS * 4 <= 64;
+  static constexpr bool BF = (EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL) && WM * ITS * 4 <= 64;
   static constexpr bool F32 = EPI == EPI_ACC_F32 && WM * ITS * 8 <= 64;
-  static constexpr bool NEEDS = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_DGELU || EPI == EPI_ACC_F32;
+  static constexpr bool NEEDS = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL || EPI == EPI_ACC_F32;
   static constexpr bool PRE = BF || F32;
   static constexpr int NLOADS = BF ? WM * ITS : (F32 ? 2 * WM * ITS : 0);   // load instructions per lane
   bf16x8 b[BF ? WM : 1][BF ? ITS : 1];
@@ -162,7 +162,7 @@ struct EpiOperands {
     if (!BF && !F32) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
-    const void* src = EPI == EPI_DGELU ? d.aux_in : (F32 ? (const void*)d.C : d.res);
+    const void* src = EPI == EPI_MUL ? d.aux_in : (F32 ? (const void*)d.C : d.res);
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -187,7 +187,7 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
   const long i = (long)m * d.N + n;
   bf16x8 pb = pb_in;
   if (!PRE && (EPI == EPI_BIAS_RES || EPI == EPI_RES)) pb = *(const bf16x8*)((const bf16_t*)d.res + i);
-  if (!PRE && EPI == EPI_DGELU) pb = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
+  if (!PRE && EPI == EPI_MUL) pb = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
     f32x4 a = pf_in[0], b = pf_in[1];
@@ -211,14 +211,17 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
     for (int j = 0; j < 8; ++j) v[j] += (float)pb[j];
   }
   bf16x8 o;
-  if (EPI == EPI_DGELU) {
+  if (EPI == EPI_MUL) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = (bf16_t)(v[j] * (float)pb[j]);
+  } else if (EPI == EPI_BIAS_GELU) {
     bf16x8 g;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < 8; ++j) {   // activation and its derivative from the fp32 pre-activation
       float gv, dgv;
-      gelu_pair_fast((float)pb[j], &gv, &dgv);
-      o[j] = (bf16_t)(v[j] * dgv);
+      gelu_pair_fast(v[j], &gv, &dgv);
       g[j] = (bf16_t)gv;
+      o[j] = (bf16_t)dgv;
     }
     *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
   } else {
@@ -226,16 +229,6 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
     for (int j = 0; j < 8; ++j) o[j] = (bf16_t)v[j];
   }
   *(bf16x8*)((bf16_t*)d.C + i) = o;
-  if (EPI == EPI_BIAS_GELU) {
-    bf16x8 g;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {   // GELU of the stored (rounded) h
-      float gv, dgv;
-      gelu_pair_fast((float)o[j], &gv, &dgv);
-      g[j] = (bf16_t)gv;
-    }
-    *(bf16x8*)((bf16_t*)d.aux_out + i) = g;
-  }
 }
 
 // Accumulators -> wavefront-private LDS rows -> 16-byte global accesses.
@@ -794,7 +787,7 @@ hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {
     switch (d.epi) {
       case EPI_STORE: return launch_form<true, true, EPI_STORE>(s, d);
       case EPI_RES: return launch_form<true, true, EPI_RES>(s, d);
-      case EPI_DGELU: return launch_form<true, true, EPI_DGELU>(s, d);
+      case EPI_MUL: return launch_form<true, true, EPI_MUL>(s, d);
       default: return hipErrorNotSupported;
     }
   }

@@ -20,20 +20,17 @@ __device__ __forceinline__ void epilogue_store(const GemmDesc& d, int m, int n, 
       ((T*)d.C)[i] = from_f32<T>(acc + to_f32<T>(((const T*)d.bias)[n]) + to_f32<T>(((const T*)d.res)[i]));
       break;
     case EPI_BIAS_GELU: {
-      const T h = from_f32<T>(acc + to_f32<T>(((const T*)d.bias)[n]));
-      ((T*)d.C)[i] = h;
-      ((T*)d.aux_out)[i] = from_f32<T>(gelu_f(to_f32<T>(h)));
+      const float h = acc + to_f32<T>(((const T*)d.bias)[n]);
+      ((T*)d.C)[i] = from_f32<T>(gelu_grad_f(h));
+      ((T*)d.aux_out)[i] = from_f32<T>(gelu_f(h));
       break;
     }
     case EPI_RES:
       ((T*)d.C)[i] = from_f32<T>(acc + to_f32<T>(((const T*)d.res)[i]));
       break;
-    case EPI_DGELU: {
-      const float h = to_f32<T>(((const T*)d.aux_in)[i]);
-      ((T*)d.C)[i] = from_f32<T>(acc * gelu_grad_f(h));
-      ((T*)d.aux_out)[i] = from_f32<T>(gelu_f(h));
+    case EPI_MUL:
+      ((T*)d.C)[i] = from_f32<T>(acc * to_f32<T>(((const T*)d.aux_in)[i]));
       break;
-    }
     case EPI_ACC_F32:
       ((float*)d.C)[i] += acc;
       break;

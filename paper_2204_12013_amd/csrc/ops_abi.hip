@@ -32,7 +32,7 @@ extern "C" {
 
 int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const void* W, const void* bias,
                   const void* res, void* Y, void* gelu_out, void* stream) {
-  if (!bias || (res && gelu_out)) return BAMBOO_E_ARG;
+  if (!bias || (res && gelu_out)) return BAMBOO_E_ARG;   // with gelu_out: Y = GELU'(h), gelu_out = GELU(h)
   GemmDesc d;
   memset(&d, 0, sizeof(d));
   d.A = X; d.B = W; d.C = Y; d.M = T; d.N = N; d.K = K;
@@ -43,14 +43,14 @@ int bk_linear_fwd(int dtype, int impl, int T, int N, int K, const void* X, const
 }
 
 int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY, const void* W, const void* res,
-                        const void* h_in, void* dX, void* gelu_out, void* stream) {
-  if ((h_in != nullptr) != (gelu_out != nullptr) || (h_in && res)) return BAMBOO_E_ARG;
+                        const void* mul, void* dX, void* stream) {
+  if (mul && res) return BAMBOO_E_ARG;
   GemmDesc d;
   memset(&d, 0, sizeof(d));
   d.A = dY; d.B = W; d.C = dX; d.M = T; d.N = K; d.K = N;
   d.a_sm = N; d.a_sk = 1; d.b_sk = 1; d.b_sn = N;
-  d.res = res; d.aux_in = h_in; d.aux_out = gelu_out;
-  d.epi = h_in ? EPI_DGELU : (res ? EPI_RES : EPI_STORE);
+  d.res = res; d.aux_in = mul;
+  d.epi = mul ? EPI_MUL : (res ? EPI_RES : EPI_STORE);
   return run_gemm(dtype, impl, d, stream);
 }
 

@@ -57,11 +57,12 @@ ParamOffsets param_offsets(int H, int F) {
 //   ctx   attention output before Wo       [T,H]
 //   r1    x + attention block              [T,H]   (post-LN: LN1 input, pre-LN: x1)
 //   fin   FFN input (post-LN: y1 = LN1(r1); pre-LN: v = LN2(x1))
-//   h     FFN pre-activation               [T,F]
+//   g     GELU(h), h = fin W1 + b1         [T,F]   (the FFN pre-activation h itself is not kept:
+//   dg    GELU'(h)                         [T,F]    the forward evaluates GELU and its derivative once)
 //   r2    post-LN only: y1 + ffn, LN2 input [T,H]
 //   lse, ln1, ln2  fp32 side data
 struct RecordLayout {
-  uint64_t x, ain, qkv, ctx, r1, fin, h, r2, lse, ln1, ln2, bytes;
+  uint64_t x, ain, qkv, ctx, r1, fin, g, dg, r2, lse, ln1, ln2, bytes;
 };
 RecordLayout record_layout(const bamboo_cfg_t& c) {
   const uint64_t es = c.dtype == BAMBOO_BF16 ? 2 : 4;
@@ -74,7 +75,8 @@ RecordLayout record_layout(const bamboo_cfg_t& c) {
   r.ctx = o; o = align_up(o + T * H * es);
   r.r1 = o; o = align_up(o + T * H * es);
   r.fin = o; o = align_up(o + T * H * es);
-  r.h = o; o = align_up(o + T * F * es);
+  r.g = o; o = align_up(o + T * F * es);
+  r.dg = o; o = align_up(o + T * F * es);
   if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) { r.r2 = o; o = align_up(o + T * H * es); } else { r.r2 = 0; }
   r.lse = o; o = align_up(o + (uint64_t)c.micro_batch * c.heads * c.seq * 4);
   r.ln1 = o; o = align_up(o + 2 * T * 4);
@@ -83,10 +85,10 @@ RecordLayout record_layout(const bamboo_cfg_t& c) {
   return r;
 }
 
-// Scratch of one lane.  Lane 1 only ever runs forwards: it needs g (GELU output)
-// and out (where an output the caller does not want is written).
+// Scratch of one lane.  Lane 1 only ever runs forwards: it needs only out (where an
+// output the caller does not want is written).
 struct LaneScratch {
-  uint64_t g, out, dh, d1, d2, dctx, ping, pong, dqkv, delta, bytes;
+  uint64_t out, dh, d1, d2, dctx, ping, pong, dqkv, delta, bytes;
   // partial rows of one layer's parameter-gradient reductions (summed by one launch at the layer's end):
   // LayerNorm 1 and 2 (gain, shift, column sums of the output), and the column sums of dh, dqkv, df
   uint64_t p_ln[2][3], p_dh, p_dqkv, p_df;
@@ -97,7 +99,6 @@ LaneScratch lane_scratch(const bamboo_cfg_t& c, bool backward) {
   LaneScratch w;
   memset(&w, 0, sizeof(w));
   uint64_t o = 0;
-  w.g = o; o = align_up(o + T * F * es);
   w.out = o; o = align_up(o + T * H * es);
   if (backward) {
     w.dh = o; o = align_up(o + T * F * es);
@@ -310,7 +311,6 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
   hipStream_t s = st->lane[lane_id];
   (void)hipGetLastError();  // do not inherit an unrelated earlier error of this thread
   char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
-  void* gbuf = ws + (lane_id == 0 ? st->ws0.g : st->ws1.g);
   const RecordLayout& r = st->rl;
   char* rec0 = st->stash[kind] + (uint64_t)slot * n * r.bytes;
   HIPCHK(hipMemcpyAsync(rec0 + r.x, x, (uint64_t)T * H * es, hipMemcpyDeviceToDevice, s));
@@ -342,19 +342,19 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
     else
       BBCHK(p_ln_fwd(st, s, T, H, rec + r.r1, P(st->po.g2), P(st->po.be2), rec + r.fin,
                                   (float*)(rec + r.ln2)));
-    d = gemm_nn(rec + r.fin, P(st->po.W1), rec + r.h, T, F, H, EPI_BIAS_GELU);
+    d = gemm_nn(rec + r.fin, P(st->po.W1), rec + r.dg, T, F, H, EPI_BIAS_GELU);
     d.bias = P(st->po.b1);
-    d.aux_out = gbuf;
+    d.aux_out = rec + r.g;
     BBCHK(p_gemm(st, s, d));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
-      d = gemm_nn(gbuf, P(st->po.W2), rec + r.r2, T, H, F, EPI_BIAS_RES);
+      d = gemm_nn(rec + r.g, P(st->po.W2), rec + r.r2, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.fin;
       BBCHK(p_gemm(st, s, d));
       BBCHK(p_ln_fwd(st, s, T, H, rec + r.r2, P(st->po.g2), P(st->po.be2), out,
                                   (float*)(rec + r.ln2)));
     } else {
-      d = gemm_nn(gbuf, P(st->po.W2), out, T, H, F, EPI_BIAS_RES);
+      d = gemm_nn(rec + r.g, P(st->po.W2), out, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.r1;
       BBCHK(p_gemm(st, s, d));
@@ -373,7 +373,6 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
   (void)hipGetLastError();
   char* ws = st->wsbase;
   const LaneScratch& w = st->ws0;
-  void* gbuf = ws + w.g;
   void* dh = ws + w.dh;
   void* d1 = ws + w.d1;
   void* d2 = ws + w.d2;
@@ -411,11 +410,10 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
       BBCHK(p_colsum(st, s, T, H, df, G + st->po.b2, w.p_df, &batch));
     }
     // f = g W2 + b2
-    d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_DGELU);
-    d.aux_in = rec + r.h;
-    d.aux_out = gbuf;
+    d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_MUL);   // through the activation: times GELU'(h)
+    d.aux_in = rec + r.dg;
     BBCHK(p_gemm(st, s, d));
-    BBCHK(p_gemm(st, s, gemm_tn(gbuf, df, G + st->po.W2, T, F, H)));
+    BBCHK(p_gemm(st, s, gemm_tn(rec + r.g, df, G + st->po.W2, T, F, H)));
     // h = fin W1 + b1
     BBCHK(p_colsum(st, s, T, F, dh, G + st->po.b1, w.p_dh, &batch));
     BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
@@ -532,12 +530,12 @@ int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot,
   return (int64_t)(((uint64_t)slot * n + layer) * sz.rec_bytes);
 }
 
-int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[12]) {
+int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[13]) {
   const int v = validate(cfg);
   if (v != BAMBOO_OK) return v;
   if (!out) return BAMBOO_E_ARG;
   const RecordLayout r = record_layout(*cfg);
-  const uint64_t f[12] = {r.x, r.ain, r.qkv, r.ctx, r.r1, r.fin, r.h, r.r2, r.lse, r.ln1, r.ln2, r.bytes};
+  const uint64_t f[13] = {r.x, r.ain, r.qkv, r.ctx, r.r1, r.fin, r.g, r.dg, r.r2, r.lse, r.ln1, r.ln2, r.bytes};
   memcpy(out, f, sizeof(f));
   return BAMBOO_OK;
 }

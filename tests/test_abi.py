@@ -84,8 +84,8 @@ def test_sizes_and_record_addresses():
     sz = B.stage_query_sizes(cfg)
     T, H, F = sc.tokens, sc.hidden, sc.ffn
     assert sz.own_w == sc.n_own * sc.layer_params * 2 and sz.own_g == sc.n_own * sc.layer_params * 4
-    # a record holds 8H+F activations per token plus fp32 side data
-    assert T * (8 * H + F) * 2 <= sz.rec_bytes <= T * (8 * H + F) * 2 + 16 * T + sc.micro_batch * sc.heads * sc.seq * 4 + 4096
+    # a record holds 8H+2F activations per token (GELU output and derivative both kept) plus fp32 side data
+    assert T * (8 * H + 2 * F) * 2 <= sz.rec_bytes <= T * (8 * H + 2 * F) * 2 + 16 * T + sc.micro_batch * sc.heads * sc.seq * 4 + 4096
     assert sz.rec_bytes % 256 == 0
     assert sz.own_stash == sz.c_own * sc.n_own * sz.rec_bytes
     assert sz.shadow_stash == sc.M * sc.n_shadow * sz.rec_bytes

@@ -175,7 +175,7 @@ def test_large_layer_stage_steps_match_oracle_on_samples(B):
     st.stage_sync()
     rng = np.random.default_rng(0)
     rows = np.sort(rng.choice(T, 48, replace=False))
-    rec = {f: st.stash_tensor(0, 0, 0, f) for f in ("x", "ain", "qkv", "ctx", "r1", "fin", "h", "lse", "ln1", "ln2")}
+    rec = {f: st.stash_tensor(0, 0, 0, f) for f in ("x", "ain", "qkv", "ctx", "r1", "fin", "g", "dg", "lse", "ln1", "ln2")}
     host = lambda t, r=rows: t[torch.from_numpy(r).to(DEV)].float().cpu().numpy().astype(np.float64)
     # pre-LN: u = LN1(x)
     u_ref, _ = L.layernorm_fwd(host(rec["x"]), p["g1"], p["be1"], 1e-5)
@@ -194,8 +194,10 @@ def test_large_layer_stage_steps_match_oracle_on_samples(B):
     assert rel_l2(host(rec["r1"]), host(rec["x"]) + host(rec["ctx"]) @ p["Wo"] + p["bo"]) <= tol
     v_ref, _ = L.layernorm_fwd(host(rec["r1"]), p["g2"], p["be2"], 1e-5)
     assert rel_l2(host(rec["fin"]), v_ref) <= tol
-    assert rel_l2(host(rec["h"]), host(rec["fin"]) @ p["W1"] + p["b1"]) <= tol
-    assert rel_l2(host(y), host(rec["r1"]) + L.gelu(host(rec["h"])) @ p["W2"] + p["b2"]) <= tol
+    h_ref = host(rec["fin"]) @ p["W1"] + p["b1"]
+    assert rel_l2(host(rec["g"]), L.gelu(h_ref)) <= tol
+    assert rel_l2(host(rec["dg"]), L.gelu_grad(h_ref)) <= tol
+    assert rel_l2(host(y), host(rec["r1"]) + host(rec["g"]) @ p["W2"] + p["b2"]) <= tol
     # backward: the gradients that have closed forms in terms of stashed tensors
     st.stage_bwd(0, gy, gx)
     st.stage_sync()
@@ -211,7 +213,7 @@ def test_large_layer_stage_steps_match_oracle_on_samples(B):
     dy = inp["gz"][0].astype(np.float64)
     assert rel_l2(grad("b2"), dy.sum(0)) <= 1e-3
     frows = np.sort(rng.choice(F, 32, replace=False))
-    g_cols = L.gelu(rec["h"][:, torch.from_numpy(frows).to(DEV)].float().cpu().numpy().astype(np.float64))
+    g_cols = rec["g"][:, torch.from_numpy(frows).to(DEV)].float().cpu().numpy().astype(np.float64)
     assert rel_l2(grad("W2", frows), g_cols.T @ dy) <= tol          # dW2 = gelu(h)^T dy
     assert bool(torch.isfinite(gx.float()).all()) and bool(torch.isfinite(G).all())
     st.stage_destroy()
