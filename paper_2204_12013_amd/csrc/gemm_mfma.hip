@@ -139,59 +139,53 @@ __device__ __forceinline__ bf16x8 frag_mn(const bf16_t* s, int row_base, int ks)
 // that publishes a slice.  M0 carries the wavefront-uniform LDS base.
 
 // ---- epilogue ---------------------------------------------------------------------------
-// The accumulators leave through a wavefront-private LDS staging area; afterwards lane l of a wave
-// owns, for row block i and pass `it`, the 8 consecutive outputs of chunk idx = l + 64 * it of the
-// staged 32 x (32 * WN) block (row idx / CHUNKS, columns 8 * (idx % CHUNKS) ..).  What the epilogue
-// has to read from memory for those outputs (residual, stored activation derivative, fp32 gradient
-// to add to) can therefore be fetched long before the accumulators are final: EpiOperands::issue is
-// called ahead of the last slices of the main loop, so the latency is covered by MFMAs.
+// The accumulators leave through a wavefront-private LDS staging area, one 32-row block of the
+// wave's sub-tile at a time; afterwards lane l owns, for pass `it`, the 8 consecutive outputs of
+// chunk idx = l + 64 * it of the staged 32 x (32 * WN) block (row idx / CHUNKS, columns
+// 8 * (idx % CHUNKS) ..).  What the epilogue has to read from memory for those outputs (residual,
+// stored activation derivative, fp32 gradient to add to) is known long before the accumulators are
+// final: EpiOperands::issue requests one row block's worth.  The kernel calls it for row block 0
+// ahead of the last slices of the main loop, so the latency is covered by MFMAs, and write_tile
+// requests row block i + 1 before it works on row block i.
 template <int WM, int WN, int EPI>
 struct EpiOperands {
   static constexpr int CHUNKS = 4 * WN, ITS = 32 * CHUNKS / 64;
-  // only where the operands fit in 64 registers per lane; larger tiles read them in the epilogue itself
-  static constexpr bool BF = (EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL) && WM * ITS * 4 <= 64;
-  static constexpr bool F32 = EPI == EPI_ACC_F32 && WM * ITS * 8 <= 64;
-  static constexpr bool NEEDS = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL || EPI == EPI_ACC_F32;
+  static constexpr bool BF = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL;
+  static constexpr bool F32 = EPI == EPI_ACC_F32;
   static constexpr bool PRE = BF || F32;
-  static constexpr int NLOADS = BF ? WM * ITS : (F32 ? 2 * WM * ITS : 0);   // load instructions per lane
-  bf16x8 b[BF ? WM : 1][BF ? ITS : 1];
-  f32x4 f[F32 ? WM : 1][F32 ? ITS : 1][2];
+  static constexpr int NLOADS = BF ? ITS : (F32 ? 2 * ITS : 0);   // load instructions per lane and row block
+  bf16x8 b[BF ? ITS : 1];
+  f32x4 f[F32 ? ITS : 1][2];
   // Rows / columns past the edge are clamped to the last valid ones (their values are never used), so
   // that every lane issues exactly NLOADS loads: the main loop counts them in its vmcnt waits.
-  __device__ __forceinline__ void issue(const GemmDesc& d, int m0, int n0) {
-    if (!BF && !F32) return;
+  __device__ __forceinline__ void issue(const GemmDesc& d, int m0, int n0, int i) {
+    if (!PRE) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int wm = wave >> 1, wn = wave & 1;
     const void* src = EPI == EPI_MUL ? d.aux_in : (F32 ? (const void*)d.C : d.res);
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
-#pragma unroll
-      for (int it = 0; it < ITS; ++it) {
-        const int idx = lane + it * 64;
-        const int m = min(m0 + wm * 32 * WM + i * 32 + idx / CHUNKS, d.M - 1);
-        const int n = min(n0 + wn * 32 * WN + (idx % CHUNKS) * 8, d.N - 8);
-        const long e = (long)m * d.N + n;
-        if (BF) b[i][it] = *(const bf16x8*)((const bf16_t*)src + e);
-        if (F32) {
-          f[i][it][0] = *(const f32x4*)((const float*)src + e);
-          f[i][it][1] = *(const f32x4*)((const float*)src + e + 4);
-        }
+    for (int it = 0; it < ITS; ++it) {
+      const int idx = lane + it * 64;
+      const int m = min(m0 + wm * 32 * WM + i * 32 + idx / CHUNKS, d.M - 1);
+      const int n = min(n0 + wn * 32 * WN + (idx % CHUNKS) * 8, d.N - 8);
+      const long e = (long)m * d.N + n;
+      if (BF) b[it] = *(const bf16x8*)((const bf16_t*)src + e);
+      if (F32) {
+        f[it][0] = *(const f32x4*)((const float*)src + e);
+        f[it][1] = *(const f32x4*)((const float*)src + e + 4);
       }
+    }
   }
 };
 
-// epilogue on 8 consecutive outputs of one row; `pb_in` / `pf_in` are the prefetched operands (if PRE)
-template <int EPI, bool PRE>
-__device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb_in,
-                                          const f32x4 (&pf_in)[2]) {
+// epilogue on 8 consecutive outputs of one row; `pb` / `pf` are the operands fetched ahead
+template <int EPI>
+__device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb,
+                                          const f32x4 (&pf)[2]) {
   const long i = (long)m * d.N + n;
-  bf16x8 pb = pb_in;
-  if (!PRE && (EPI == EPI_BIAS_RES || EPI == EPI_RES)) pb = *(const bf16x8*)((const bf16_t*)d.res + i);
-  if (!PRE && EPI == EPI_MUL) pb = *(const bf16x8*)((const bf16_t*)d.aux_in + i);
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
-    f32x4 a = pf_in[0], b = pf_in[1];
-    if (!PRE) { a = *(f32x4*)c; b = *(f32x4*)(c + 4); }
+    f32x4 a = pf[0], b = pf[1];
 #pragma unroll
     for (int j = 0; j < 4; ++j) { a[j] += acc[j]; b[j] += acc[4 + j]; }
     *(f32x4*)c = a;
@@ -231,16 +225,21 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
   *(bf16x8*)((bf16_t*)d.C + i) = o;
 }
 
-// Accumulators -> wavefront-private LDS rows -> 16-byte global accesses.
+// Accumulators -> wavefront-private LDS rows -> 16-byte global accesses.  `first` holds the operands
+// of row block 0 (requested by the caller).
 template <int WM, int WN, int EPI, int EPI_LD>
 __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][WN], float* stage_all, int m0, int n0,
-                                           const EpiOperands<WM, WN, EPI>& ops) {
+                                           const EpiOperands<WM, WN, EPI>& first) {
   typedef EpiOperands<WM, WN, EPI> Ops;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   float* stage = stage_all + wave * 32 * EPI_LD;
+  Ops ops[2];
+  ops[0] = first;
 #pragma unroll
   for (int i = 0; i < WM; ++i) {
+    if (i + 1 < WM) ops[(i + 1) & 1].issue(d, m0, n0, i + 1);
+    const Ops& cur = ops[i & 1];
     // D[row][col]: lane holds col = lane%32, rows 8*(r/4) + 4*(lane/32) + r%4
 #pragma unroll
     for (int j = 0; j < WN; ++j)
@@ -260,7 +259,7 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
       const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
       if (m < d.M && n < d.N) {
         const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI, Ops::PRE>(d, m, n, v, ops.b[Ops::BF ? i : 0][Ops::BF ? it : 0], ops.f[Ops::F32 ? i : 0][Ops::F32 ? it : 0]);
+        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0]);
       }
     }
     __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
@@ -357,7 +356,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
   }
 
   EpiOperands<WM, WN, EPI> ops;
-  ops.issue(d, m0, n0);
+  ops.issue(d, m0, n0, 0);
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
 }
 
@@ -555,7 +554,8 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
   typedef PlLoop<WM, WN, A_K, B_K> Loop;
   constexpr int BM = SM::BM, BN = SM::BN, NL = Loop::NL;
   constexpr unsigned STAGE = SM::STAGE_BYTES, RING = NS * STAGE;
-  static_assert((NS - 1) * NL + EpiOperands<WM, WN, EPI>::NLOADS < 64, "too many loads in flight for the vmcnt counter");
+  static_assert((NS - 1) * NL + (WM * WN <= 8 ? EpiOperands<WM, WN, EPI>::NLOADS : 0) < 64,
+                "too many loads in flight for the vmcnt counter");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
@@ -614,12 +614,14 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
     L.template kstep<true, 2>(acc, fa[3], fb[3], fa[1], fb[1], nxt, 1, cur);
     cur = nxt;
   }
-  // The last NS slices issue no slice loads; instead the epilogue's operands are requested now, so
-  // that they arrive under the remaining MFMAs.  They are younger than every slice load, hence
-  // simply add to the number of loads that may still be in flight at the waits below.
+  // The last NS slices issue no slice loads; instead the epilogue's operands for the first row block
+  // are requested now, so that they arrive under the remaining MFMAs.  They are younger than every
+  // slice load, hence simply add to the number of loads that may still be in flight at the waits below.
+  // (256 x 256 tiles have no registers to spare for them until the fragments are dead.)
+  constexpr bool EARLY = WM * WN <= 8;
   EpiOperands<WM, WN, EPI> ops;
-  ops.issue(d, m0, n0);
-  constexpr int NEPI = EpiOperands<WM, WN, EPI>::NLOADS;
+  if (EARLY) ops.issue(d, m0, n0, 0);
+  constexpr int NEPI = EARLY ? EpiOperands<WM, WN, EPI>::NLOADS : 0;
   BAMBOO_SCHED_FENCE();
   // slice nk-1-J still has J slices after it, J-1 of which may be in flight
   auto tail = [&](auto jc) __attribute__((always_inline)) {
@@ -643,6 +645,8 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
   // every wave is done with the slice buffers before the staging area reuses them
   __builtin_amdgcn_s_waitcnt(0xc07f);
   __syncthreads();
+  BAMBOO_SCHED_FENCE();
+  if (!EARLY) ops.issue(d, m0, n0, 0);
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
 }
 
