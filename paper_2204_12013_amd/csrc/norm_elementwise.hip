@@ -12,6 +12,9 @@ namespace bamboo {
 template <typename T> struct Vec;
 template <> struct Vec<float> {
   static constexpr int N = 4;
+  typedef float4 Raw;
+  __device__ static __forceinline__ Raw load_raw(const float* p) { return *(const float4*)p; }
+  __device__ static __forceinline__ void unpack(const Raw& t, float (&v)[4]) { v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
   __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
     const float4 t = *(const float4*)p;
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
@@ -23,6 +26,12 @@ template <> struct Vec<float> {
 template <> struct Vec<bf16_t> {
   static constexpr int N = 8;
   typedef __attribute__((ext_vector_type(8))) __bf16 raw;
+  typedef raw Raw;
+  __device__ static __forceinline__ Raw load_raw(const bf16_t* p) { return *(const raw*)p; }
+  __device__ static __forceinline__ void unpack(const Raw& t, float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = (float)t[i];
+  }
   __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
     const raw t = *(const raw*)p;
 #pragma unroll
@@ -39,7 +48,9 @@ template <> struct Vec<bf16_t> {
 constexpr int kMaxPartials = 256;   // workgroups contributing partial column sums
 
 // ------------------------------------------------------------ LayerNorm forward
-// NCH = vector chunks a lane keeps in registers (row length <= NCH * 64 * V).
+// NCH = vector chunks a lane keeps in registers (row length <= NCH * 64 * V).  Every load of a
+// row is requested before the first is used (lanes past the row's end re-read its last vector and
+// drop it), so a wavefront keeps the whole row in flight.
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int T_rows, int H, float eps, const T* __restrict__ r,
                                                             const T* __restrict__ gamma, const T* __restrict__ beta,
@@ -50,37 +61,41 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(int T_rows, int H, f
   if (row >= T_rows) return;
   const T* rr = r + (long)row * H;
   const int nvec = H / V;
+  typename Vec<T>::Raw raw[NCH], graw[NCH], braw[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) raw[j] = Vec<T>::load_raw(rr + min(lane + 64 * j, nvec - 1) * V);
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    graw[j] = Vec<T>::load_raw(gamma + min(lane + 64 * j, nvec - 1) * V);
+    braw[j] = Vec<T>::load_raw(beta + min(lane + 64 * j, nvec - 1) * V);
+  }
   float v[NCH][V];
   float s = 0.f;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const int c = lane + 64 * j;
-    if (c < nvec) {
-      Vec<T>::load(rr + c * V, v[j]);
+    Vec<T>::unpack(raw[j], v[j]);
+    const float keep = lane + 64 * j < nvec ? 1.f : 0.f;
 #pragma unroll
-      for (int i = 0; i < V; ++i) s += v[j][i];
-    }
+    for (int i = 0; i < V; ++i) s += keep * v[j][i];
   }
   const float mean = wave_sum(s) / (float)H;
   float q = 0.f;
 #pragma unroll
-  for (int j = 0; j < NCH; ++j)
-    if (lane + 64 * j < nvec) {
+  for (int j = 0; j < NCH; ++j) {
+    const float keep = lane + 64 * j < nvec ? 1.f : 0.f;
 #pragma unroll
-      for (int i = 0; i < V; ++i) q += (v[j][i] - mean) * (v[j][i] - mean);
-    }
+    for (int i = 0; i < V; ++i) q += keep * (v[j][i] - mean) * (v[j][i] - mean);
+  }
   const float rstd = rsqrtf(wave_sum(q) / (float)H + eps);
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int c = lane + 64 * j;
-    if (c < nvec) {
-      float g[V], b[V], o[V];
-      Vec<T>::load(gamma + c * V, g);
-      Vec<T>::load(beta + c * V, b);
+    float g[V], b[V], o[V];
+    Vec<T>::unpack(graw[j], g);
+    Vec<T>::unpack(braw[j], b);
 #pragma unroll
-      for (int i = 0; i < V; ++i) o[i] = g[i] * ((v[j][i] - mean) * rstd) + b[i];
-      Vec<T>::store(y + (long)row * H + c * V, o);
-    }
+    for (int i = 0; i < V; ++i) o[i] = g[i] * ((v[j][i] - mean) * rstd) + b[i];
+    if (c < nvec) Vec<T>::store(y + (long)row * H + c * V, o);
   }
   if (lane == 0) {
     stats[2 * row] = mean;
@@ -158,9 +173,13 @@ hipError_t launch_layernorm_fwd(hipStream_t s, int dtype, int T, int H, float ep
 // ----------------------------------------------------------- LayerNorm backward
 // dr = (dhat - mean(dhat) - rhat * mean(dhat * rhat)) * rstd, dhat = dout * gamma.
 // Fused variant: the workgroup also accumulates its rows' contributions to the
-// gain and shift gradients (sum dout*rhat, sum dout) and writes one partial row
-// per workgroup; lane-owned columns stay in registers across rows.
-template <typename T, int NCH>
+// gain and shift gradients (sum dout*rhat, sum dout) and, if COLSUM, the column sums of the stored
+// output dr (the bias gradient of the linear layer whose output gradient dr is), and writes one
+// partial row of each per workgroup; lane-owned columns stay in registers across rows.
+// A wavefront takes two of its rows per pass and requests all of their data before it works on
+// either: the kernel is bound by memory latency times bytes in flight, not by arithmetic.  Lanes
+// past the row's end re-read its last vector and zero it.
+template <typename T, int NCH, bool ADD, bool COLSUM>
 __global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, int H, int rows_per_block,
                                                                   const T* __restrict__ dout, const T* __restrict__ r,
                                                                   const float* __restrict__ stats,
@@ -169,35 +188,61 @@ __global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, in
                                                                   float* __restrict__ pg, float* __restrict__ pb,
                                                                   float* __restrict__ pc) {
   constexpr int V = Vec<T>::N;
+  typedef typename Vec<T>::Raw Raw;
   extern __shared__ float red[];                 // [4][H]
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int nvec = H / V;
-  // pc (optional): column sums of the stored output dr, i.e. the bias gradient of the linear
-  // layer whose output gradient dr is
-  float g[NCH][V], ag[NCH][V], ab[NCH][V], ac[NCH][V];
+  float g[NCH][V], ag[NCH][V], ab[NCH][V], ac[COLSUM ? NCH : 1][V];
+  int cc[NCH];
+  float keep[NCH];
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int c = lane + 64 * j;
+    cc[j] = min(c, nvec - 1) * V;
+    keep[j] = c < nvec ? 1.f : 0.f;
 #pragma unroll
-    for (int i = 0; i < V; ++i) { g[j][i] = 0.f; ag[j][i] = 0.f; ab[j][i] = 0.f; ac[j][i] = 0.f; }
-    if (c < nvec) Vec<T>::load(gamma + c * V, g[j]);
+    for (int i = 0; i < V; ++i) { ag[j][i] = 0.f; ab[j][i] = 0.f; }
+    if (COLSUM) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) ac[j][i] = 0.f;
+    }
+    Vec<T>::load(gamma + cc[j], g[j]);
   }
   const int row_end = min(T_rows, (int)(blockIdx.x + 1) * rows_per_block);
-  for (int row = blockIdx.x * rows_per_block + w; row < row_end; row += 4) {
-    const long off = (long)row * H;
-    const float mean = stats[2 * row], rstd = stats[2 * row + 1];
-    float d[NCH][V], xh[NCH][V];
-    float s1 = 0.f, s2 = 0.f;
+  for (int row0 = blockIdx.x * rows_per_block + w; row0 < row_end; row0 += 8) {
+    // second row of the pass: if there is none, the first is read again and its results dropped
+    const bool two = row0 + 4 < row_end;
+    const int rows[2] = {row0, two ? row0 + 4 : row0};
+    Raw dw[2][NCH], xw[2][NCH], aw[2][ADD ? NCH : 1];
+    float mean[2], rstd[2];
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      const int c = lane + 64 * j;
-      if (c < nvec) {
+    for (int u = 0; u < 2; ++u) {
+      const long off = (long)rows[u] * H;
+      mean[u] = stats[2 * rows[u]];
+      rstd[u] = stats[2 * rows[u] + 1];
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        dw[u][j] = Vec<T>::load_raw(dout + off + cc[j]);
+        xw[u][j] = Vec<T>::load_raw(r + off + cc[j]);
+        if (ADD) aw[u][j] = Vec<T>::load_raw(add + off + cc[j]);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const float use = (u == 0 || two) ? 1.f : 0.f;
+      const long off = (long)rows[u] * H;
+      float d[NCH][V], xh[NCH][V];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
         float x[V];
-        Vec<T>::load(dout + off + c * V, d[j]);
-        Vec<T>::load(r + off + c * V, x);
+        Vec<T>::unpack(dw[u][j], d[j]);
+        Vec<T>::unpack(xw[u][j], x);
+        const float k = keep[j] * use;
 #pragma unroll
         for (int i = 0; i < V; ++i) {
-          xh[j][i] = (x[i] - mean) * rstd;
+          d[j][i] *= k;
+          xh[j][i] = (x[i] - mean[u]) * rstd[u];
           ag[j][i] += d[j][i] * xh[j][i];
           ab[j][i] += d[j][i];
           d[j][i] *= g[j][i];                      // dhat
@@ -205,41 +250,39 @@ __global__ __launch_bounds__(256) void layernorm_bwd_fused_kernel(int T_rows, in
           s2 += d[j][i] * xh[j][i];
         }
       }
-    }
-    const float m1 = wave_sum(s1) / (float)H;
-    const float m2 = wave_sum(s2) / (float)H;
+      const float m1 = wave_sum(s1) / (float)H;
+      const float m2 = wave_sum(s2) / (float)H;
 #pragma unroll
-    for (int j = 0; j < NCH; ++j) {
-      const int c = lane + 64 * j;
-      if (c < nvec) {
+      for (int j = 0; j < NCH; ++j) {
         float o[V];
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = (d[j][i] - m1 - xh[j][i] * m2) * rstd;
-        if (add != nullptr) {
+        for (int i = 0; i < V; ++i) o[i] = (d[j][i] - m1 - xh[j][i] * m2) * rstd[u];
+        if (ADD) {
           float a[V];
-          Vec<T>::load(add + off + c * V, a);
+          Vec<T>::unpack(aw[u][j], a);
 #pragma unroll
           for (int i = 0; i < V; ++i) o[i] += a[i];
         }
-        Vec<T>::store(dr + off + c * V, o);
-        if (pc != nullptr) {
+        if (COLSUM) {
+          const float k = keep[j] * use;
 #pragma unroll
-          for (int i = 0; i < V; ++i) ac[j][i] += round_storage<T>(o[i]);
+          for (int i = 0; i < V; ++i) ac[j][i] += k * round_storage<T>(o[i]);
         }
+        if (lane + 64 * j < nvec && (u == 0 || two)) Vec<T>::store(dr + off + cc[j], o);
       }
     }
   }
   // ordered reduction of the four wavefronts: gain gradient, shift gradient, output column sums
 #pragma unroll
-  for (int which = 0; which < 3; ++which) {
-    if (which == 2 && pc == nullptr) break;
+  for (int which = 0; which < (COLSUM ? 3 : 2); ++which) {
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = lane + 64 * j;
       if (c < nvec) {
 #pragma unroll
-        for (int i = 0; i < V; ++i) red[w * H + c * V + i] = which == 0 ? ag[j][i] : (which == 1 ? ab[j][i] : ac[j][i]);
+        for (int i = 0; i < V; ++i)
+          red[w * H + c * V + i] = which == 0 ? ag[j][i] : (which == 1 ? ab[j][i] : ac[COLSUM ? j : 0][i]);
       }
     }
     __syncthreads();
@@ -489,12 +532,18 @@ static hipError_t ln_bwd_partials_impl(hipStream_t s, int T_rows, int H, const v
   if (nch <= 4 && (size_t)4 * H * sizeof(float) <= 48 * 1024) {
     split_rows(T_rows, kMaxPartials, &rpb, &rb);
     const size_t sh = (size_t)4 * H * sizeof(float);
-#define LN_BWD(K)                                                                                                  \
-  hipLaunchKernelGGL(K, dim3(rb), dim3(256), sh, s, T_rows, H, rpb, (const T*)dout, (const T*)r, stats,          \
-                     (const T*)gamma, (const T*)add, (T*)dr, pg, pb, pc)
-    if (nch <= 1) LN_BWD((layernorm_bwd_fused_kernel<T, 1>));
-    else if (nch <= 2) LN_BWD((layernorm_bwd_fused_kernel<T, 2>));
-    else LN_BWD((layernorm_bwd_fused_kernel<T, 4>));
+#define LN_BWD1(NC, A, C)                                                                                          \
+  hipLaunchKernelGGL((layernorm_bwd_fused_kernel<T, NC, A, C>), dim3(rb), dim3(256), sh, s, T_rows, H, rpb,         \
+                     (const T*)dout, (const T*)r, stats, (const T*)gamma, (const T*)add, (T*)dr, pg, pb, pc)
+#define LN_BWD(NC)                                                                                                 \
+  do {                                                                                                             \
+    if (add != nullptr) { if (pc != nullptr) LN_BWD1(NC, true, true); else LN_BWD1(NC, true, false); }             \
+    else { if (pc != nullptr) LN_BWD1(NC, false, true); else LN_BWD1(NC, false, false); }                          \
+  } while (0)
+    if (nch <= 1) LN_BWD(1);
+    else if (nch <= 2) LN_BWD(2);
+    else LN_BWD(4);
+#undef LN_BWD1
 #undef LN_BWD
   } else {
     const int col_blocks = (H + 64 * V - 1) / (64 * V);
