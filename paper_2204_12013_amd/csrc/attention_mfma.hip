@@ -30,6 +30,18 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMasked = -1.0e30f;
 constexpr int TILE = 64;   // rows streamed through LDS per step
 
+// Workgroup -> (row block, batch*head).  The grid is one-dimensional and ordered by row block
+// first, all (batch, head) pairs of a row block being consecutive; with a causal mask the row
+// blocks with the most key tiles to visit come first (HEAVY_LAST: the highest row block is the
+// heaviest, as for query owners; otherwise the lowest, as for key owners), so the dispatcher
+// hands out long workgroups first and the short ones fill the tail of the launch.
+template <bool CAUSAL, bool HEAVY_LAST>
+__device__ __forceinline__ void block_of(int nblk, int nbh, int* blk, int* bh) {
+  const int i = blockIdx.x / nbh;
+  *bh = blockIdx.x % nbh;
+  *blk = (CAUSAL && HEAVY_LAST) ? nblk - 1 - i : i;
+}
+
 // ---- cooperative copy of 64 rows x D (bf16) global -> registers -> LDS -------------
 template <int D>
 struct RowTile {
@@ -135,8 +147,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
   bf16_t* Vs = Ks + 2 * TILE * LDK;               // [2][64][LDV]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5;
   const int H = a.heads * D, S = a.S;
-  const int b = blockIdx.y / a.heads, h = blockIdx.y % a.heads;
-  const int q0 = blockIdx.x * 128, qw0 = q0 + wave * 32;
+  int qblk, bh;
+  block_of<CAUSAL, true>((S + 127) / 128, a.B * a.heads, &qblk, &bh);
+  const int b = bh / a.heads, h = bh % a.heads;
+  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
   const long rs = 3L * H;
   const bf16_t* base = (const bf16_t*)a.qkv + (long)b * S * rs + h * D;
   const float c = rsqrtf((float)D) * kLog2e;
@@ -266,8 +280,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
   bf16_t* Vs = Ks + 2 * TILE * LD;                // [2][64][LD]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int H = a.heads * D, S = a.S;
-  const int b = blockIdx.y / a.heads, h = blockIdx.y % a.heads;
-  const int q0 = blockIdx.x * 128, qw0 = q0 + wave * 32;
+  int qblk, bh;
+  block_of<CAUSAL, true>((S + 127) / 128, a.B * a.heads, &qblk, &bh);
+  const int b = bh / a.heads, h = bh % a.heads;
+  const int q0 = qblk * 128, qw0 = q0 + wave * 32;
   const long rs = 3L * H;
   const bf16_t* base = (const bf16_t*)a.qkv + (long)b * S * rs + h * D;
   const bf16_t* dbase = (const bf16_t*)a.dctx + (long)b * S * H + h * D;
@@ -355,8 +371,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
   float* del_s = lse_s + 2 * TILE;                // [2][64]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5;
   const int H = a.heads * D, S = a.S;
-  const int b = blockIdx.y / a.heads, h = blockIdx.y % a.heads;
-  const int kb0 = blockIdx.x * 128, kw0 = kb0 + wave * 32;
+  int kblk, bh;
+  block_of<CAUSAL, false>((S + 127) / 128, a.B * a.heads, &kblk, &bh);
+  const int b = bh / a.heads, h = bh % a.heads;
+  const int kb0 = kblk * 128, kw0 = kb0 + wave * 32;
   const long rs = 3L * H;
   const bf16_t* base = (const bf16_t*)a.qkv + (long)b * S * rs + h * D;
   const bf16_t* dbase = (const bf16_t*)a.dctx + (long)b * S * H + h * D;
@@ -487,7 +505,7 @@ static hipError_t fwd_launch(hipStream_t s, const AttnDesc& a) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  hipLaunchKernelGGL(kern, dim3((a.S + 127) / 128, a.B * a.heads), dim3(256), BYTES, s, a);
+  hipLaunchKernelGGL(kern, dim3(((a.S + 127) / 128) * a.B * a.heads), dim3(256), BYTES, s, a);
   return hipGetLastError();
 }
 
@@ -506,7 +524,7 @@ static hipError_t bwd_launch(hipStream_t s, const AttnDesc& a) {
   }
   const long chunks = (long)a.B * a.S * a.heads * D / 8;
   hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, a);
-  dim3 grid((a.S + 127) / 128, a.B * a.heads);
+  dim3 grid(((a.S + 127) / 128) * a.B * a.heads);
   hipLaunchKernelGGL(kq, grid, dim3(256), BYTES_DQ, s, a);
   hipLaunchKernelGGL(kkv, grid, dim3(256), BYTES_DKV, s, a);
   return hipGetLastError();
