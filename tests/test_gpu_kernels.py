@@ -68,6 +68,41 @@ def test_linear_backward_mfma(B, T, N, K):
     test_linear_backward_variants(B, 1, 2, T, N, K)
 
 
+@pytest.mark.parametrize("T,N,K", [(520, 392, 448), (1024, 1152, 1024)])
+def test_mfma_tiles_and_pipeline_depths_agree_bitwise(B, T, N, K):
+    """Every output tile shape and every depth of the LDS slice ring walks K in the same order with the
+    same matrix instruction, so the results must be identical to the last bit: the tile choice can
+    then never break the bitwise FRC == successor and failover == failure-free invariants."""
+    rng = np.random.default_rng(T + N)
+    X, W, b = _mk(rng, (T, K), 1), _mk(rng, (K, N), 1, 0.05), _mk(rng, (N,), 1, 0.1)
+    dY, R = _mk(rng, (T, N), 1), _mk(rng, (T, N), 1)
+    Xd, Wd, bd, dYd, Rd = (_dev(B, a, 1) for a in (X, W, b, dY, R))
+    ref = None
+    try:
+        for tile in (22, 11, 24, 42, 44):
+            for depth in (2, 3, 4):
+                B.bk_gemm_tile(tile)
+                B.bk_gemm_stages(depth)
+                Y, G, dX = _empty((T, N), 1), _empty((T, N), 1), _empty((T, K), 1)
+                dW = torch.zeros(K, N, dtype=torch.float32, device=DEV)
+                B.bk_linear_fwd(Xd, Wd, bd, Y, gelu_out=G, impl=2)
+                Y2 = _empty((T, N), 1)
+                B.bk_linear_fwd(Xd, Wd, bd, Y2, res=Rd, impl=2)
+                B.bk_linear_bwd_input(dYd, Wd, dX, mul=Xd, impl=2)
+                B.bk_linear_bwd_weight(Xd, dYd, dW, impl=2)
+                torch.cuda.synchronize()
+                got = (Y, G, Y2, dX, dW)
+                if ref is None:
+                    ref = got
+                    assert rel_l2(B.to_host(Y2), X.astype(np.float64) @ W.astype(np.float64) + b + R) <= TOL[1]
+                else:
+                    for a, r in zip(got, ref):
+                        assert torch.equal(a, r), (tile, depth)
+    finally:
+        B.bk_gemm_tile(0)
+        B.bk_gemm_stages(0)
+
+
 def test_mfma_kernel_refuses_what_it_does_not_cover(B):
     X, W, b = _empty((12, 16), 1), _empty((16, 24), 1), _empty((24,), 1)
     with pytest.raises(B.BambooError) as e:
