@@ -18,13 +18,19 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Per-file additions.  The attention kernels do elementwise arithmetic on MFMA results inside their
+# main loops; with the accumulators allocated as ordinary VGPRs (instead of AGPRs) no register moves
+# separate the matrix instructions from that arithmetic.
+EXTRA = {"attention_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def _sources():
     return sorted(f for f in os.listdir(CSRC) if f.endswith((".hip", ".cpp")))
 
 
 def _compile(src):
     obj = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC] + COMMON + (["-x", "hip"] if src.endswith(".hip") else []) + \
+    cmd = [HIPCC] + COMMON + EXTRA.get(src, []) + (["-x", "hip"] if src.endswith(".hip") else []) + \
         ["-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
