@@ -192,38 +192,63 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
           s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(ks_, LDK, u * 32, ks), qf[ks], s[u], 0, 0, 0);
+      // Online softmax in the log2 domain.  The running maximum m_i is only raised when some row's
+      // maximum has grown by more than 8 (a factor 256, harmless in fp32 and bf16): softmax is
+      // invariant to the shift, and the rescaling of the running output then happens on a few
+      // tiles instead of on every one.  Tiles that need no masking take a path without the
+      // per-element index arithmetic (the choice is uniform over the wavefront).
       const bool need_mask = (k0 + TILE > S) || (CAUSAL && k0 + TILE - 1 > qw0);
       float mx = kMasked;
+      if (need_mask) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[u][r] * c;
-          if (need_mask) {
+          for (int r = 0; r < 16; ++r) {
             const int key = k0 + u * 32 + acc_row(r);
-            if (key >= S || (CAUSAL && key > query)) v = kMasked;
+            const float v = (key >= S || (CAUSAL && key > query)) ? kMasked : s[u][r] * c;
+            s[u][r] = v;
+            mx = fmaxf(mx, v);
           }
-          s[u][r] = v;
-          mx = fmaxf(mx, v);
-        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][r]);
+        mx *= c;
+      }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_i, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m_i - m_new);
+      const bool grow = mx > m_i + 8.f;
+      if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+        const float m_new = grow ? mx : m_i;
+        const float alpha = __builtin_amdgcn_exp2f(m_i - m_new);
+        l_i *= alpha;
+        m_i = m_new;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      }
       float ls = 0.f;
+      if (need_mask) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(s[u][r] - m_new);
-          s[u][r] = p;
-          ls += p;
-        }
-      l_i = l_i * alpha + ls;
-      m_i = m_new;
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(s[u][r] - m_i);
+            s[u][r] = p;
+            ls += p;
+          }
+      } else {
 #pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -m_i));
+            s[u][r] = p;
+            ls += p;
+          }
+      }
+      l_i += ls;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bf16x8 pb = pack8(s[u >> 1], u & 1);
@@ -331,17 +356,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
           dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(vs_, LD, u * 32, ks), dof[ks], dp[u], 0, 0, 0);
         }
       const bool need_mask = (k0 + TILE > S) || (CAUSAL && k0 + TILE - 1 > qw0);
+      if (need_mask) {                            // uniform over the wavefront
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(s[u][r] * c - lse2);
-          if (need_mask) {
+          for (int r = 0; r < 16; ++r) {
+            float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -lse2));
             const int key = k0 + u * 32 + acc_row(r);
             if (key >= S || (CAUSAL && key > query)) p = 0.f;
+            s[u][r] = p * (dp[u][r] - delta);     // dS^T
           }
-          s[u][r] = p * (dp[u][r] - delta);       // dS^T
-        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            s[u][r] = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -lse2)) * (dp[u][r] - delta);
+      }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bf16x8 dsb = pack8(s[u >> 1], u & 1);
@@ -447,16 +478,24 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
           const int row = u * 32 + 8 * a4 + 4 * g;   // first of 4 consecutive query rows of this lane
           const f32x4 l4 = *(const f32x4*)(lse_s + buf * TILE + row);
           const f32x4 d4 = *(const f32x4*)(del_s + buf * TILE + row);
+          if (need_mask) {                        // uniform over the wavefront
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc) {
-            const int r = 4 * a4 + cc;
-            float p = __builtin_amdgcn_exp2f(s[u][r] * c - l4[cc]);
-            if (need_mask) {
+            for (int cc = 0; cc < 4; ++cc) {
+              const int r = 4 * a4 + cc;
+              float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -l4[cc]));
               const int query = q0t + row + cc;
               if (query >= S || key >= S || (CAUSAL && key > query)) p = 0.f;
+              s[u][r] = p;
+              dp[u][r] = p * (dp[u][r] - d4[cc]);    // dS
             }
-            s[u][r] = p;
-            dp[u][r] = p * (dp[u][r] - d4[cc]);      // dS
+          } else {
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) {
+              const int r = 4 * a4 + cc;
+              const float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -l4[cc]));
+              s[u][r] = p;
+              dp[u][r] = p * (dp[u][r] - d4[cc]);    // dS
+            }
           }
         }
 #pragma unroll
