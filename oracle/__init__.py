@@ -12,6 +12,8 @@ Modules
             (Sections 2, 5.2)
   stage     a stage executing an instruction list with simulated neighbours
             (Sections 5.1, 5.2: eager FRC, lazy BRC, recovery)
+  optim     Adam update (Section 7 names the optimizer) and replica weight
+            synchronisation (Section 5.1 requires equal parameters)
 
 Pins (see tests/test_oracle_*.py): finite differences, an independent autograd
 implementation, closed forms for the timeline, the paper's worked values, brute
