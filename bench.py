@@ -175,6 +175,36 @@ def main():
                               "ms_per_step_frc_on": ms_c_on,
                               "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
 
+    # the APPLY step (Adam over the own parameters) and the replica weight synchronisation, timed with
+    # events on lane 0; algorithmic HBM bytes: 16 read + 14 written per parameter (fp32 gradient, master
+    # weights and two moments in, the last three and the bf16 copy out); the synchronisation is a device
+    # copy of the parameters and the optimizer state (2 + 12 bytes per parameter, read and written)
+    st.stage_optimizer_init()
+    n_own = int(st.sizes.layer_params) * sc.n_own
+    n_sh = int(st.sizes.layer_params) * sc.n_shadow
+    es = 2 if sc.dtype == 1 else 4
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    reps = 5
+    st.stage_apply(1)
+    st.stage_sync_replica(st.shadow_w, st.shadow_opt)          # self-copy: same traffic as from a neighbour's buffer
+    st.stage_sync()
+    with torch.cuda.stream(st.stream_main):
+        ev[0].record()
+        for i in range(reps):
+            st.stage_apply(2 + i)
+        ev[1].record()
+        for i in range(reps):
+            st.stage_sync_replica(st.shadow_w, st.shadow_opt)
+        ev[2].record()
+    st.stage_sync()
+    t_adam = ev[0].elapsed_time(ev[1]) / reps
+    t_sync = ev[1].elapsed_time(ev[2]) / reps
+    out["apply_step"] = {"adam_ms": t_adam, "adam_GB/s": n_own * (28.0 + es) / (t_adam * 1e-3) / 1e9,
+                         "adam_frac_of_hbm_peak": n_own * (28.0 + es) / (t_adam * 1e-3) / PEAK["hbm"],
+                         "replica_sync_ms": t_sync,
+                         "replica_sync_GB/s": 2.0 * n_sh * (12.0 + es) / (t_sync * 1e-3) / 1e9,
+                         "parameters_own": n_own, "parameters_replica": n_sh}
+
     # per-kernel-class roofline: the iteration again with an event pair around every launch, on the
     # launch's own stream.  By default FRC is left out of this pass: with two lanes active a kernel
     # shares the GPU with the other lane's kernels and its event time is no longer its own.

@@ -81,6 +81,12 @@ int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream);
  * offered.  Not thread-safe against concurrent launches. */
 int bk_gemm_tile(int code);
 
+/* One Adam step (Section 7 names the optimizer) over n parameters, n a multiple of 4, step >= 1:
+ * g fp32 gradient; master, m, v fp32 master weights and moments, updated in place; w[n] (storage
+ * dtype) = the new master weights rounded to storage.  All device pointers, 16-byte aligned. */
+int bk_adam(int dtype, int64_t n, const float* g, float* master, float* m, float* v, void* w, float lr, float beta1,
+            float beta2, float eps, int step, void* stream);
+
 /* Tuning and test hook: force the depth of the LDS slice ring of the pipelined MFMA
  * GEMM kernel (2, 3 or 4 buffers; a depth that does not fit the tile's LDS budget
  * or exceeds the number of K slices falls back to the next smaller one); 0 restores

@@ -117,7 +117,15 @@ typedef struct {
   uint64_t layer_params;            /* elements per layer: 4H^2 + 2HF + 9H + F */
   int32_t c_own;                    /* own stash slots = min(P - stage_id, M) */
   int32_t c_shadow;                 /* shadow stash slots = M (everything BRC may need) */
+  uint64_t own_opt, shadow_opt;     /* optimizer state (only for stage_optimizer_init): fp32 master weights,
+                                       first and second moments, 3 x 4 bytes per parameter */
 } bamboo_sizes_t;
+
+/* Adam hyper-parameters (Section 7 names the optimizer and a learning rate of 6e-3 for the
+ * language models; beta1 0.9, beta2 0.999, eps 1e-8 are the usual defaults). */
+typedef struct {
+  float lr, beta1, beta2, eps;
+} bamboo_adam_t;
 
 /* ---- host-only entry points (no GPU needed) ------------------------------ */
 
@@ -216,6 +224,31 @@ int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy);
  * allowed) and the failover schedule is written to out.  BAMBOO_E_STATE when
  * called twice or with n_shadow == 0.  Returns the instruction count. */
 int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
+
+/* ---- the APPLY instruction and the replica's weight synchronisation ----------------------
+ * Section 5.1: node n keeps a replica of node n+1's layers together with their optimizer state,
+ * and FRC/BRC use the same parameters as node n+1.  The paper gives no mechanism; here the
+ * replica is overwritten with the successor's values after every update.
+ *
+ * stage_optimizer_init: own_opt / shadow_opt are device buffers of sizes.own_opt / sizes.shadow_opt
+ * bytes (256-byte aligned; shadow_opt may be NULL when n_shadow == 0), laid out as
+ * [master | m | v], each layer_params * n_layers floats in parameter order.  Enqueues on lane 0:
+ * master <- the current parameters widened to fp32, m = v = 0.  From then on own_w (and shadow_w)
+ * passed to stage_init are rewritten by stage_apply / stage_sync_replica although stage_init took
+ * them as const. */
+int stage_optimizer_init(bamboo_stage_t* st, void* own_opt, void* shadow_opt);
+
+/* APPLY: one Adam step (step counts from 1) on the own parameters from the own gradients, on
+ * lane 0.  After failover_merge the stage owns the victim's layers too: the replica parameters
+ * are then updated from the replica gradients with the replica's optimizer state.
+ * BAMBOO_E_STATE without stage_optimizer_init. */
+int stage_apply(bamboo_stage_t* st, const bamboo_adam_t* hp, int32_t step);
+
+/* Replica weight synchronisation, on lane 0: the replica parameters become successor_w (device,
+ * sizes.shadow_w bytes: the successor's own parameters after its update) and, if successor_opt is
+ * not NULL, the replica's optimizer state becomes successor_opt (device, sizes.shadow_opt bytes).
+ * Stands for the transfer from node n+1 to node n; on one GPU it is a device-local copy. */
+int stage_sync_replica(bamboo_stage_t* st, const void* successor_w, const void* successor_opt);
 
 /* Simulated pipeline bubble: one single-wave workgroup on lane 0 that spins on
  * the device wall clock for ticks * us_per_tick microseconds. */

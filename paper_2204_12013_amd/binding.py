@@ -38,7 +38,12 @@ class Instr(C.Structure):
 class Sizes(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("own_w", "shadow_w", "own_g", "shadow_g", "own_stash", "shadow_stash", "workspace",
-                 "rec_bytes", "layer_params")] + [("c_own", C.c_int32), ("c_shadow", C.c_int32)]
+                 "rec_bytes", "layer_params")] + [("c_own", C.c_int32), ("c_shadow", C.c_int32)] + \
+        [("own_opt", C.c_uint64), ("shadow_opt", C.c_uint64)]
+
+
+class Adam(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
 
 
 class BambooError(RuntimeError):
@@ -65,6 +70,9 @@ _SIGS = {
     "shadow_bwd_brc": (C.c_int, [_vp, _i32, _vp, _vp]),
     "failover_merge": (C.c_int, [_vp, _i32, _insp, _i32]),
     "stage_bubble": (C.c_int, [_vp, _i32, _f32]),
+    "stage_optimizer_init": (C.c_int, [_vp, _vp, _vp]),
+    "stage_apply": (C.c_int, [_vp, C.POINTER(Adam), _i32]),
+    "stage_sync_replica": (C.c_int, [_vp, _vp, _vp]),
     "stage_join": (C.c_int, [_vp]),
     "stage_sync": (C.c_int, [_vp]),
     "stage_destroy": (C.c_int, [_vp]),
@@ -83,6 +91,7 @@ _SIGS = {
     "bk_copy": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
     "bk_gemm_tile": (C.c_int, [C.c_int]),
     "bk_gemm_stages": (C.c_int, [C.c_int]),
+    "bk_adam": (C.c_int, [C.c_int, C.c_int64] + [_vp] * 5 + [C.c_float] * 4 + [C.c_int, _vp]),
 }
 EXPORTS = tuple(_SIGS)
 for _name, (_res, _args) in _SIGS.items():
@@ -177,6 +186,8 @@ class Stage:
         self.stream_main = torch.cuda.Stream(device=self.device)
         self.stream_frc = torch.cuda.Stream(device=self.device)
         self._h = C.c_void_p()
+        self.merged = False
+        self.own_opt = self.shadow_opt = None
         torch.cuda.synchronize(self.device)
         _check(lib.stage_init(C.byref(cfg), C.byref(sz), _ptr(self.own_w), _ptr(self.shadow_w), _ptr(self.own_g),
                               _ptr(self.shadow_g) if cfg.n_shadow > 0 else None, _ptr(self.own_stash),
@@ -232,7 +243,26 @@ class Stage:
         cap = 8 * self.cfg.M + 16
         arr = (Instr * cap)()
         n = _check(lib.failover_merge(self._h, k_fail, arr, cap), "failover_merge")
+        self.merged = True
         return _instr_list(arr, n)
+
+    def stage_optimizer_init(self):
+        """Allocates the optimizer state ([master | m | v] fp32 for own and replica parameters)
+        and has the library initialise it from the current parameters."""
+        torch = self.torch
+        self.own_opt = torch.empty(int(self.sizes.own_opt) // 4, dtype=torch.float32, device=self.device)
+        self.shadow_opt = None
+        if self.cfg.n_shadow > 0:
+            self.shadow_opt = torch.empty(int(self.sizes.shadow_opt) // 4, dtype=torch.float32, device=self.device)
+        torch.cuda.synchronize(self.device)
+        _check(lib.stage_optimizer_init(self._h, _ptr(self.own_opt), _ptr(self.shadow_opt)), "stage_optimizer_init")
+
+    def stage_apply(self, step, lr=6e-3, beta1=0.9, beta2=0.999, eps=1e-8):
+        hp = Adam(lr, beta1, beta2, eps)
+        _check(lib.stage_apply(self._h, C.byref(hp), step), "stage_apply")
+
+    def stage_sync_replica(self, successor_w, successor_opt=None):
+        _check(lib.stage_sync_replica(self._h, _ptr(successor_w), _ptr(successor_opt)), "stage_sync_replica")
 
     def stage_bubble(self, ticks, us_per_tick):
         _check(lib.stage_bubble(self._h, ticks, us_per_tick), "stage_bubble")
@@ -350,6 +380,12 @@ def bk_copy(src, dst, stream=None):
 def bk_gemm_tile(code):
     """Force the MFMA GEMM output tile (10*WM + WN; 0 = automatic); returns the previous code."""
     return _check(lib.bk_gemm_tile(code), "bk_gemm_tile")
+
+
+def bk_adam(g, master, m, v, w, step, lr=6e-3, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
+    """One Adam step on flat tensors: fp32 g, master, m, v; w = storage-dtype copy of the new master."""
+    _check(lib.bk_adam(_dt(w), master.numel(), _ptr(g), _ptr(master), _ptr(m), _ptr(v), _ptr(w), lr, beta1, beta2,
+                       eps, step, _stream(stream)), "bk_adam")
 
 
 def bk_gemm_stages(n):

@@ -149,6 +149,15 @@ size_t reduce_max_partials();
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);
+
+// ---- optimizer ------------------------------------------------------------------
+// Adam on n parameters (n a multiple of 4): fp32 gradient g, fp32 master weights and moments m, v
+// updated in place, w = storage-dtype copy of the new master weights.  step counts from 1.
+hipError_t launch_adam(hipStream_t s, int dtype, long n, const float* g, float* master, float* m, float* v, void* w,
+                       float lr, float beta1, float beta2, float eps, int step);
+// master[i] = (float) w[i]
+hipError_t launch_widen(hipStream_t s, int dtype, long n, const void* w, float* master);
+hipError_t launch_fill_zero(hipStream_t s, long n, float* p);
 hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 
 }  // namespace bamboo

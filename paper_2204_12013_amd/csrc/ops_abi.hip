@@ -139,6 +139,17 @@ int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
   return finish(launch_copy((hipStream_t)stream, src, dst, (size_t)bytes));
 }
 
+int bk_adam(int dtype, int64_t n, const float* g, float* master, float* m, float* v, void* w, float lr, float beta1,
+            float beta2, float eps, int step, void* stream) {
+  if (dtype != 0 && dtype != 1) return BAMBOO_E_ARG;
+  if (n <= 0 || n % 4 || step < 1 || !g || !master || !m || !v || !w) return BAMBOO_E_ARG;
+  const void* ptrs[] = {g, master, m, v, w};
+  for (const void* p : ptrs)
+    if (((uintptr_t)p) & 15) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_adam((hipStream_t)stream, dtype, (long)n, g, master, m, v, w, lr, beta1, beta2, eps, step));
+}
+
 int bk_gemm_tile(int code) {
   if (!gemm_tile_code_valid(code)) return BAMBOO_E_ARG;
   return set_gemm_tile(code);

@@ -160,6 +160,7 @@ struct bamboo_stage {
   std::vector<hipEvent_t> ev_fwd, ev_frc;
   hipEvent_t ev_join;
   int last_frc_on_lane1;
+  float* opt[2];      // own, shadow optimizer state [master | m | v], or null
   // optional per-kernel-class timing: an event pair around every launch
   bool prof_on;
   struct ProfRec { int cls; double work; hipEvent_t a, b; };
@@ -495,6 +496,8 @@ int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out) {
   out->own_stash = (uint64_t)out->c_own * cfg->n_own * rl.bytes;
   out->shadow_stash = (uint64_t)out->c_shadow * cfg->n_shadow * rl.bytes;
   out->workspace = lane_scratch(*cfg, true).bytes + lane_scratch(*cfg, false).bytes;
+  out->own_opt = po.count * cfg->n_own * 12;
+  out->shadow_opt = po.count * cfg->n_shadow * 12;
   return BAMBOO_OK;
 }
 
@@ -584,6 +587,7 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     st->ev_join = nullptr;
     st->last_frc_on_lane1 = -1;
     st->prof_on = false;
+    st->opt[0] = st->opt[1] = nullptr;
   } catch (const std::bad_alloc&) {
     delete st;
     return BAMBOO_E_NOMEM;
@@ -693,6 +697,56 @@ int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int3
   st->merged = true;
   st->program.swap(prog);
   return n;
+}
+
+int stage_optimizer_init(bamboo_stage_t* st, void* own_opt, void* shadow_opt) {
+  if (!st || !own_opt) return BAMBOO_E_ARG;
+  if (st->cfg.n_shadow > 0 && !shadow_opt) return BAMBOO_E_ARG;
+  if (((uintptr_t)own_opt) % kAlign || ((uintptr_t)shadow_opt) % kAlign) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  void* bufs[2] = {own_opt, st->cfg.n_shadow > 0 ? shadow_opt : nullptr};
+  for (int kind = 0; kind < 2; ++kind) {
+    st->opt[kind] = (float*)bufs[kind];
+    if (!bufs[kind]) continue;
+    const long n = (long)st->po.count * (kind == 0 ? st->cfg.n_own : st->cfg.n_shadow);
+    HIPCHK(launch_widen(st->lane[0], st->cfg.dtype, n, st->w[kind], st->opt[kind]));
+    HIPCHK(launch_fill_zero(st->lane[0], 2 * n, st->opt[kind] + n));
+  }
+  return BAMBOO_OK;
+}
+
+int stage_apply(bamboo_stage_t* st, const bamboo_adam_t* hp, int32_t step) {
+  if (!st || !hp) return BAMBOO_E_ARG;
+  if (step < 1 || !(hp->lr >= 0.f) || !(hp->beta1 >= 0.f && hp->beta1 < 1.f) || !(hp->beta2 >= 0.f && hp->beta2 < 1.f) ||
+      !(hp->eps > 0.f))
+    return BAMBOO_E_ARG;
+  if (!st->opt[0]) return BAMBOO_E_STATE;
+  (void)hipGetLastError();
+  const int kinds = st->merged ? 2 : 1;     // the merged stage owns the victim's layers too
+  for (int kind = 0; kind < kinds; ++kind) {
+    if (!st->opt[kind]) return BAMBOO_E_STATE;
+    const long n = (long)st->po.count * (kind == 0 ? st->cfg.n_own : st->cfg.n_shadow);
+    float* o = st->opt[kind];
+    HIPCHK(launch_adam(st->lane[0], st->cfg.dtype, n, st->g[kind], o, o + n, o + 2 * n, (void*)st->w[kind], hp->lr,
+                       hp->beta1, hp->beta2, hp->eps, step));
+  }
+  return BAMBOO_OK;
+}
+
+int stage_sync_replica(bamboo_stage_t* st, const void* successor_w, const void* successor_opt) {
+  if (!st || !successor_w) return BAMBOO_E_ARG;
+  if (st->cfg.n_shadow <= 0 || st->merged) return BAMBOO_E_STATE;   // no replica / the victim is gone
+  if (successor_opt && !st->opt[1]) return BAMBOO_E_STATE;
+  (void)hipGetLastError();
+  // lane 1 may still be reading the replica parameters (FRC of the iteration that just ended)
+  HIPCHK(hipEventRecord(st->ev_join, st->lane[1]));
+  HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_join, 0));
+  HIPCHK(launch_copy(st->lane[0], successor_w, (void*)st->w[1], st->sizes.shadow_w));
+  if (successor_opt) HIPCHK(launch_copy(st->lane[0], successor_opt, st->opt[1], st->sizes.shadow_opt));
+  // and the next iteration's FRC on lane 1 must see the new values
+  HIPCHK(hipEventRecord(st->ev_join, st->lane[0]));
+  HIPCHK(hipStreamWaitEvent(st->lane[1], st->ev_join, 0));
+  return BAMBOO_OK;
 }
 
 int stage_bubble(bamboo_stage_t* st, int32_t ticks, float us_per_tick) {

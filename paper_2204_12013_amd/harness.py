@@ -12,12 +12,14 @@ from . import binding as B
 
 
 class StageHarness:
-    def __init__(self, stage, x, gz, successor=None, gy_table=None, us_per_tick=0.0):
+    def __init__(self, stage, x, gz, successor=None, gy_table=None, us_per_tick=0.0, adam=None):
         self.st = stage
         self.x, self.gz = x, gz
         self.succ = successor
         self.gy_table = gy_table
         self.us_per_tick = us_per_tick
+        self.adam = adam          # dict of Adam hyper-parameters: APPLY then runs the optimizer step
+        self.step = 0
         M = stage.cfg.M
         self.y = [stage.new_act() for _ in range(M)]
         self.gx = [stage.new_act() for _ in range(M)]
@@ -76,6 +78,15 @@ class StageHarness:
                     st.stage_bubble(arg, self.us_per_tick)
             elif op == B.JOIN:
                 st.stage_join()
+            elif op == B.APPLY and self.adam is not None:
+                # the stage and its (live) successor both update; the replica then takes the
+                # successor's new parameters and optimizer state
+                self.step += 1
+                st.stage_apply(self.step, **self.adam)
+                if self.succ is not None and not st.merged:
+                    self.succ.stage_apply(self.step, **self.adam)
+                    st.stream_main.wait_stream(self.succ.stream_main)
+                    st.stage_sync_replica(self.succ.own_w, self.succ.own_opt)
             # SEND_*, RECV_ACT, ALLREDUCE, APPLY: placeholders on one GPU
         return self
 
