@@ -16,6 +16,10 @@ An instruction is a tuple (op, lane, mb, arg):
 """
 
 RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, FWD, BWD, FRC, BRC, BUBBLE, JOIN, ALLREDUCE, APPLY = range(12)
+
+# Redundant-computation variants compared in the paper's microbenchmarks (Section 7.4, Table 4):
+# lazy FRC + lazy BRC, eager FRC + lazy BRC (Bamboo's choice), eager FRC + eager BRC.
+LFLB, EFLB, EFEB = 0, 1, 2
 OP_NAMES = ("RECV_ACT", "SEND_ACT", "RECV_GRAD", "SEND_GRAD", "FWD", "BWD",
             "FRC", "BRC", "BUBBLE", "JOIN", "ALLREDUCE", "APPLY")
 
@@ -103,18 +107,31 @@ def _head_comm(prev, cur, P, s):
     return out
 
 
-def stage_program(P, s, M, frc=True, tick_F=1, tick_B=2, bubbles=True):
-    """Instruction list of stage s for one iteration (no failure)."""
+def stage_program(P, s, M, frc=True, tick_F=1, tick_B=2, bubbles=True, rc=None):
+    """Instruction list of stage s for one iteration (no failure).
+
+    rc (overrides frc): LFLB emits no redundant computation at all; EFLB emits FRC(k) on lane 1
+    right after FWD(k); EFEB additionally emits BRC(k) on lane 1 as soon as the upstream gradient
+    of the successor's layers exists, i.e. where the stage starts to wait for the successor's
+    backward of micro-batch k (the receive from the stage after the successor comes with it).
+    """
+    if rc is None:
+        rc = EFLB if frc else LFLB
+    frc = rc != LFLB
     seq = compute_order(P, s, M)
     C = own_slots(P, s, M)
     start, end, makespan = timeline(P, M, tick_F, tick_B)
     prog, prev, clock = [], None, 0
     for j, cur in enumerate(seq):
         gap = start[s][j] - clock
+        kind, k = cur
+        if rc == EFEB and kind == "B" and s < P - 1:
+            if s + 2 < P:
+                prog.append((RECV_GRAD, 1, k, s + 2))
+            prog.append((BRC, 1, k, k))
         if bubbles and gap > 0:
             prog.append((BUBBLE, 0, -1, gap))
         prog += _head_comm(prev, cur, P, s)
-        kind, k = cur
         if kind == "F":
             prog.append((FWD, 0, k, k % C))
             if frc:
@@ -139,18 +156,24 @@ def lost_backwards(P, s, M, k_fail):
     return sum(1 for kind, _ in seq[:j] if kind == "B")
 
 
-def prefix_until_failure(P, s, M, k_fail, frc=True, tick_F=1, tick_B=2, bubbles=True):
+def prefix_until_failure(P, s, M, k_fail, frc=True, tick_F=1, tick_B=2, bubbles=True, rc=None):
     """The part of the normal program that ran before the failure was detected:
     everything up to and including FWD(k_fail) and its FRC."""
-    prog = stage_program(P, s, M, frc, tick_F, tick_B, bubbles)
+    prog = stage_program(P, s, M, frc, tick_F, tick_B, bubbles, rc)
     last = max(i for i, ins in enumerate(prog)
                if ins[2] == k_fail and ins[0] in (FWD, FRC))
     return prog[:last + 1]
 
 
-def failover_program(P, s, M, k_fail):
+def failover_program(P, s, M, k_fail, rc=EFLB):
     """Failover schedule of shadow stage s after its successor s+1 is lost while
     stage s tries to send it the activation of micro-batch k_fail.
+
+    rc = EFLB is the paper's design and the description below.  With EFEB step (ii) is empty
+    (BRC of those micro-batches already ran, eagerly).  With LFLB nothing redundant has been
+    computed yet: step (ii) runs FRC before each BRC, and the FRC of the micro-batches the
+    victim had forwarded but not yet back-propagated follows before step (iii) -- this is the
+    longer pause that eager FRC avoids (Section 7.4).
 
     (i)   wait for the FRC stream up to FRC(k_fail);
     (ii)  replay: BRC over the micro-batches whose successor-side backward had
@@ -165,10 +188,15 @@ def failover_program(P, s, M, k_fail):
     has_far = s + 2 < P                     # the victim had a successor of its own
     b = lost_backwards(P, s, M, k_fail)
     prog = [(JOIN, 0, -1, k_fail)]
-    for k in range(b):
-        if has_far:
-            prog.append((RECV_GRAD, 0, k, s + 2))
-        prog.append((BRC, 0, k, k))
+    if rc != EFEB:
+        for k in range(b):
+            if has_far:
+                prog.append((RECV_GRAD, 0, k, s + 2))
+            if rc == LFLB:
+                prog.append((FRC, 0, k, k))
+            prog.append((BRC, 0, k, k))
+    if rc == LFLB:
+        prog += [(FRC, 0, k, k) for k in range(b, k_fail + 1)]
     rest = seq[seq.index(("F", k_fail)) + 1:]
     # groups: a backward starts a new group; a forward joins the group of the
     # backward just before it (backward work is ordered first inside a group)

@@ -111,13 +111,13 @@ class StageSim:
         return self
 
 
-def run_no_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, frc=True, eps=1e-5):
+def run_no_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, frc=True, eps=1e-5, rc=None):
     sim = StageSim(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, eps)
-    return sim.run(S.stage_program(P, s, M, frc=frc))
+    return sim.run(S.stage_program(P, s, M, frc=frc, rc=rc))
 
 
-def run_with_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, k_fail, eps=1e-5):
+def run_with_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, k_fail, eps=1e-5, rc=S.EFLB):
     sim = StageSim(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, eps)
-    sim.run(S.prefix_until_failure(P, s, M, k_fail))
+    sim.run(S.prefix_until_failure(P, s, M, k_fail, rc=rc))
     sim.preempt_successor()
-    return sim.run(S.failover_program(P, s, M, k_fail))
+    return sim.run(S.failover_program(P, s, M, k_fail, rc=rc))

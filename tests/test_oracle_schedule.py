@@ -187,3 +187,43 @@ def test_failover_example_of_the_bert_stage():
                            "SEND_ACT(5) RECV_GRAD(3) RECV_ACT(6) BRC(3) BWD(3) FWD(6) FRC(6) "
                            "SEND_ACT(6) RECV_GRAD(4) SEND_GRAD(3) RECV_ACT(7) BRC(4) BWD(4) FWD(7) FRC(7)")
     assert text.endswith("BRC(7) BWD(7) SEND_GRAD(7) JOIN ALLREDUCE APPLY")
+
+
+def test_rc_variant_programs():
+    """The three redundant-computation variants of Section 7.4 (Table 4) as instruction lists."""
+    for P, M in itertools.product(range(2, 6), range(1, 6)):
+        for s in range(P - 1):
+            base = S.stage_program(P, s, M, rc=S.EFLB)
+            assert base == S.stage_program(P, s, M, frc=True)
+            lazy = S.stage_program(P, s, M, rc=S.LFLB)
+            assert lazy == S.stage_program(P, s, M, frc=False) == [i for i in base if i[0] != S.FRC]
+            eager = S.stage_program(P, s, M, rc=S.EFEB)
+            # the eager-BRC program is the EFLB program plus, on lane 1, BRC(k) (and the receive of its
+            # upstream gradient from the stage after the successor) ahead of the wait for BWD(k)
+            assert [i for i in eager if i[1] == 0 or i[0] == S.FRC] == base
+            extra = [i for i in eager if i[1] == 1 and i[0] != S.FRC]
+            assert [i for i in extra if i[0] == S.BRC] == [(S.BRC, 1, k, k) for k in range(M)]
+            assert len([i for i in extra if i[0] == S.RECV_GRAD]) == (M if s + 2 < P else 0)
+            for k in range(M):
+                i_brc = eager.index((S.BRC, 1, k, k))
+                assert eager.index((S.FRC, 1, k, k)) < i_brc < eager.index((S.BWD, 0, k, k % S.own_slots(P, s, M)))
+                nxt = [i for i in eager[i_brc + 1:] if i[0] != S.BUBBLE][0]
+                assert nxt[0] in (S.SEND_ACT, S.SEND_GRAD, S.RECV_GRAD)     # issued before the stage waits
+            for k_fail in range(M):
+                b = S.lost_backwards(P, s, M, k_fail)
+                f1 = S.failover_program(P, s, M, k_fail, rc=S.EFLB)
+                f2 = S.failover_program(P, s, M, k_fail, rc=S.EFEB)
+                f0 = S.failover_program(P, s, M, k_fail, rc=S.LFLB)
+                n_replay = b * (2 if s + 2 < P else 1)
+                assert f2 == f1[:1] + f1[1 + n_replay:]                     # no replay: BRC already ran
+                # lazy FRC: every FRC of the iteration happens after the failure, each before its BRC
+                whole = S.prefix_until_failure(P, s, M, k_fail, rc=S.LFLB) + f0
+                for k in range(M):
+                    assert sum(1 for i in whole if i[0] == S.FRC and i[2] == k) == 1
+                    assert sum(1 for i in whole if i[0] == S.BRC and i[2] == k) == 1
+                    assert whole.index((S.FRC, 0, k, k)) < whole.index((S.BRC, 0, k, k))
+                assert [i[2] for i in whole if i[0] == S.BRC] == list(range(M))
+                rest = lambda f: [i for i in f if i[0] != S.FRC or i[2] > k_fail]
+                assert rest(f0) == rest(f1)
+                whole2 = S.prefix_until_failure(P, s, M, k_fail, rc=S.EFEB) + f2
+                assert [i[2] for i in whole2 if i[0] == S.BRC] == list(range(M))

@@ -104,3 +104,35 @@ def test_too_small_own_stash_is_detected():
 def test_record_index():
     assert St.stash_record_index(0, 0, 6) == 0
     assert St.stash_record_index(2, 3, 6) == 15
+
+
+@pytest.mark.parametrize("rc", [S.LFLB, S.EFLB, S.EFEB])
+def test_every_rc_variant_recovers_the_failure_free_gradients(rc):
+    """Section 7.4 compares lazy/eager FRC and BRC: whatever is computed eagerly, a preemption must
+    end with the gradients of the failure-free run (brute force over tiny pipelines, every k_fail)."""
+    for P, s, M in [(3, 0, 4), (4, 1, 5), (2, 0, 3)]:
+        args = _setup(0, P, s, M, seed=P * 10 + M)
+        ref = St.run_no_failure(*args)
+        for k_fail in range(M):
+            sim = St.run_with_failure(*args, k_fail, rc=rc)
+            for l in range(len(ref.G_own)):
+                for n in L.PARAM_NAMES:
+                    assert np.array_equal(sim.G_own[l][n], ref.G_own[l][n]), (P, s, M, k_fail, n)
+                    assert np.array_equal(sim.G_shadow[l][n], ref.G_succ[l][n]), (P, s, M, k_fail, n)
+            for k in range(M):
+                assert np.array_equal(sim.gx[k], ref.gx[k])
+                assert np.array_equal(sim.z_frc[k], ref.z_succ[k])
+            assert not sim.own_stash and not sim.shadow_stash
+
+
+def test_eager_brc_without_failure_reproduces_the_successors_gradients():
+    args = _setup(1, 4, 1, 5, n_own=2, n_shadow=2)
+    sim = St.run_no_failure(*args, rc=S.EFEB)
+    for l in range(2):
+        for n in L.PARAM_NAMES:
+            assert np.array_equal(sim.G_shadow[l][n], sim.G_succ[l][n])
+    assert not sim.shadow_stash                                 # every FRC stash was consumed by its BRC
+    lazy = St.run_no_failure(*args, rc=S.LFLB)
+    assert not lazy.z_frc and not lazy.shadow_stash
+    for k in range(5):
+        assert np.array_equal(lazy.gx[k], sim.gx[k])
