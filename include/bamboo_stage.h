@@ -58,6 +58,16 @@ enum bamboo_dtype {
   BAMBOO_BF16 = 1 /* bf16 weights and activations, fp32 accumulation, fp32 gradients */
 };
 
+/* Redundant-computation variants (Section 7.4, Table 4).  Bamboo's design is eager FRC + lazy
+ * BRC; the other two are what the paper measures it against.
+ *   LFLB  nothing redundant runs until a preemption; the failover schedule then runs FRC before
+ *         every BRC (longer pause).  Also the setting for "redundancy off" (the schedule is the same).
+ *   EFLB  FRC(k) on lane 1 right after FWD(k); BRC only after a preemption.
+ *   EFEB  as EFLB, and BRC(k) on lane 1 as soon as the upstream gradient of the successor's layers
+ *         exists (where the stage starts to wait for the successor's backward of micro-batch k);
+ *         after a preemption nothing has to be replayed. */
+enum bamboo_rc_mode { BAMBOO_RC_LFLB = 0, BAMBOO_RC_EFLB = 1, BAMBOO_RC_EFEB = 2 };
+
 /* Configuration of one stage (Section 4: the schedule is a static function of
  * the stage id, the pipeline depth and the number of micro-batches). */
 typedef struct {
@@ -73,7 +83,7 @@ typedef struct {
   int32_t P;           /* pipeline depth */
   int32_t stage_id;    /* 0-indexed forward stage id (Section 5.1) */
   int32_t M;           /* micro-batches per iteration, <= 32767 */
-  int32_t frc_enabled; /* emit and allow FRC */
+  int32_t rc_mode;     /* enum bamboo_rc_mode: which redundant computation runs eagerly */
   int32_t tick_F;      /* slot-timeline duration of a forward (>= 1) */
   int32_t tick_B;      /* slot-timeline duration of a backward (>= 1) */
   float ln_eps;        /* LayerNorm epsilon */

@@ -28,7 +28,7 @@ KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd"
 class Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("arch", "dtype", "hidden", "heads", "ffn", "seq", "micro_batch", "n_own", "n_shadow",
-                 "P", "stage_id", "M", "frc_enabled", "tick_F", "tick_B")] + [("ln_eps", C.c_float)]
+                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float)]
 
 
 class Instr(C.Structure):
@@ -105,11 +105,17 @@ def _check(status, where):
     return status
 
 
-def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, **override):
+RC_LFLB, RC_EFLB, RC_EFEB = 0, 1, 2
+
+
+def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, rc_mode=None, **override):
+    """rc_mode (RC_LFLB / RC_EFLB / RC_EFEB) overrides frc_enabled (True = EFLB, False = LFLB)."""
+    if rc_mode is None:
+        rc_mode = RC_EFLB if frc_enabled else RC_LFLB
     """Cfg from a synth.StageConfig (or anything with the same attributes)."""
     vals = dict(arch=sc.arch, dtype=sc.dtype, hidden=sc.hidden, heads=sc.heads, ffn=sc.ffn, seq=sc.seq,
                 micro_batch=sc.micro_batch, n_own=sc.n_own, n_shadow=sc.n_shadow, P=sc.P,
-                stage_id=sc.stage_id, M=sc.M, frc_enabled=int(frc_enabled), tick_F=tick_F, tick_B=tick_B,
+                stage_id=sc.stage_id, M=sc.M, rc_mode=int(rc_mode), tick_F=tick_F, tick_B=tick_B,
                 ln_eps=ln_eps)
     vals.update(override)
     return Cfg(**vals)
@@ -240,7 +246,7 @@ class Stage:
         _check(lib.shadow_bwd_brc(self._h, k, _ptr(gz), _ptr(gy)), "shadow_bwd_brc")
 
     def failover_merge(self, k_fail):
-        cap = 8 * self.cfg.M + 16
+        cap = 16 * self.cfg.M + 32
         arr = (Instr * cap)()
         n = _check(lib.failover_merge(self._h, k_fail, arr, cap), "failover_merge")
         self.merged = True

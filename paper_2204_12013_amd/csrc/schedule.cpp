@@ -99,9 +99,16 @@ std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c) {
   const int slots = own_slot_count(P, s, M);
   int tail = 0;
   const std::vector<int> gaps = idle_before(P, s, M, c.tick_F, c.tick_B, &tail);
-  const bool frc = c.frc_enabled && c.n_shadow > 0;
+  const bool frc = c.rc_mode != BAMBOO_RC_LFLB && c.n_shadow > 0;
+  const bool eager_brc = c.rc_mode == BAMBOO_RC_EFEB && c.n_shadow > 0 && s < P - 1;
   std::vector<bamboo_instr_t> out;
   for (size_t j = 0; j < seq.size(); ++j) {
+    if (eager_brc && seq[j].backward) {
+      // eager BRC (Section 7.4): issued on lane 1 where the stage starts to wait for the successor's
+      // backward of this micro-batch; its upstream gradient comes from the stage after the successor
+      if (s + 2 < P) out.push_back(ins(BAMBOO_RECV_GRAD, 1, seq[j].mb, s + 2));
+      out.push_back(ins(BAMBOO_BRC, 1, seq[j].mb, seq[j].mb));
+    }
     if (gaps[j] > 0) out.push_back(ins(BAMBOO_BUBBLE, 0, -1, gaps[j]));
     group_head(out, j ? &seq[j - 1] : nullptr, &seq[j], P, s);
     const int k = seq[j].mb;
@@ -140,10 +147,17 @@ std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_
   while (at < seq.size() && !(!seq[at].backward && seq[at].mb == k_fail)) lost += seq[at++].backward ? 1 : 0;
   std::vector<bamboo_instr_t> out;
   out.push_back(ins(BAMBOO_JOIN, 0, -1, k_fail));
-  for (int k = 0; k < lost; ++k) {
-    if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, s + 2));
-    out.push_back(ins(BAMBOO_BRC, 0, k, k));
-  }
+  // Variants (Section 7.4): with eager BRC the lost gradients were never only the victim's, so
+  // nothing is replayed; with lazy FRC nothing redundant exists yet, so FRC runs before every BRC
+  // and the micro-batches the victim had forwarded but not back-propagated are forwarded again.
+  if (c.rc_mode != BAMBOO_RC_EFEB)
+    for (int k = 0; k < lost; ++k) {
+      if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, s + 2));
+      if (c.rc_mode == BAMBOO_RC_LFLB) out.push_back(ins(BAMBOO_FRC, 0, k, k));
+      out.push_back(ins(BAMBOO_BRC, 0, k, k));
+    }
+  if (c.rc_mode == BAMBOO_RC_LFLB)
+    for (int k = lost; k <= k_fail; ++k) out.push_back(ins(BAMBOO_FRC, 0, k, k));
   std::vector<int> z_pending{k_fail};  // FRC outputs the far stage still has to get
   std::vector<int> gx_pending;          // input gradients not yet sent back
   size_t j = at + 1;

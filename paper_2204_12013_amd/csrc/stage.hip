@@ -129,6 +129,7 @@ int validate(const bamboo_cfg_t* c) {
   if (c->seq <= 0 || c->micro_batch <= 0 || c->n_own <= 0 || c->n_shadow < 0) return BAMBOO_E_BADCFG;
   if (c->P <= 0 || c->stage_id < 0 || c->stage_id >= c->P || c->M <= 0 || c->M > 32767) return BAMBOO_E_BADCFG;
   if (c->tick_F < 1 || c->tick_B < 1 || !(c->ln_eps >= 0.f)) return BAMBOO_E_BADCFG;
+  if (c->rc_mode != BAMBOO_RC_LFLB && c->rc_mode != BAMBOO_RC_EFLB && c->rc_mode != BAMBOO_RC_EFEB) return BAMBOO_E_BADCFG;
   if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
   return BAMBOO_OK;
 }
@@ -248,13 +249,13 @@ int p_ln_fwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* r, const
 }
 // LayerNorm backward: dr, plus partial rows of the gain / shift gradients and (pc != nullptr) of the
 // column sums of dr; their ordered final sums into dgamma / dbeta / dbias are queued in `batch`
-int p_ln_bwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* dout, const void* r, const float* stats,
+int p_ln_bwd(bamboo_stage* st, hipStream_t s, char* ws, int T, int H, const void* dout, const void* r, const float* stats,
              const void* gamma, const void* add, void* dr, float* dgamma, float* dbeta, float* dbias,
              const uint64_t (&poff)[3], GradReduceBatch* batch) {
   ProfScope ps(st, K_LN_BWD, s, (double)T * ((add ? 4.0 : 3.0) * H * esize(st) + 8.0));
-  float* pg = (float*)(st->wsbase + poff[0]);
-  float* pb = (float*)(st->wsbase + poff[1]);
-  float* pc = dbias ? (float*)(st->wsbase + poff[2]) : nullptr;
+  float* pg = (float*)(ws + poff[0]);      // ws: the scratch area of the lane the backward runs on
+  float* pb = (float*)(ws + poff[1]);
+  float* pc = dbias ? (float*)(ws + poff[2]) : nullptr;
   int parts = 0;
   HIPCHK(launch_layernorm_bwd_partials(s, st->cfg.dtype, T, H, dout, r, stats, gamma, add, dr, pg, pb, pc, &parts));
   if (!grad_reduce_add(batch, H, parts, pg, dgamma, pb, dbeta)) return BAMBOO_E_STATE;
@@ -262,10 +263,10 @@ int p_ln_bwd(bamboo_stage* st, hipStream_t s, int T, int H, const void* dout, co
   return BAMBOO_OK;
 }
 // partial rows of the column sums of a[T,N]; the final sum into `out` is queued in `batch`
-int p_colsum(bamboo_stage* st, hipStream_t s, int T, int N, const void* a, float* out, uint64_t poff,
+int p_colsum(bamboo_stage* st, hipStream_t s, char* ws, int T, int N, const void* a, float* out, uint64_t poff,
              GradReduceBatch* batch) {
   ProfScope ps(st, K_COLSUM, s, (double)T * N * esize(st));
-  float* p = (float*)(st->wsbase + poff);
+  float* p = (float*)(ws + poff);
   int parts = 0;
   HIPCHK(launch_colsum_partials(s, st->cfg.dtype, T, N, a, p, &parts));
   if (!grad_reduce_add(batch, N, parts, p, out, nullptr, nullptr)) return BAMBOO_E_STATE;
@@ -364,16 +365,16 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
   return BAMBOO_OK;
 }
 
-// backward of one layer stack on lane 0; gx may be null (input gradient discarded)
-int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx) {
+// backward of one layer stack; gx may be null (input gradient discarded).  Lane 1 only with eager BRC.
+int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* gy, void* gx) {
   const bamboo_cfg_t& c = st->cfg;
   const int n = kind == 0 ? c.n_own : c.n_shadow;
   const int T = c.micro_batch * c.seq, H = c.hidden, F = c.ffn;
   const uint64_t es = esize(st);
-  hipStream_t s = st->lane[0];
+  hipStream_t s = st->lane[lane_id];
   (void)hipGetLastError();
-  char* ws = st->wsbase;
-  const LaneScratch& w = st->ws0;
+  char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
+  const LaneScratch& w = lane_id == 0 ? st->ws0 : st->ws1;
   void* dh = ws + w.dh;
   void* d1 = ws + w.d1;
   void* d2 = ws + w.d2;
@@ -403,12 +404,12 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     GemmDesc d;
     const void* df;     // gradient at the FFN output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
-      BBCHK(p_ln_bwd(st, s, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
+      BBCHK(p_ln_bwd(st, s, ws, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
                      G + st->po.g2, G + st->po.be2, G + st->po.b2, w.p_ln[1], &batch));
       df = d1;
     } else {
       df = dy;
-      BBCHK(p_colsum(st, s, T, H, df, G + st->po.b2, w.p_df, &batch));
+      BBCHK(p_colsum(st, s, ws, T, H, df, G + st->po.b2, w.p_df, &batch));
     }
     // f = g W2 + b2
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_MUL);   // through the activation: times GELU'(h)
@@ -416,19 +417,19 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     BBCHK(p_gemm(st, s, d));
     BBCHK(p_gemm(st, s, gemm_tn(rec + r.g, df, G + st->po.W2, T, F, H)));
     // h = fin W1 + b1
-    BBCHK(p_colsum(st, s, T, F, dh, G + st->po.b1, w.p_dh, &batch));
+    BBCHK(p_colsum(st, s, ws, T, F, dh, G + st->po.b1, w.p_dh, &batch));
     BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
       d.res = d1;
       BBCHK(p_gemm(st, s, d));
-      BBCHK(p_ln_bwd(st, s, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
+      BBCHK(p_ln_bwd(st, s, ws, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
                      G + st->po.g1, G + st->po.be1, G + st->po.bo, w.p_ln[0], &batch));
       da = d1;
     } else {
       BBCHK(p_gemm(st, s, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
-      BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
+      BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
                      G + st->po.g2, G + st->po.be2, G + st->po.bo, w.p_ln[1], &batch));   // + residual branch of y = x1 + f
       da = d2;
     }
@@ -437,7 +438,7 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
     BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
     BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
-    BBCHK(p_colsum(st, s, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
+    BBCHK(p_colsum(st, s, ws, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
     BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
@@ -445,7 +446,7 @@ int run_backward(bamboo_stage* st, int kind, int slot, const void* gy, void* gx)
       BBCHK(p_gemm(st, s, d));
     } else {
       BBCHK(p_gemm(st, s, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
-      BBCHK(p_ln_bwd(st, s, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
+      BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
                      G + st->po.g1, G + st->po.be1, nullptr, w.p_ln[0], &batch));   // + residual branch of x1 = x + a
     }
     BBCHK(p_grad_reduce(st, s, batch));
@@ -495,7 +496,7 @@ int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out) {
   out->c_shadow = cfg->n_shadow > 0 ? cfg->M : 0;
   out->own_stash = (uint64_t)out->c_own * cfg->n_own * rl.bytes;
   out->shadow_stash = (uint64_t)out->c_shadow * cfg->n_shadow * rl.bytes;
-  out->workspace = lane_scratch(*cfg, true).bytes + lane_scratch(*cfg, false).bytes;
+  out->workspace = lane_scratch(*cfg, true).bytes + lane_scratch(*cfg, cfg->rc_mode == BAMBOO_RC_EFEB).bytes;
   out->own_opt = po.count * cfg->n_own * 12;
   out->shadow_opt = po.count * cfg->n_shadow * 12;
   return BAMBOO_OK;
@@ -566,7 +567,7 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     st->po = param_offsets(cfg->hidden, cfg->ffn);
     st->rl = record_layout(*cfg);
     st->ws0 = lane_scratch(*cfg, true);
-    st->ws1 = lane_scratch(*cfg, false);
+    st->ws1 = lane_scratch(*cfg, cfg->rc_mode == BAMBOO_RC_EFEB);   // lane 1 runs backwards only with eager BRC
     st->w[0] = (const char*)own_w;
     st->w[1] = (const char*)shadow_w;
     st->g[0] = (float*)own_g;
@@ -633,7 +634,8 @@ int stage_fwd(bamboo_stage_t* st, int32_t k, const void* x, void* y) {
 
 int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z) {
   if (!st || !y) return BAMBOO_E_ARG;
-  if (st->cfg.n_shadow <= 0 || !st->cfg.frc_enabled) return BAMBOO_E_STATE;
+  // lazy FRC: only the failover schedule runs it
+  if (st->cfg.n_shadow <= 0 || (st->cfg.rc_mode == BAMBOO_RC_LFLB && !st->merged)) return BAMBOO_E_STATE;
   if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
   if (!st->fwd_issued[k] || st->frc_issued[k]) return BAMBOO_E_BADMB;
   const int lane_id = st->merged ? 0 : 1;
@@ -661,7 +663,7 @@ int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx) {
   if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
   const int slot = k % st->sizes.c_own;
   if (st->own_slot_mb[slot] != k) return BAMBOO_E_BADMB;
-  const int rc = run_backward(st, 0, slot, gy, gx);
+  const int rc = run_backward(st, 0, 0, slot, gy, gx);
   if (rc != BAMBOO_OK) return rc;
   st->own_slot_mb[slot] = -1;
   return BAMBOO_OK;
@@ -669,11 +671,14 @@ int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx) {
 
 int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy) {
   if (!st || !gz) return BAMBOO_E_ARG;
-  if (st->cfg.n_shadow <= 0 || !st->merged) return BAMBOO_E_STATE;
+  // lazy BRC runs after a preemption only; eager BRC (EFEB) also before, on the FRC lane
+  if (st->cfg.n_shadow <= 0 || (!st->merged && st->cfg.rc_mode != BAMBOO_RC_EFEB)) return BAMBOO_E_STATE;
   if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
   if (!st->shadow_live[k]) return BAMBOO_E_STATE;
-  if (st->ev_frc[k] != nullptr) HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_frc[k], 0));
-  const int rc = run_backward(st, 1, k, gz, gy);
+  const int lane_id = st->merged ? 0 : 1;
+  // on lane 1 BRC(k) follows FRC(k) in stream order; on lane 0 it waits for an FRC issued on lane 1
+  if (lane_id == 0 && st->ev_frc[k] != nullptr) HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_frc[k], 0));
+  const int rc = run_backward(st, 1, lane_id, k, gz, gy);
   if (rc != BAMBOO_OK) return rc;
   st->shadow_live[k] = 0;
   return BAMBOO_OK;

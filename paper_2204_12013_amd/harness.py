@@ -68,7 +68,9 @@ class StageHarness:
                 st.stage_bwd(k, self.gy[k], self.gx[k])
                 self.bwd_done.add(k)
             elif op == B.BRC:
-                if k in self.bwd_done:            # replayed: own backward already ran
+                if not st.merged:                 # eager BRC beside a live successor: its g_y is the
+                    st.shadow_bwd_brc(k, self.gz[k], None)      # successor's to deliver, ours is dropped
+                elif k in self.bwd_done:          # replayed: own backward already ran
                     self.gy_replay[k] = st.new_act()
                     st.shadow_bwd_brc(k, self.gz[k], self.gy_replay[k])
                 else:

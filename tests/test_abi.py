@@ -40,20 +40,20 @@ def test_op_codes_agree():
 
 def _cfg(P, s, M, frc=1, n_shadow=1, tick_F=1, tick_B=2):
     return B.Cfg(arch=0, dtype=0, hidden=64, heads=2, ffn=256, seq=16, micro_batch=2, n_own=1, n_shadow=n_shadow,
-                 P=P, stage_id=s, M=M, frc_enabled=frc, tick_F=tick_F, tick_B=tick_B, ln_eps=1e-5)
+                 P=P, stage_id=s, M=M, rc_mode=int(frc), tick_F=tick_F, tick_B=tick_B, ln_eps=1e-5)
 
 
 def test_program_equals_oracle_bit_exact():
     n = 0
     for P, M in itertools.product(range(1, 7), [1, 2, 3, 4, 5, 8, 16]):
         for s in range(P):
-            for frc in (0, 1):
+            for rc in (S.LFLB, S.EFLB, S.EFEB):
                 for tf, tb in ((1, 2), (2, 3)):
-                    got = B.stage_program(_cfg(P, s, M, frc, tick_F=tf, tick_B=tb))
-                    want = S.stage_program(P, s, M, frc=bool(frc), tick_F=tf, tick_B=tb)
-                    assert got == want, (P, s, M, frc)
+                    got = B.stage_program(_cfg(P, s, M, rc, tick_F=tf, tick_B=tb))
+                    want = S.stage_program(P, s, M, rc=rc, tick_F=tf, tick_B=tb)
+                    assert got == want, (P, s, M, rc)
                     n += 1
-    assert n > 300
+    assert n > 450
     # FRC disabled by having no replica layers
     assert B.stage_program(_cfg(4, 1, 8, 1, n_shadow=0)) == S.stage_program(4, 1, 8, frc=False)
 
@@ -62,8 +62,9 @@ def test_failover_program_equals_oracle_bit_exact():
     for P, M in itertools.product(range(2, 7), [1, 2, 3, 5, 8, 16]):
         for s in range(P - 1):
             for k_fail in range(M):
-                got = B.stage_failover_program(_cfg(P, s, M), k_fail)
-                assert got == S.failover_program(P, s, M, k_fail), (P, s, M, k_fail)
+                for rc in (S.LFLB, S.EFLB, S.EFEB):
+                    got = B.stage_failover_program(_cfg(P, s, M, rc), k_fail)
+                    assert got == S.failover_program(P, s, M, k_fail, rc=rc), (P, s, M, k_fail, rc)
 
 
 def test_workload_table_programs():
@@ -103,7 +104,8 @@ def test_sizes_and_record_addresses():
 def test_bad_configurations_are_rejected():
     sc = synth.CONFIGS["tiny"]
     for bad in (dict(heads=3), dict(hidden=60), dict(stage_id=2), dict(M=0), dict(arch=2), dict(dtype=5),
-                dict(tick_F=0), dict(n_own=0), dict(heads=0), dict(hidden=2048, heads=8), dict(M=40000)):
+                dict(tick_F=0), dict(n_own=0), dict(heads=0), dict(hidden=2048, heads=8), dict(M=40000),
+                dict(rc_mode=3), dict(rc_mode=-1)):
         with pytest.raises(B.BambooError) as e:
             B.stage_query_sizes(B.make_cfg(sc, **bad))
         assert e.value.status == B.E_BADCFG, bad

@@ -184,3 +184,57 @@ def test_bubble_kernel_waits_about_as_long_as_asked(B):
     ms = e0.elapsed_time(e1)
     assert 1.9 <= ms <= 3.0, ms
     st.stage_destroy()
+
+
+@pytest.mark.parametrize("name,k_fail", [("tiny", 2), ("bf16_post_ln", 3), ("bf16_causal_d128", 0)])
+@pytest.mark.parametrize("rc", ["LFLB", "EFEB"])
+def test_rc_variants_recover_the_failure_free_gradients(B, name, k_fail, rc):
+    """The lazy-FRC and eager-BRC variants of the paper's microbenchmarks (Section 7.4): same
+    programs as the oracle's, and after a preemption the same gradients as the failure-free run of
+    Bamboo's own variant, bitwise."""
+    from paper_2204_12013_amd.harness import StageHarness, split_at_failure
+    sc = SMALL[name]
+    mode = {"LFLB": (B.RC_LFLB, S.LFLB), "EFEB": (B.RC_EFEB, S.EFEB)}[rc]
+    inp, st0, hz0 = _build(B, sc)                       # reference: EFLB, no failure
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+
+    def build():
+        st = B.Stage(B.make_cfg(sc, rc_mode=mode[0]), B.to_device(inp["own_w"].reshape(-1), sc.dtype),
+                     B.to_device(inp["shadow_w"].reshape(-1), sc.dtype))
+        scs = sc.replace(n_own=sc.n_shadow, n_shadow=0, stage_id=sc.stage_id + 1)
+        succ = B.Stage(B.make_cfg(scs, frc_enabled=False), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype), None)
+        x = [B.to_device(inp["x"][k], sc.dtype) for k in range(sc.M)]
+        gz = [B.to_device(inp["gz"][k], sc.dtype) for k in range(sc.M)]
+        torch.cuda.synchronize()
+        return st, StageHarness(st, x, gz, successor=succ)
+    # failure-free iteration of the variant
+    st1, hz1 = build()
+    prog = st1.stage_schedule()
+    assert prog == S.stage_program(sc.P, sc.stage_id, sc.M, rc=mode[1])
+    hz1.begin_iteration()
+    hz1.run(prog)
+    hz1.sync()
+    assert torch.equal(st1.own_g, st0.own_g)
+    if rc == "EFEB":                                    # eager BRC reproduces the successor's gradients
+        assert torch.equal(st1.shadow_g, hz0.succ.own_g)
+    else:
+        assert float(st1.shadow_g.abs().max()) == 0.0
+    # the variant with the successor lost at k_fail
+    st2, hz2 = build()
+    hz2.begin_iteration()
+    hz2.run(split_at_failure(prog, k_fail))
+    hz2.succ.stage_sync()
+    hz2.succ.own_g.zero_()
+    merged = st2.failover_merge(k_fail)
+    assert merged == S.failover_program(sc.P, sc.stage_id, sc.M, k_fail, rc=mode[1])
+    hz2.run(merged)
+    hz2.sync()
+    assert torch.equal(st2.own_g, st0.own_g)
+    assert torch.equal(st2.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz2.gx[k], hz0.gx[k])
+        assert torch.equal(hz2.z_frc[k], hz0.z_succ[k])
+    for s_ in (st0, hz0.succ, st1, hz1.succ, st2, hz2.succ):
+        s_.stage_destroy()
