@@ -175,6 +175,56 @@ def main():
                               "ms_per_step_frc_on": ms_c_on,
                               "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
 
+    # The redundant-computation variants of the paper's microbenchmarks (Section 7.4, Table 4) on this
+    # stage, in bubble mode: time of a failure-free iteration relative to running nothing redundant, and
+    # the pause after a preemption (failover_merge until the lost state is rebuilt: BRC replay, plus,
+    # with lazy FRC, the FRCs that were never run).
+    if not args.no_extra_modes and sc.n_shadow > 0 and sc.stage_id < sc.P - 1:
+        from paper_2204_12013_amd.harness import split_at_failure
+        k_fail = min(5, M - 1)
+        variants = {}
+        for label, mode in (("LFLB", B.RC_LFLB), ("EFLB", B.RC_EFLB), ("EFEB", B.RC_EFEB)):
+            sv = B.Stage(B.make_cfg(sc, rc_mode=mode), st.own_w, st.shadow_w)
+            hv = StageHarness(sv, x, gz=gy, gy_table=gy)
+            pv = sv.stage_schedule()
+
+            def iters(n):
+                hv.us_per_tick = us_per_tick
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n):
+                    hv.begin_iteration(zero_grads=True)
+                    hv.run(pv)
+                hv.sync()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3 / n
+            iters(1)
+            ms_v = iters(k_c)
+            # preemption at micro-batch k_fail: time the part of the failover schedule that rebuilds lost state
+            hv.us_per_tick = 0.0
+            hv.begin_iteration(zero_grads=True)
+            hv.run(split_at_failure(pv, k_fail))
+            merged = sv.failover_merge(k_fail)
+            first_group = next(i for i, ins in enumerate(merged) if ins[0] == B.SEND_ACT)
+            hv.sync()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            hv.run(merged[:first_group])
+            hv.sync()
+            torch.cuda.synchronize()
+            pause = (time.perf_counter() - t0) * 1e3
+            hv.run(merged[first_group:])
+            hv.sync()
+            variants[label] = {"ms_per_step": ms_v, "pause_ms": pause}
+            sv.stage_destroy()
+            del sv, hv
+            torch.cuda.empty_cache()
+        base = variants["LFLB"]["ms_per_step"]
+        for v in variants.values():
+            v["overhead_pct"] = 100.0 * (v["ms_per_step"] - base) / base
+        out["rc_variants"] = {"mode": "simulated bubbles, %d iterations each, preemption at micro-batch %d" % (k_c, k_fail),
+                              **variants}
+
     # the APPLY step (Adam over the own parameters) and the replica weight synchronisation, timed with
     # events on lane 0; algorithmic HBM bytes: 16 read + 14 written per parameter (fp32 gradient, master
     # weights and two moments in, the last three and the bf16 copy out); the synchronisation is a device
