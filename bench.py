@@ -225,6 +225,38 @@ def main():
         out["rc_variants"] = {"mode": "simulated bubbles, %d iterations each, preemption at micro-batch %d" % (k_c, k_fail),
                               **variants}
 
+    # Context for the roofline fraction: the stage's four forward GEMM shapes run stand-alone on operands
+    # that are not cache-resident (a ring of buffer sets larger than the Infinity Cache, as inside an
+    # iteration), this library's kernel beside the vendor GEMM that torch.matmul dispatches to.  The
+    # vendor library is a yardstick for what the chip sustains at these sizes, nothing in the path uses it.
+    if not args.no_extra_modes and sc.dtype == 1:
+        ref = {}
+        for name_, (N_, K_) in (("qkv", (3 * H, H)), ("attn_out", (H, H)), ("ffn1", (sc.ffn, H)), ("ffn2", (H, sc.ffn))):
+            set_bytes = 2 * (T * K_ + K_ * N_ + T * N_)
+            nb = max(2, min(64, int(1.2e9 // set_bytes)))
+            Xs = [torch.randn(T, K_, device=dev, dtype=torch.float32).to(act) for _ in range(nb)]
+            Ws = [(torch.randn(K_, N_, device=dev, dtype=torch.float32) * 0.02).to(act) for _ in range(nb)]
+            Ys = [torch.empty(T, N_, device=dev, dtype=act) for _ in range(nb)]
+            bias = torch.zeros(N_, device=dev, dtype=act)
+            res = {}
+            for who, fn in (("this_library", lambda i: B.bk_linear_fwd(Xs[i], Ws[i], bias, Ys[i], impl=2)),
+                            ("vendor_via_torch", lambda i: torch.matmul(Xs[i], Ws[i], out=Ys[i]))):
+                for i in range(nb):
+                    fn(i)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                n_it = 3 * nb
+                e0.record()
+                for j in range(n_it):
+                    fn(j % nb)
+                e1.record()
+                torch.cuda.synchronize()
+                res[who] = 2.0 * T * N_ * K_ / (e0.elapsed_time(e1) * 1e-3 / n_it) / 1e12
+            ref[name_] = {"M": T, "N": N_, "K": K_, "TFLOP/s": res}
+            del Xs, Ws, Ys
+        out["gemm_reference"] = ref
+        torch.cuda.empty_cache()
+
     # the APPLY step (Adam over the own parameters) and the replica weight synchronisation, timed with
     # events on lane 0; algorithmic HBM bytes: 16 read + 14 written per parameter (fp32 gradient, master
     # weights and two moments in, the last three and the bf16 copy out); the synchronisation is a device
