@@ -151,6 +151,14 @@ int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out);
  * status; BAMBOO_E_ARG if cap is too small. */
 int stage_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap);
 
+/* stage_program for a pipeline whose stages differ in speed (Section 5.2: the partition gives
+ * later stages more layers, so they are slower and earlier stages see larger bubbles):
+ * tick_F[P], tick_B[P] are the slot-timeline durations of a forward / backward on each stage
+ * (host arrays; NULL = cfg->tick_F / cfg->tick_B for every stage).  Only the BUBBLE instructions
+ * differ from stage_program's. */
+int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const int32_t* tick_B, bamboo_instr_t* out,
+                         int32_t cap);
+
 /* The failover schedule of the shadow stage when sending micro-batch k_fail's
  * activation to the successor fails (Section 5.2, merge rules 1-4): join the FRC
  * lane, replay BRC for the micro-batches whose successor-side gradients were

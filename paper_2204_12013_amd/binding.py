@@ -57,6 +57,7 @@ _cfgp, _insp, _szp = C.POINTER(Cfg), C.POINTER(Instr), C.POINTER(Sizes)
 _SIGS = {
     "stage_query_sizes": (C.c_int, [_cfgp, _szp]),
     "stage_program": (C.c_int, [_cfgp, _insp, _i32]),
+    "stage_program_uneven": (C.c_int, [_cfgp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _insp, _i32]),
     "stage_failover_program": (C.c_int, [_cfgp, _i32, _insp, _i32]),
     "stage_record_offset": (_i64, [_cfgp, _i32, _i32, _i32]),
     "stage_strerror": (C.c_char_p, [C.c_int]),
@@ -135,6 +136,17 @@ def stage_program(cfg):
     n = _check(lib.stage_program(C.byref(cfg), None, 0), "stage_program")
     arr = (Instr * n)()
     _check(lib.stage_program(C.byref(cfg), arr, n), "stage_program")
+    return _instr_list(arr, n)
+
+
+def stage_program_uneven(cfg, tick_F=None, tick_B=None):
+    """stage_program with a forward / backward duration per stage (sequences of P ints or None)."""
+    def arr_of(t):
+        return None if t is None else (C.c_int32 * cfg.P)(*[int(v) for v in t])
+    f, b = arr_of(tick_F), arr_of(tick_B)
+    n = _check(lib.stage_program_uneven(C.byref(cfg), f, b, None, 0), "stage_program_uneven")
+    arr = (Instr * n)()
+    _check(lib.stage_program_uneven(C.byref(cfg), f, b, arr, n), "stage_program_uneven")
     return _instr_list(arr, n)
 
 

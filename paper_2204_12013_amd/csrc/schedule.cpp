@@ -32,6 +32,11 @@ std::vector<Step> one_f_one_b(int P, int s, int M) {
 }
 
 std::vector<int> idle_before(int P, int s, int M, int tick_F, int tick_B, int* tail) {
+  const std::vector<int> f(P, tick_F), b(P, tick_B);
+  return idle_before(P, s, M, f.data(), b.data(), tail);
+}
+
+std::vector<int> idle_before(int P, int s, int M, const int* tick_F, const int* tick_B, int* tail) {
   // Play all P stages: a stage advances through its sequence whenever the same
   // micro-batch has finished on the neighbour it depends on (previous stage for
   // a forward, next stage for a backward).  fwd_end/bwd_end hold finishing times.
@@ -52,7 +57,7 @@ std::vector<int> idle_before(int P, int s, int M, int tick_F, int tick_B, int* t
         if (ready < 0) break;  // neighbour has not produced it yet
         const long t0 = std::max(clock[st], ready);
         if (st == s) gaps[cursor[st]] = (int)(t0 - clock[st]);
-        clock[st] = t0 + (c.backward ? tick_B : tick_F);
+        clock[st] = t0 + (c.backward ? tick_B[st] : tick_F[st]);
         (c.backward ? bwd_end : fwd_end)[st][c.mb] = clock[st];
         ++cursor[st];
         moved = true;
@@ -93,12 +98,15 @@ void epilogue(std::vector<bamboo_instr_t>& out) {
 }
 }  // namespace
 
-std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c) {
+std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c) { return build_program(c, nullptr, nullptr); }
+
+std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c, const int* tick_F, const int* tick_B) {
   const int P = c.P, s = c.stage_id, M = c.M;
   const std::vector<Step> seq = one_f_one_b(P, s, M);
   const int slots = own_slot_count(P, s, M);
   int tail = 0;
-  const std::vector<int> gaps = idle_before(P, s, M, c.tick_F, c.tick_B, &tail);
+  const std::vector<int> uf(P, c.tick_F), ub(P, c.tick_B);
+  const std::vector<int> gaps = idle_before(P, s, M, tick_F ? tick_F : uf.data(), tick_B ? tick_B : ub.data(), &tail);
   const bool frc = c.rc_mode != BAMBOO_RC_LFLB && c.n_shadow > 0;
   const bool eager_brc = c.rc_mode == BAMBOO_RC_EFEB && c.n_shadow > 0 && s < P - 1;
   std::vector<bamboo_instr_t> out;

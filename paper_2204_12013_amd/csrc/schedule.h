@@ -19,8 +19,12 @@ std::vector<Step> one_f_one_b(int P, int s, int M);
 // Idle ticks of stage s before each of its computations and after the last one,
 // from a zero-latency simulation of all P stages.
 std::vector<int> idle_before(int P, int s, int M, int tick_F, int tick_B, int* tail);
+// the same with a forward / backward duration per stage (P entries each): uneven partitions
+std::vector<int> idle_before(int P, int s, int M, const int* tick_F, const int* tick_B, int* tail);
 
 std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c);
+// per-stage durations; null arrays fall back to c.tick_F / c.tick_B for every stage
+std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c, const int* tick_F, const int* tick_B);
 std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_fail);
 
 }  // namespace bamboo

@@ -512,6 +512,19 @@ int stage_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap) {
   }
 }
 
+int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const int32_t* tick_B, bamboo_instr_t* out,
+                         int32_t cap) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  for (int st = 0; st < cfg->P; ++st)
+    if ((tick_F && tick_F[st] < 1) || (tick_B && tick_B[st] < 1)) return BAMBOO_E_BADCFG;
+  try {
+    return copy_out(build_program(*cfg, tick_F, tick_B), out, cap);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+}
+
 int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
   const int v = validate(cfg);
   if (v != BAMBOO_OK) return v;

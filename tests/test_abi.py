@@ -58,6 +58,27 @@ def test_program_equals_oracle_bit_exact():
     assert B.stage_program(_cfg(4, 1, 8, 1, n_shadow=0)) == S.stage_program(4, 1, 8, frc=False)
 
 
+def test_uneven_partition_program_equals_oracle_bit_exact():
+    """Per-stage forward / backward durations (later stages slower, Section 5.2): same bubbles as the oracle."""
+    import random
+    rnd = random.Random(7)
+    for P, M in itertools.product(range(1, 7), [1, 3, 4, 8]):
+        for s in range(P):
+            tf = [rnd.randint(1, 4) for _ in range(P)]
+            tb = [rnd.randint(1, 7) for _ in range(P)]
+            for rc in (S.LFLB, S.EFLB, S.EFEB):
+                got = B.stage_program_uneven(_cfg(P, s, M, rc), tf, tb)
+                assert got == S.stage_program(P, s, M, rc=rc, tick_F=tf, tick_B=tb), (P, s, M, tf, tb)
+            assert B.stage_program_uneven(_cfg(P, s, M), None, None) == S.stage_program(P, s, M)
+    with pytest.raises(B.BambooError):
+        B.stage_program_uneven(_cfg(3, 0, 2), [1, 0, 1], None)
+    # the paper's observation: with slower later stages the earlier stages wait longer
+    tf = [2, 2, 2, 2, 3, 3, 3, 3]
+    bubbles = [sum(i[3] for i in B.stage_program_uneven(_cfg(8, s, 16), tf, [2 * t for t in tf]) if i[0] == S.BUBBLE)
+               for s in range(8)]
+    assert bubbles[0] > bubbles[4] > 0 and bubbles[3] > bubbles[7]
+
+
 def test_failover_program_equals_oracle_bit_exact():
     for P, M in itertools.product(range(2, 7), [1, 2, 3, 5, 8, 16]):
         for s in range(P - 1):
