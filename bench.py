@@ -219,6 +219,40 @@ def main():
             sv.stage_destroy()
             del sv, hv
             torch.cuda.empty_cache()
+        # How much of the eager FRC the bubbles hide depends on where the stage sits when the partition is
+        # uneven (Section 5.2: later stages hold more layers and are slower, so early stages wait longer).
+        # Same stage computation, timeline with the second half of the pipeline 25 % slower; one tick is
+        # sized so that this stage's own forward + backward take their simulated number of ticks.
+        by_stage = {}
+        tfs = [4 if i < (sc.P + 1) // 2 else 5 for i in range(sc.P)]
+        tbs = [2 * t for t in tfs]
+        for sid in range(sc.P - 1):
+            scs_ = sc.replace(stage_id=sid)
+            sv = B.Stage(B.make_cfg(scs_), st.own_w, st.shadow_w)
+            hv = StageHarness(sv, x, gz=gy, gy_table=gy)
+            p_on = B.stage_program_uneven(sv.cfg, tfs, tbs)
+            p_off = [i for i in p_on if i[0] != B.FRC]
+            res = []
+            for prog_ in (p_off, p_on):
+                hv.us_per_tick = ms_off * 1e3 / (M * (tfs[sid] + tbs[sid]))
+                for n_ in (1, 3):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(n_):
+                        hv.begin_iteration(zero_grads=True)
+                        hv.run(prog_)
+                    hv.sync()
+                    torch.cuda.synchronize()
+                    t_ = (time.perf_counter() - t0) * 1e3 / n_
+                res.append(t_)
+            ticks = sum(i[3] for i in p_on if i[0] == B.BUBBLE)
+            by_stage["stage_%d" % sid] = {"bubble_ticks": ticks, "ticks_per_fwd_bwd": tfs[sid] + tbs[sid],
+                                          "ms_frc_off": res[0], "ms_frc_on": res[1],
+                                          "frc_overhead_pct": 100.0 * (res[1] - res[0]) / res[0]}
+            sv.stage_destroy()
+            del sv, hv
+            torch.cuda.empty_cache()
+        out["frc_overhead_by_stage"] = {"timeline_ticks_fwd": tfs, "timeline_ticks_bwd": tbs, **by_stage}
         base = variants["LFLB"]["ms_per_step"]
         for v in variants.values():
             v["overhead_pct"] = 100.0 * (v["ms_per_step"] - base) / base
