@@ -31,6 +31,53 @@ typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
+// ---- GELU table -------------------------------------------------------------------------------
+// The forward epilogue of the first FFN GEMM needs GELU(h) and GELU'(h) for 16.8 M values per call at
+// the BERT-large stage; evaluated with exp and rcp that is ~28 vector instructions per value and as
+// long as the GEMM's main loop.  Both results are stored as bf16, so it is enough to know
+// Phi(h) = GELU(h) / h and GELU'(h) at the bf16 value nearest to h: a table over the bf16 values with
+// 2^-11 <= |h| < 16 (15 exponents x 128 mantissas x 2 signs, fp32 pairs, 30 KB, kept in LDS) replaces
+// the arithmetic by one LDS read.  Below 2^-11 Phi and GELU' are 0.5 to within 4e-4, above 16 they
+// are 0 or 1 to fp32 precision, so clamping the index is exact enough at both ends.
+constexpr int kGeluExpLo = 116, kGeluExpHi = 131;          // biased bf16 exponents covered
+constexpr int kGeluN = (kGeluExpHi - kGeluExpLo) * 128;    // entries per sign
+constexpr int kGeluBytes = 2 * kGeluN * 8;
+__device__ float2 g_gelu_table[2 * kGeluN];
+
+__global__ void gelu_table_init_kernel() {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 2 * kGeluN) return;
+  const unsigned bits = ((unsigned)(i / kGeluN) << 15) | (unsigned)((kGeluExpLo << 7) + i % kGeluN);
+  const float h = __uint_as_float(bits << 16);
+  const float phi = 0.5f * (1.0f + erff(h * 0.70710678118654752f));
+  g_gelu_table[i] = make_float2(phi, phi + h * expf(-0.5f * h * h) * 0.39894228040143268f);
+}
+
+// Fills the table once per process (the one launcher call that waits for the device: the first GEMM
+// with a GELU epilogue).
+static hipError_t ensure_gelu_table(hipStream_t s) {
+  static bool ready = false;
+  if (ready) return hipSuccess;
+  hipLaunchKernelGGL(gelu_table_init_kernel, dim3((2 * kGeluN + 255) / 256), dim3(256), 0, s);
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  if (e == hipSuccess) ready = true;
+  return e;
+}
+
+// (GELU(h), GELU'(h)) from the table in LDS at byte address `tab`
+__device__ __forceinline__ void gelu_pair_lookup(float h, unsigned tab, float* g, float* dg) {
+  const bf16_t hb = (bf16_t)h;
+  const unsigned b = __builtin_bit_cast(unsigned short, hb);
+  int rel = (int)(b & 0x7fffu) - (kGeluExpLo << 7);
+  rel = min(max(rel, 0), kGeluN - 1);
+  const unsigned addr = tab + ((b & 0x8000u) ? kGeluN * 8 : 0) + rel * 8;
+  typedef __attribute__((ext_vector_type(2))) float f32x2;
+  const f32x2 t = *(__attribute__((address_space(3))) const f32x2*)(uintptr_t)addr;
+  *g = h * t[0];
+  *dg = t[1];
+}
+
 constexpr int BK = 64;          // k-slice
 constexpr int KROW = BK + 8;    // LDS row length (elements) of a k-contiguous operand: 144 B, conflict-free b128 reads
 
@@ -39,7 +86,7 @@ struct MnMajor {                 // LDS row length (elements) of an operand stor
   static constexpr int LD = ROWS + 32;   // +64 B: the 4 k-rows x 64 B of a transposing read fall in distinct banks
 };
 
-template <int WM, int WN, bool A_K, bool B_K>
+template <int WM, int WN, bool A_K, bool B_K, bool GELU = false>
 struct Smem {
   static constexpr int BM = 64 * WM, BN = 64 * WN;
   static constexpr int A_ELEMS = A_K ? BM * KROW : BK * MnMajor<BM>::LD;
@@ -48,7 +95,8 @@ struct Smem {
   static constexpr int EPI_LD = 32 * WN + 4;                             // floats per staged output row
   static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;                  // 4 waves x 32 rows
   static constexpr int MAIN_BYTES = 2 * STAGE * 2;
-  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  static constexpr int TABLE_OFF = (MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES);   // GELU table behind the rest
+  static constexpr int BYTES = TABLE_OFF + (GELU ? kGeluBytes : 0);
 };
 
 // ---- global -> register -> LDS copies of one operand slice --------------------
@@ -181,7 +229,7 @@ struct EpiOperands {
 // epilogue on 8 consecutive outputs of one row; `pb` / `pf` are the operands fetched ahead
 template <int EPI>
 __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb,
-                                          const f32x4 (&pf)[2]) {
+                                          const f32x4 (&pf)[2], unsigned gelu_tab) {
   const long i = (long)m * d.N + n;
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
@@ -211,9 +259,9 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
   } else if (EPI == EPI_BIAS_GELU) {
     bf16x8 g;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {   // activation and its derivative from the fp32 pre-activation
+    for (int j = 0; j < 8; ++j) {   // activation and its derivative, looked up at the nearest bf16 value
       float gv, dgv;
-      gelu_pair_fast(v[j], &gv, &dgv);
+      gelu_pair_lookup(v[j], gelu_tab, &gv, &dgv);
       g[j] = (bf16_t)gv;
       o[j] = (bf16_t)dgv;
     }
@@ -229,7 +277,7 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
 // of row block 0 (requested by the caller).
 template <int WM, int WN, int EPI, int EPI_LD>
 __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][WN], float* stage_all, int m0, int n0,
-                                           const EpiOperands<WM, WN, EPI>& first) {
+                                           const EpiOperands<WM, WN, EPI>& first, unsigned gelu_tab) {
   typedef EpiOperands<WM, WN, EPI> Ops;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -259,7 +307,7 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
       const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
       if (m < d.M && n < d.N) {
         const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0]);
+        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], gelu_tab);
       }
     }
     __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
@@ -286,7 +334,7 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int* tm,
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
-  typedef Smem<WM, WN, A_K, B_K> SM;
+  typedef Smem<WM, WN, A_K, B_K, EPI == EPI_BIAS_GELU> SM;
   constexpr int BM = SM::BM, BN = SM::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = (bf16_t*)smem_raw;
@@ -355,9 +403,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
     __syncthreads();
   }
 
+  const unsigned gelu_tab = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void*)smem_raw + SM::TABLE_OFF;
+  if (EPI == EPI_BIAS_GELU) {     // the table region lies behind everything else: no barrier needed before writing it
+    for (int c = threadIdx.x; c < kGeluBytes / 16; c += 256)
+      ((f32x4*)(smem_raw + SM::TABLE_OFF))[c] = ((const f32x4*)g_gelu_table)[c];
+    __syncthreads();
+  }
   EpiOperands<WM, WN, EPI> ops;
   ops.issue(d, m0, n0, 0);
-  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops, gelu_tab);
 }
 
 // ---- software-pipelined kernel with direct global -> LDS loads (K a multiple of 64) ------
@@ -457,14 +511,15 @@ struct PlMN {
   }
 };
 
-template <int WM, int WN, int NS>
+template <int WM, int WN, int NS, bool GELU = false>
 struct SmemPl {
   static constexpr int BM = 64 * WM, BN = 64 * WN;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + B_BYTES;
   static constexpr int EPI_LD = 32 * WN + 4;
   static constexpr int EPI_BYTES = 4 * 32 * EPI_LD * 4;
   static constexpr int MAIN_BYTES = NS * STAGE_BYTES;
-  static constexpr int BYTES = MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES;
+  static constexpr int TABLE_OFF = (MAIN_BYTES > EPI_BYTES ? MAIN_BYTES : EPI_BYTES);   // GELU table behind the rest
+  static constexpr int BYTES = TABLE_OFF + (GELU ? kGeluBytes : 0);
 };
 
 #define BAMBOO_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -550,7 +605,7 @@ __device__ __forceinline__ void wait_loads_and_lds() {
 // in flight while slice kt feeds the MFMAs, i.e. a load has NS - 1 slices of MFMA time to land.
 template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS, int MINB>
 __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
-  typedef SmemPl<WM, WN, NS> SM;
+  typedef SmemPl<WM, WN, NS, EPI == EPI_BIAS_GELU> SM;
   typedef PlLoop<WM, WN, A_K, B_K> Loop;
   constexpr int BM = SM::BM, BN = SM::BN, NL = Loop::NL;
   constexpr unsigned STAGE = SM::STAGE_BYTES, RING = NS * STAGE;
@@ -586,6 +641,17 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   const int nk = d.K / BK;                 // nk >= NS (checked by the launcher)
+  if (EPI == EPI_BIAS_GELU) {
+    // GELU table -> its own LDS region, by the same direct loads as the slices and ahead of them: the
+    // wait for slice 0 below covers these older loads too.  A wavefront copies 1 KB per load.
+#pragma unroll
+    for (int it = 0; it < (kGeluBytes / 16 + 255) / 256; ++it) {
+      const int c0 = it * 256 + wave * 64;            // first chunk of this wavefront, uniform
+      if (c0 < kGeluBytes / 16)
+        gload_lds16((unsigned)(((threadIdx.x & 63)) << 4), (const char*)g_gelu_table + (long)c0 * 16,
+                    L.lds0 + SM::TABLE_OFF + c0 * 16);
+    }
+  }
   // four fragment register sets: k-step s of a slice computes from set s while set (s + 2) % 4 is
   // filled for the k-step after the next one, so an LDS read has more than a whole k-step to return
   bf16x8 fa[4][WM], fb[4][WN];
@@ -647,12 +713,12 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
   __syncthreads();
   BAMBOO_SCHED_FENCE();
   if (!EARLY) ops.issue(d, m0, n0, 0);
-  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops);
+  write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops, L.lds0 + SM::TABLE_OFF);
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
 static hipError_t launch_pl(hipStream_t s, const GemmDesc& d, int tiles) {
-  typedef SmemPl<WM, WN, NS> SM;
+  typedef SmemPl<WM, WN, NS, EPI == EPI_BIAS_GELU> SM;
   static bool attr_set = false;
   auto kern = gemm_mfma_pl_kernel<WM, WN, A_K, B_K, EPI, NS, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
   if (!attr_set) {
@@ -679,15 +745,16 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d, int ns) {
     const int nk = d.K / BK;
     if (g_forced_stages) ns = g_forced_stages;
     if (ns > nk) ns = nk >= 3 ? 3 : 2;
-    if constexpr (SmemPl<WM, WN, 4>::BYTES <= 160 * 1024) {
+    constexpr bool G = EPI == EPI_BIAS_GELU;
+    if constexpr (SmemPl<WM, WN, 4, G>::BYTES <= 160 * 1024) {
       if (ns == 4) return launch_pl<WM, WN, A_K, B_K, EPI, 4>(s, d, tiles);
     }
-    if constexpr (SmemPl<WM, WN, 3>::BYTES <= 160 * 1024) {
+    if constexpr (SmemPl<WM, WN, 3, G>::BYTES <= 160 * 1024) {
       if (ns >= 3) return launch_pl<WM, WN, A_K, B_K, EPI, 3>(s, d, tiles);
     }
     return launch_pl<WM, WN, A_K, B_K, EPI, 2>(s, d, tiles);
   }
-  typedef Smem<WM, WN, A_K, B_K> SM;
+  typedef Smem<WM, WN, A_K, B_K, EPI == EPI_BIAS_GELU> SM;
   static bool attr_set = false;
   auto kern = gemm_mfma_kernel<WM, WN, A_K, B_K, EPI>;
   if (!attr_set) {
@@ -726,10 +793,11 @@ static const TileCost kCostAcc[] = {       // fp32 read-modify-write output (wei
     {22, 3, 0.f, 0.616f, 2.88f}, {24, 2, 0.f, 1.216f, 6.12f}, {24, 3, 0.f, 1.072f, 1.03f},
     {42, 2, 0.f, 1.102f, 11.56f}, {42, 3, 0.f, 0.997f, 4.55f}, {44, 2, 0.f, 1.737f, 0.f}};
 
-static void choose_tile(const GemmDesc& d, bool acc_form, int* code, int* ns) {
+static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* code, int* ns) {
   const int nk = d.K / BK;
   const TileCost* tab = acc_form ? kCostAcc : kCostStore;
   float best = 0.f;
+  bool found = false;
   *code = 22;
   *ns = 2;
   for (int i = 0; i < 9; ++i) {
@@ -738,11 +806,13 @@ static void choose_tile(const GemmDesc& d, bool acc_form, int* code, int* ns) {
     const int wm = t.code / 10, wn = t.code % 10;
     const long tiles = (long)((d.M + 64 * wm - 1) / (64 * wm)) * ((d.N + 64 * wn - 1) / (64 * wn));
     const long stage = (long)(wm + wn) * 64 * BK * 2, epi = 4L * 32 * (32 * wn + 4) * 4;
-    const long lds = t.ns * stage > epi ? t.ns * stage : epi;
+    const long lds = (t.ns * stage > epi ? t.ns * stage : epi) + extra_lds;
+    if (lds > 160 * 1024) continue;
     const long slots = 256 * (2 * lds <= 160 * 1024 ? 2 : 1);
     const long rounds = (tiles + slots - 1) / slots;
     const float cost = rounds * (t.a + t.b * nk) + t.c;
-    if (i == 0 || cost < best) {
+    if (!found || cost < best) {
+      found = true;
       best = cost;
       *code = t.code;
       *ns = t.ns;
@@ -753,7 +823,11 @@ static void choose_tile(const GemmDesc& d, bool acc_form, int* code, int* ns) {
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
   int pick, ns;
-  choose_tile(d, EPI == EPI_ACC_F32, &pick, &ns);
+  choose_tile(d, EPI == EPI_ACC_F32, EPI == EPI_BIAS_GELU ? kGeluBytes : 0, &pick, &ns);
+  if (EPI == EPI_BIAS_GELU) {
+    const hipError_t e = ensure_gelu_table(s);
+    if (e != hipSuccess) return e;
+  }
   if (g_forced_tile) {
     pick = g_forced_tile;
     ns = 2;
