@@ -259,6 +259,32 @@ def main():
         out["rc_variants"] = {"mode": "simulated bubbles, %d iterations each, preemption at micro-batch %d" % (k_c, k_fail),
                               **variants}
 
+    # Pure data parallelism (Section 5.2 "over-batching", Section 7.6): there is no bubble, so eager FRC means
+    # that a node also processes its neighbour's minibatch, i.e. twice the batch; the paper reports about 1.5x
+    # the time on its GPUs.  Measured here as the own layers' forward + backward at twice the micro-batch.
+    if not args.no_extra_modes:
+        sc2 = sc.replace(micro_batch=2 * sc.micro_batch, n_shadow=0, stage_id=sc.P - 1)
+        s2 = B.Stage(B.make_cfg(sc2, frc_enabled=False), st.own_w, None)
+        x2 = [torch.cat([x[k], x[(k + 1) % M]]) for k in range(M)]
+        g2 = [torch.cat([gy[k], gy[(k + 1) % M]]) for k in range(M)]
+        h2 = StageHarness(s2, x2, gz=g2, gy_table=g2)
+        p2 = [i for i in s2.stage_schedule() if i[0] != B.BUBBLE]
+        t2 = None
+        for n_ in (1, k_c):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n_):
+                h2.begin_iteration(zero_grads=True)
+                h2.run(p2)
+            h2.sync()
+            torch.cuda.synchronize()
+            t2 = (time.perf_counter() - t0) * 1e3 / n_
+        out["over_batching"] = {"ms_per_step_batch": ms_off, "ms_per_step_twice_the_batch": t2,
+                                "time_ratio": t2 / ms_off}
+        s2.stage_destroy()
+        del s2, h2, x2, g2
+        torch.cuda.empty_cache()
+
     # Context for the roofline fraction: the stage's four forward GEMM shapes run stand-alone on operands
     # that are not cache-resident (a ring of buffer sets larger than the Infinity Cache, as inside an
     # iteration), this library's kernel beside the vendor GEMM that torch.matmul dispatches to.  The

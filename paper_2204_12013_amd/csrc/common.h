@@ -25,25 +25,6 @@ __device__ __forceinline__ float gelu_grad_f(float h) {
   return 0.5f * (1.0f + erff(h * 0.70710678118654752f)) + h * __expf(-0.5f * h * h) * 0.39894228040143268f;
 }
 
-// GELU and its derivative together from one exponential: with x = |h|/sqrt(2),
-// exp(-x^2) = exp(-h^2/2) serves both the normal density in GELU' and the
-// Abramowitz-Stegun 7.1.26 rational approximation of erf (|error| <= 1.5e-7,
-// far below bf16 resolution).  Phi(h) = 1 - q for h >= 0 and q for h < 0,
-// q = poly(t) * exp(-h^2/2) / 2, t = 1 / (1 + p x).
-__device__ __forceinline__ void gelu_pair_fast(float h, float* g, float* dg) {
-  const float ax = fabsf(h) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
-  const float e = __builtin_amdgcn_exp2f(-0.72134752044448170f * h * h);   // exp(-h^2/2)
-  float poly = fmaf(t, 1.061405429f, -1.453152027f);
-  poly = fmaf(t, poly, 1.421413741f);
-  poly = fmaf(t, poly, -0.284496736f);
-  poly = fmaf(t, poly, 0.254829592f);
-  const float q = 0.5f * poly * t * e;
-  const float phi = h >= 0.f ? 1.0f - q : q;
-  *g = h * phi;
-  *dg = fmaf(h * e, 0.39894228040143268f, phi);
-}
-
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
