@@ -140,5 +140,6 @@ hipError_t launch_adam(hipStream_t s, int dtype, long n, const float* g, float* 
 hipError_t launch_widen(hipStream_t s, int dtype, long n, const void* w, float* master);
 hipError_t launch_fill_zero(hipStream_t s, long n, float* p);
 hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
+hipError_t launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes);
 
 }  // namespace bamboo

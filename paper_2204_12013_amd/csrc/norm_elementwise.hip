@@ -584,18 +584,35 @@ hipError_t launch_layernorm_bwd(hipStream_t s, int dtype, int T, int H, const vo
 }
 
 // --------------------------------------------------------------------- copy
-// Plain 16-byte-per-lane copy of a known size: the yardstick that the HBM
-// traffic counters of the other kernels are scaled by.
-__global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, long n16) {
+// Plain 16-byte-per-lane copy. The replica sync uses copy_kernel; the copy of a
+// known size that the HBM traffic counters of the other kernels are scaled by
+// has a kernel name of its own, so that a counter summary can tell it apart.
+__device__ __forceinline__ void copy_body(const float4* __restrict__ src, float4* __restrict__ dst, long n16) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n16; i += (long)gridDim.x * 256) dst[i] = src[i];
 }
-hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+__global__ __launch_bounds__(256) void copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst, long n16) {
+  copy_body(src, dst, n16);
+}
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const float4* __restrict__ src, float4* __restrict__ dst,
+                                                               long n16) {
+  copy_body(src, dst, n16);
+}
+static hipError_t launch_copy_impl(hipStream_t s, const void* src, void* dst, size_t bytes, bool calibration) {
   const long n16 = (long)(bytes / 16);
   if (n16 == 0) return hipSuccess;
   long blocks = (n16 + 255) / 256;
   if (blocks > 256 * 16) blocks = 256 * 16;
-  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float4*)src, (float4*)dst, n16);
+  if (calibration)
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float4*)src, (float4*)dst, n16);
+  else
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const float4*)src, (float4*)dst, n16);
   return hipGetLastError();
+}
+hipError_t launch_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  return launch_copy_impl(s, src, dst, bytes, false);
+}
+hipError_t launch_calibration_copy(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  return launch_copy_impl(s, src, dst, bytes, true);
 }
 
 // ------------------------------------------------------------------- bubble

@@ -136,7 +136,7 @@ uint64_t bk_layernorm_bwd_scratch_floats(int H) { return ln_bwd_partial_floats(H
 int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
   if (!src || !dst || bytes % 16 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return BAMBOO_E_ARG;
   (void)hipGetLastError();
-  return finish(launch_copy((hipStream_t)stream, src, dst, (size_t)bytes));
+  return finish(launch_calibration_copy((hipStream_t)stream, src, dst, (size_t)bytes));
 }
 
 int bk_adam(int dtype, int64_t n, const float* g, float* master, float* m, float* v, void* w, float lr, float beta1,

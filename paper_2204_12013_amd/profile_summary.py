@@ -6,7 +6,7 @@
 `stats` prints calls / average / total per kernel.  `pmc` prints, per kernel, the
 mean counter value per dispatch, and scales FETCH_SIZE / WRITE_SIZE (KiB) by what
 the same counter reads for the library's plain copy kernel of known size
-(bamboo::copy_kernel, launched by `bench.py --calibration-copy`).
+(bamboo::calibration_copy_kernel, launched by `bench.py --calibration-copy`).
 """
 import csv
 import collections
@@ -40,7 +40,7 @@ def pmc(paths, copy_bytes=256 << 20):
         for r in csv.DictReader(open(path)):
             acc[r["Counter_Name"]][_short(r["Kernel_Name"])].append(float(r["Counter_Value"]))
     for counter, per_kernel in acc.items():
-        cal = [v for k, vals in per_kernel.items() if k.startswith("copy_kernel") for v in vals]
+        cal = [v for k, vals in per_kernel.items() if k.startswith("calibration_copy_kernel") for v in vals]
         factor = None
         if cal and counter in ("FETCH_SIZE", "WRITE_SIZE"):
             factor = (copy_bytes / 1024.0) / (sum(cal) / len(cal))
