@@ -288,6 +288,68 @@ def main():
         del s2, h2, x2, g2
         torch.cuda.empty_cache()
 
+    # Swap-out of the FRC results to host memory (Section 5.2; Section 7.4 puts the GPU-memory cost of eager
+    # FRC at about 1.5x): the device keeps a ring of two shadow slots, every FRC's records go to pinned host
+    # memory on a third stream and come back for BRC after a preemption.  Reported: iteration time with the
+    # copies (no bubbles / simulated bubbles), the host-link rate they reach, the pause after a preemption,
+    # and the device memory of the stage without redundancy, with the device-resident stash and with swap-out.
+    if not args.no_extra_modes and sc.n_shadow > 0 and sc.stage_id < sc.P - 1:
+        from paper_2204_12013_amd.harness import split_at_failure
+        cfg_sw = B.make_cfg(sc, swap_slots=min(2, M))
+        sz_sw = B.stage_query_sizes(cfg_sw)
+        sz = st.sizes
+        opt_own, opt_sh = int(sz.own_opt), int(sz.shadow_opt)
+        mem_plain = int(sz.own_w + sz.own_g + sz.own_stash + sz.workspace) + opt_own
+        mem_rc = mem_plain + int(sz.shadow_w + sz.shadow_g) + opt_sh
+        mem = {"no_redundancy": mem_plain, "eager_frc_device_stash": mem_rc + int(sz.shadow_stash),
+               "eager_frc_swap_out": mem_rc + int(sz_sw.shadow_stash), "host_pinned_swap_out": int(sz_sw.host_stash)}
+        sw = {"device_bytes": mem,
+              "device_memory_ratio": {"device_stash": mem["eager_frc_device_stash"] / mem_plain,
+                                      "swap_out": mem["eager_frc_swap_out"] / mem_plain}}
+        if int(sz_sw.host_stash) <= (32 << 30):
+            sv = B.Stage(cfg_sw, st.own_w, st.shadow_w)
+            hv = StageHarness(sv, x, gz=gy, gy_table=gy)
+            pv = sv.stage_schedule()
+
+            def iters_sw(n, upt):
+                hv.us_per_tick = upt
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n):
+                    hv.begin_iteration(zero_grads=True)
+                    hv.run(pv)
+                hv.sync()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3 / n
+            iters_sw(1, 0.0)
+            ms_sw = iters_sw(k_c, 0.0)
+            ms_sw_c = iters_sw(k_c, us_per_tick)
+            k_fail = min(5, M - 1)
+            hv.us_per_tick = 0.0
+            hv.begin_iteration(zero_grads=True)
+            hv.run(split_at_failure(pv, k_fail))
+            merged = sv.failover_merge(k_fail)
+            first_group = next(i for i, ins in enumerate(merged) if ins[0] == B.SEND_ACT)
+            hv.sync()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            hv.run(merged[:first_group])
+            hv.sync()
+            torch.cuda.synchronize()
+            pause = (time.perf_counter() - t0) * 1e3
+            hv.run(merged[first_group:])
+            hv.sync()
+            sw.update({"ring_slots": int(cfg_sw.swap_slots), "ms_per_step_no_bubbles": ms_sw,
+                       "ms_per_step_bubbles": ms_sw_c, "ms_per_step_device_stash_no_bubbles": ms_on,
+                       "ms_per_step_device_stash_bubbles": ms_c_on,
+                       "host_bytes_per_step": int(sz_sw.host_stash),
+                       "device_to_host_GB/s_no_bubbles": int(sz_sw.host_stash) / (ms_sw * 1e-3) / 1e9,
+                       "pause_ms_preemption_at_%d" % k_fail: pause})
+            sv.stage_destroy()
+            del sv, hv
+            torch.cuda.empty_cache()
+        out["swap_out"] = sw
+
     # Context for the roofline fraction: the stage's four forward GEMM shapes run stand-alone on operands
     # that are not cache-resident (a ring of buffer sets larger than the Infinity Cache, as inside an
     # iteration), this library's kernel beside the vendor GEMM that torch.matmul dispatches to.  The

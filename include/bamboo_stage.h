@@ -87,6 +87,10 @@ typedef struct {
   int32_t tick_F;      /* slot-timeline duration of a forward (>= 1) */
   int32_t tick_B;      /* slot-timeline duration of a backward (>= 1) */
   float ln_eps;        /* LayerNorm epsilon */
+  int32_t swap_slots;  /* 0: FRC results stay in device memory (M shadow stash slots).  R in 1..M: the
+                          paper's swap-out (Section 5.2): the device keeps a ring of R shadow slots, the
+                          results of every FRC are copied to pinned host memory on a third stream and copied
+                          back only for BRC.  Needs stage_swap_attach before the first FRC. */
 } bamboo_cfg_t;
 
 /* Instruction set: the paper's computation and communication instructions
@@ -126,9 +130,12 @@ typedef struct {
   uint64_t rec_bytes;               /* one stash record: one layer, one micro-batch */
   uint64_t layer_params;            /* elements per layer: 4H^2 + 2HF + 9H + F */
   int32_t c_own;                    /* own stash slots = min(P - stage_id, M) */
-  int32_t c_shadow;                 /* shadow stash slots = M (everything BRC may need) */
+  int32_t c_shadow;                 /* shadow stash slots in device memory = M (everything BRC may need),
+                                       or cfg.swap_slots when the FRC results are swapped out to the host */
   uint64_t own_opt, shadow_opt;     /* optimizer state (only for stage_optimizer_init): fp32 master weights,
                                        first and second moments, 3 x 4 bytes per parameter */
+  uint64_t host_stash;              /* pinned host bytes for stage_swap_attach: M x n_shadow x rec_bytes
+                                       (0 when cfg.swap_slots is 0) */
 } bamboo_sizes_t;
 
 /* Adam hyper-parameters (Section 7 names the optimizer and a learning rate of 6e-3 for the
@@ -268,14 +275,31 @@ int stage_apply(bamboo_stage_t* st, const bamboo_adam_t* hp, int32_t step);
  * Stands for the transfer from node n+1 to node n; on one GPU it is a device-local copy. */
 int stage_sync_replica(bamboo_stage_t* st, const void* successor_w, const void* successor_opt);
 
+/* ---- swap-out of the FRC results to host memory (Section 5.2, "Eager FRC") ------------------
+ * The paper moves the outputs and intermediate results of each micro-batch's FRC to CPU memory
+ * right after the FRC and keeps only the replica's parameters on the GPU; they come back only
+ * when a preemption makes BRC necessary.  With cfg.swap_slots = R > 0 the shadow stash passed to
+ * stage_init holds R micro-batch slots (FRC(k) writes slot k mod R) and
+ *   - after FRC(k), the swap stream waits for it and copies the slot to host_stash[k]; a later FRC
+ *     into the same slot waits for that copy;
+ *   - BRC(k) reads the slot directly if it still holds k, else the swap stream copies host_stash[k]
+ *     back first; while BRC(k) runs, the copy for the next BRC of the stage's program is started
+ *     when it lands in another slot.
+ * host_stash: page-locked host memory of sizes.host_stash bytes (micro-batch k at offset
+ * k * n_shadow * rec_bytes, records in layer order), allocated pinned by the caller (not
+ * registered after the fact) and kept until stage_destroy.  stream_swap: a third stream of the
+ * same priority as the other two.  BAMBOO_E_STATE if cfg.swap_slots == 0 or already attached;
+ * BAMBOO_E_ARG if bytes is too small.  Results are bitwise those of the device-resident stash. */
+int stage_swap_attach(bamboo_stage_t* st, void* host_stash, uint64_t bytes, void* stream_swap);
+
 /* Simulated pipeline bubble: one single-wave workgroup on lane 0 that spins on
  * the device wall clock for ticks * us_per_tick microseconds. */
 int stage_bubble(bamboo_stage_t* st, int32_t ticks, float us_per_tick);
 
-/* JOIN on the device: lane 0 waits for everything issued on lane 1. */
+/* JOIN on the device: lane 0 waits for everything issued on lane 1 (and on the swap stream). */
 int stage_join(bamboo_stage_t* st);
 
-/* JOIN and block the host until both lanes are idle. */
+/* JOIN and block the host until all lanes are idle. */
 int stage_sync(bamboo_stage_t* st);
 
 /* Per-kernel-class timing for roofline measurements (not part of the method).

@@ -28,7 +28,7 @@ KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd"
 class Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("arch", "dtype", "hidden", "heads", "ffn", "seq", "micro_batch", "n_own", "n_shadow",
-                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float)]
+                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float), ("swap_slots", C.c_int32)]
 
 
 class Instr(C.Structure):
@@ -39,7 +39,7 @@ class Sizes(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("own_w", "shadow_w", "own_g", "shadow_g", "own_stash", "shadow_stash", "workspace",
                  "rec_bytes", "layer_params")] + [("c_own", C.c_int32), ("c_shadow", C.c_int32)] + \
-        [("own_opt", C.c_uint64), ("shadow_opt", C.c_uint64)]
+        [("own_opt", C.c_uint64), ("shadow_opt", C.c_uint64), ("host_stash", C.c_uint64)]
 
 
 class Adam(C.Structure):
@@ -74,6 +74,7 @@ _SIGS = {
     "stage_optimizer_init": (C.c_int, [_vp, _vp, _vp]),
     "stage_apply": (C.c_int, [_vp, C.POINTER(Adam), _i32]),
     "stage_sync_replica": (C.c_int, [_vp, _vp, _vp]),
+    "stage_swap_attach": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
     "stage_join": (C.c_int, [_vp]),
     "stage_sync": (C.c_int, [_vp]),
     "stage_destroy": (C.c_int, [_vp]),
@@ -117,7 +118,7 @@ def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, rc_mode=None
     vals = dict(arch=sc.arch, dtype=sc.dtype, hidden=sc.hidden, heads=sc.heads, ffn=sc.ffn, seq=sc.seq,
                 micro_batch=sc.micro_batch, n_own=sc.n_own, n_shadow=sc.n_shadow, P=sc.P,
                 stage_id=sc.stage_id, M=sc.M, rc_mode=int(rc_mode), tick_F=tick_F, tick_B=tick_B,
-                ln_eps=ln_eps)
+                ln_eps=ln_eps, swap_slots=0)
     vals.update(override)
     return Cfg(**vals)
 
@@ -178,7 +179,7 @@ class Stage:
     """Owns the device buffers (as torch tensors) and the two streams of one
     stage and forwards every call to the C ABI."""
 
-    def __init__(self, cfg, own_w, shadow_w, device="cuda:0"):
+    def __init__(self, cfg, own_w, shadow_w, device="cuda:0", attach_swap=True):
         import torch
         self.torch = torch
         self.cfg = cfg
@@ -212,6 +213,13 @@ class Stage:
                               _ptr(self.shadow_stash) if cfg.n_shadow > 0 else None, _ptr(self.workspace),
                               C.c_void_p(self.stream_main.cuda_stream), C.c_void_p(self.stream_frc.cuda_stream),
                               C.byref(self._h)), "stage_init")
+        self.host_stash = self.stream_swap = None
+        if cfg.swap_slots > 0 and attach_swap:
+            # FRC results swapped out to the host: pinned memory allocated as such, a third stream
+            self.host_stash = torch.empty(int(sz.host_stash), dtype=torch.uint8, pin_memory=True)
+            self.stream_swap = torch.cuda.Stream(device=self.device)
+            _check(lib.stage_swap_attach(self._h, C.c_void_p(self.host_stash.data_ptr()), int(sz.host_stash),
+                                         C.c_void_p(self.stream_swap.cuda_stream)), "stage_swap_attach")
 
     def stash_tensor(self, kind, slot, layer, field):
         """View of one tensor of a stash record (kind 0 own, 1 shadow)."""

@@ -131,6 +131,7 @@ int validate(const bamboo_cfg_t* c) {
   if (c->tick_F < 1 || c->tick_B < 1 || !(c->ln_eps >= 0.f)) return BAMBOO_E_BADCFG;
   if (c->rc_mode != BAMBOO_RC_LFLB && c->rc_mode != BAMBOO_RC_EFLB && c->rc_mode != BAMBOO_RC_EFEB) return BAMBOO_E_BADCFG;
   if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
+  if (c->swap_slots < 0 || c->swap_slots > c->M || (c->swap_slots > 0 && c->n_shadow <= 0)) return BAMBOO_E_BADCFG;
   return BAMBOO_OK;
 }
 
@@ -162,6 +163,16 @@ struct bamboo_stage {
   hipEvent_t ev_join;
   int last_frc_on_lane1;
   float* opt[2];      // own, shadow optimizer state [master | m | v], or null
+  // swap-out of the FRC results (cfg.swap_slots = R > 0): the shadow stash is a ring of R slots
+  char* host_stash;                    // pinned host memory, micro-batch k at k * n_shadow * rec_bytes; null until attached
+  hipStream_t lane_swap;
+  std::vector<int> ring_mb;            // micro-batch whose record the enqueued work leaves in each ring slot, -1 none
+  std::vector<char> on_host;           // swap-out of micro-batch k has been enqueued
+  std::vector<hipEvent_t> ev_written;  // per ring slot: last FRC into it
+  std::vector<hipEvent_t> ev_out;      // per ring slot: last copy to the host out of it
+  std::vector<hipEvent_t> ev_in;       // per ring slot: last copy from the host into it
+  std::vector<hipEvent_t> ev_read;     // per ring slot: last BRC reading it
+  hipEvent_t ev_swap_join;
   // optional per-kernel-class timing: an event pair around every launch
   bool prof_on;
   struct ProfRec { int cls; double work; hipEvent_t a, b; };
@@ -455,6 +466,33 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
   return BAMBOO_OK;
 }
 
+bool swapping(const bamboo_stage* st) { return st->cfg.swap_slots > 0; }
+uint64_t shadow_slot_bytes(const bamboo_stage* st) { return (uint64_t)st->cfg.n_shadow * st->rl.bytes; }
+
+// Copy host_stash[k] back into ring slot k mod R on the swap stream.  The copy waits for the
+// last reader of the slot; a writer of the slot (FRC) and its copy out precede it in the swap
+// stream's own order.
+int swap_in(bamboo_stage* st, int k) {
+  const int d = k % st->cfg.swap_slots;
+  const uint64_t nb = shadow_slot_bytes(st);
+  HIPCHK(hipStreamWaitEvent(st->lane_swap, st->ev_read[d], 0));
+  HIPCHK(hipMemcpyAsync(st->stash[1] + (uint64_t)d * nb, st->host_stash + (uint64_t)k * nb, nb, hipMemcpyHostToDevice,
+                        st->lane_swap));
+  HIPCHK(hipEventRecord(st->ev_in[d], st->lane_swap));
+  st->ring_mb[d] = k;
+  return BAMBOO_OK;
+}
+
+// The micro-batch of the first BRC after BRC(k) in the stage's current program, or -1.
+int next_brc_after(const bamboo_stage* st, int k) {
+  const std::vector<bamboo_instr_t>& p = st->program;
+  size_t i = 0;
+  while (i < p.size() && !(p[i].op == BAMBOO_BRC && p[i].mb == k)) ++i;
+  for (++i; i < p.size(); ++i)
+    if (p[i].op == BAMBOO_BRC) return p[i].mb;
+  return -1;
+}
+
 int get_event(std::vector<hipEvent_t>& v, int k, hipEvent_t* out) {
   if (v[k] == nullptr) HIPCHK(hipEventCreateWithFlags(&v[k], hipEventDisableTiming));
   *out = v[k];
@@ -493,7 +531,8 @@ int stage_query_sizes(const bamboo_cfg_t* cfg, bamboo_sizes_t* out) {
   out->shadow_g = po.count * cfg->n_shadow * 4;
   out->rec_bytes = rl.bytes;
   out->c_own = own_slot_count(cfg->P, cfg->stage_id, cfg->M);
-  out->c_shadow = cfg->n_shadow > 0 ? cfg->M : 0;
+  out->c_shadow = cfg->n_shadow > 0 ? (cfg->swap_slots > 0 ? cfg->swap_slots : cfg->M) : 0;
+  out->host_stash = cfg->swap_slots > 0 ? (uint64_t)cfg->M * cfg->n_shadow * rl.bytes : 0;
   out->own_stash = (uint64_t)out->c_own * cfg->n_own * rl.bytes;
   out->shadow_stash = (uint64_t)out->c_shadow * cfg->n_shadow * rl.bytes;
   out->workspace = lane_scratch(*cfg, true).bytes + lane_scratch(*cfg, cfg->rc_mode == BAMBOO_RC_EFEB).bytes;
@@ -602,6 +641,10 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     st->last_frc_on_lane1 = -1;
     st->prof_on = false;
     st->opt[0] = st->opt[1] = nullptr;
+    st->host_stash = nullptr;
+    st->lane_swap = nullptr;
+    st->ev_swap_join = nullptr;
+    st->on_host.assign(cfg->M, 0);
   } catch (const std::bad_alloc&) {
     delete st;
     return BAMBOO_E_NOMEM;
@@ -626,6 +669,8 @@ int stage_begin_iteration(bamboo_stage_t* st) {
   std::fill(st->fwd_issued.begin(), st->fwd_issued.end(), 0);
   std::fill(st->frc_issued.begin(), st->frc_issued.end(), 0);
   std::fill(st->shadow_live.begin(), st->shadow_live.end(), 0);
+  std::fill(st->ring_mb.begin(), st->ring_mb.end(), -1);
+  std::fill(st->on_host.begin(), st->on_host.end(), 0);
   st->last_frc_on_lane1 = -1;
   return BAMBOO_OK;
 }
@@ -659,10 +704,30 @@ int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z) {
   }
   char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
   void* zout = z ? z : (void*)(ws + (lane_id == 0 ? st->ws0.out : st->ws1.out));
-  const int rc = run_forward(st, 1, lane_id, k, y, zout);
+  int slot = k;
+  if (swapping(st)) {
+    if (!st->host_stash) return BAMBOO_E_STATE;
+    // the ring slot may be overwritten once its last occupant is on the host, no copy into it is
+    // in flight and its last reader is done
+    slot = k % st->cfg.swap_slots;
+    HIPCHK(hipStreamWaitEvent(st->lane[lane_id], st->ev_out[slot], 0));
+    HIPCHK(hipStreamWaitEvent(st->lane[lane_id], st->ev_in[slot], 0));
+    HIPCHK(hipStreamWaitEvent(st->lane[lane_id], st->ev_read[slot], 0));
+  }
+  const int rc = run_forward(st, 1, lane_id, slot, y, zout);
   if (rc != BAMBOO_OK) return rc;
   st->frc_issued[k] = 1;
   st->shadow_live[k] = 1;
+  if (swapping(st)) {
+    const uint64_t nb = shadow_slot_bytes(st);
+    HIPCHK(hipEventRecord(st->ev_written[slot], st->lane[lane_id]));
+    HIPCHK(hipStreamWaitEvent(st->lane_swap, st->ev_written[slot], 0));
+    HIPCHK(hipMemcpyAsync(st->host_stash + (uint64_t)k * nb, st->stash[1] + (uint64_t)slot * nb, nb,
+                          hipMemcpyDeviceToHost, st->lane_swap));
+    HIPCHK(hipEventRecord(st->ev_out[slot], st->lane_swap));
+    st->ring_mb[slot] = k;
+    st->on_host[k] = 1;
+  }
   if (lane_id == 1) {
     if (get_event(st->ev_frc, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
     HIPCHK(hipEventRecord(ev, st->lane[1]));
@@ -691,9 +756,33 @@ int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy) {
   const int lane_id = st->merged ? 0 : 1;
   // on lane 1 BRC(k) follows FRC(k) in stream order; on lane 0 it waits for an FRC issued on lane 1
   if (lane_id == 0 && st->ev_frc[k] != nullptr) HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_frc[k], 0));
-  const int rc = run_backward(st, 1, lane_id, k, gz, gy);
+  int slot = k;
+  if (swapping(st)) {
+    if (!st->host_stash || !st->on_host[k]) return BAMBOO_E_STATE;
+    slot = k % st->cfg.swap_slots;
+    if (st->ring_mb[slot] != k) {
+      const int e = swap_in(st, k);
+      if (e != BAMBOO_OK) return e;
+    }
+    HIPCHK(hipStreamWaitEvent(st->lane[lane_id], st->ev_written[slot], 0));
+    HIPCHK(hipStreamWaitEvent(st->lane[lane_id], st->ev_in[slot], 0));
+  }
+  const int rc = run_backward(st, 1, lane_id, slot, gz, gy);
   if (rc != BAMBOO_OK) return rc;
   st->shadow_live[k] = 0;
+  if (swapping(st)) {
+    HIPCHK(hipEventRecord(st->ev_read[slot], st->lane[lane_id]));
+    st->ring_mb[slot] = -1;     // consumed: nothing to keep
+    // start bringing in what the next BRC needs while this one runs
+    const int k2 = next_brc_after(st, k);
+    if (k2 >= 0 && k2 < st->cfg.M && st->on_host[k2] && st->shadow_live[k2]) {
+      const int d2 = k2 % st->cfg.swap_slots;
+      if (d2 != slot && st->ring_mb[d2] != k2) {
+        const int e = swap_in(st, k2);
+        if (e != BAMBOO_OK) return e;
+      }
+    }
+  }
   return BAMBOO_OK;
 }
 
@@ -779,6 +868,10 @@ int stage_join(bamboo_stage_t* st) {
   if (!st) return BAMBOO_E_ARG;
   HIPCHK(hipEventRecord(st->ev_join, st->lane[1]));
   HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_join, 0));
+  if (st->host_stash) {
+    HIPCHK(hipEventRecord(st->ev_swap_join, st->lane_swap));
+    HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_swap_join, 0));
+  }
   return BAMBOO_OK;
 }
 
@@ -787,6 +880,36 @@ int stage_sync(bamboo_stage_t* st) {
   if (rc != BAMBOO_OK) return rc;
   HIPCHK(hipStreamSynchronize(st->lane[0]));
   HIPCHK(hipStreamSynchronize(st->lane[1]));
+  if (st->host_stash) HIPCHK(hipStreamSynchronize(st->lane_swap));
+  return BAMBOO_OK;
+}
+
+int stage_swap_attach(bamboo_stage_t* st, void* host_stash, uint64_t bytes, void* stream_swap) {
+  if (!st || !host_stash) return BAMBOO_E_ARG;
+  if (!swapping(st) || st->host_stash) return BAMBOO_E_STATE;
+  if (bytes < st->sizes.host_stash || ((uintptr_t)host_stash % 16)) return BAMBOO_E_ARG;
+  const int R = st->cfg.swap_slots;
+  std::vector<hipEvent_t> ev;
+  try {
+    ev.assign(4 * (size_t)R + 1, nullptr);
+    st->ring_mb.assign(R, -1);
+    st->ev_written.resize(R); st->ev_out.resize(R); st->ev_in.resize(R); st->ev_read.resize(R);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+  for (size_t i = 0; i < ev.size(); ++i)
+    if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+      st->ring_mb.clear(); st->ev_written.clear(); st->ev_out.clear(); st->ev_in.clear(); st->ev_read.clear();
+      return BAMBOO_E_HIP;
+    }
+  for (int d = 0; d < R; ++d) {
+    st->ev_written[d] = ev[4 * d]; st->ev_out[d] = ev[4 * d + 1]; st->ev_in[d] = ev[4 * d + 2]; st->ev_read[d] = ev[4 * d + 3];
+  }
+  st->ev_swap_join = ev[4 * (size_t)R];
+  st->lane_swap = (hipStream_t)stream_swap;
+  st->host_stash = (char*)host_stash;
   return BAMBOO_OK;
 }
 
@@ -834,6 +957,10 @@ int stage_destroy(bamboo_stage_t* st) {
   for (hipEvent_t e : st->ev_frc)
     if (e) (void)hipEventDestroy(e);
   if (st->ev_join) (void)hipEventDestroy(st->ev_join);
+  for (auto* v : {&st->ev_written, &st->ev_out, &st->ev_in, &st->ev_read})
+    for (hipEvent_t e : *v)
+      if (e) (void)hipEventDestroy(e);
+  if (st->ev_swap_join) (void)hipEventDestroy(st->ev_swap_join);
   delete st;
   return BAMBOO_OK;
 }

@@ -122,6 +122,19 @@ def test_sizes_and_record_addresses():
             B.stage_record_offset(cfg, kind, 0, n_layers)
 
 
+def test_sizes_with_swap():
+    sc = synth.StageConfig("b0", 0, 1, 256, 4, 1024, 200, 2, 2, 2, 4, 1, 5, 12)
+    a = B.stage_query_sizes(B.make_cfg(sc))
+    b = B.stage_query_sizes(B.make_cfg(sc, swap_slots=2))
+    assert a.host_stash == 0 and a.c_shadow == sc.M
+    assert b.c_shadow == 2 and b.shadow_stash == 2 * sc.n_shadow * b.rec_bytes
+    assert b.host_stash == sc.M * sc.n_shadow * b.rec_bytes == a.shadow_stash
+    for bad in (dict(swap_slots=-1), dict(swap_slots=sc.M + 1), dict(swap_slots=1, n_shadow=0)):
+        with pytest.raises(B.BambooError) as e:
+            B.stage_query_sizes(B.make_cfg(sc, **bad))
+        assert e.value.status == B.E_BADCFG
+
+
 def test_bad_configurations_are_rejected():
     sc = synth.CONFIGS["tiny"]
     for bad in (dict(heads=3), dict(hidden=60), dict(stage_id=2), dict(M=0), dict(arch=2), dict(dtype=5),

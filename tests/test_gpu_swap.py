@@ -1,0 +1,122 @@
+"""Swap-out of the FRC results to host memory (Section 5.2): a data-movement variant of the
+stage, so its results must be bitwise those of the device-resident stash, which the other GPU
+tests compare with the oracle.  Checked here: the host copy holds exactly the records FRC wrote,
+a failure-free iteration and a failover give the same gradients for every ring size and RC
+variant, and the oracle agrees with the recovered gradients to the stated tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import schedule as S
+from paper_2204_12013_amd import synth
+from test_gpu_stage import SMALL, _oracle
+from util import TOL, check_grads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2204_12013_amd import binding
+    return binding
+
+
+def _pair(B, sc, inp, rc_mode, swap_slots):
+    from paper_2204_12013_amd.harness import StageHarness
+    st = B.Stage(B.make_cfg(sc, rc_mode=rc_mode, swap_slots=swap_slots),
+                 B.to_device(inp["own_w"].reshape(-1), sc.dtype), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype))
+    st.shadow_stash.zero_()       # padding between the fields of a record is never written
+    scs = sc.replace(n_own=sc.n_shadow, n_shadow=0, stage_id=sc.stage_id + 1)
+    succ = B.Stage(B.make_cfg(scs, frc_enabled=False), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype), None)
+    x = [B.to_device(inp["x"][k], sc.dtype) for k in range(sc.M)]
+    gz = [B.to_device(inp["gz"][k], sc.dtype) for k in range(sc.M)]
+    torch.cuda.synchronize()
+    return st, StageHarness(st, x, gz, successor=succ)
+
+
+@pytest.mark.parametrize("name,slots", [("tiny", 1), ("tiny", 2), ("bf16_post_ln", 2), ("bf16_post_ln", 3),
+                                        ("bf16_causal_d128", 1), ("ragged_fp32_causal", 2)])
+def test_host_copy_holds_what_frc_wrote_and_gradients_are_unchanged(B, name, slots):
+    sc = SMALL[name]
+    inp = synth.make_stage_inputs(sc)
+    st0, hz0 = _pair(B, sc, inp, B.RC_EFLB, 0)
+    st1, hz1 = _pair(B, sc, inp, B.RC_EFLB, slots)
+    for _ in range(2):                                   # the ring starts afresh every iteration
+        for hz in (hz0, hz1):
+            hz.begin_iteration()
+            hz.run(hz.st.stage_schedule())
+            hz.sync()
+        assert st1.stage_schedule() == st0.stage_schedule()
+        assert torch.equal(st1.own_g, st0.own_g)
+        nb = sc.n_shadow * st0.sizes.rec_bytes
+        assert st1.sizes.host_stash == sc.M * nb
+        assert torch.equal(st1.host_stash, st0.shadow_stash[:sc.M * nb].cpu())
+        for k in range(sc.M):
+            assert torch.equal(hz1.z_frc[k], hz0.z_frc[k])
+            assert torch.equal(hz1.gx[k], hz0.gx[k])
+        st1.host_stash.zero_()
+    for s_ in (st0, hz0.succ, st1, hz1.succ):
+        s_.stage_destroy()
+
+
+@pytest.mark.parametrize("rc", ["EFLB", "LFLB", "EFEB"])
+@pytest.mark.parametrize("name,k_fail,slots", [("tiny", 2, 1), ("bf16_post_ln", 3, 2), ("bf16_post_ln", 0, 1),
+                                               ("bf16_causal_d128", 1, 3), ("ragged_fp32_causal", 4, 2)])
+def test_failover_from_the_host_copy_recovers_the_failure_free_gradients(B, name, k_fail, slots, rc):
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc = SMALL[name]
+    mode = {"EFLB": (B.RC_EFLB, S.EFLB), "LFLB": (B.RC_LFLB, S.LFLB), "EFEB": (B.RC_EFEB, S.EFEB)}[rc]
+    inp = synth.make_stage_inputs(sc)
+    st0, hz0 = _pair(B, sc, inp, B.RC_EFLB, 0)           # reference: device-resident stash, no failure
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+    st, hz = _pair(B, sc, inp, mode[0], slots)
+    prog = st.stage_schedule()
+    assert prog == S.stage_program(sc.P, sc.stage_id, sc.M, rc=mode[1])
+    hz.begin_iteration()
+    hz.run(split_at_failure(prog, k_fail))
+    hz.succ.stage_sync()
+    hz.succ.own_g.zero_()                                # the victim's gradients are gone
+    merged = st.failover_merge(k_fail)
+    assert merged == S.failover_program(sc.P, sc.stage_id, sc.M, k_fail, rc=mode[1])
+    hz.run(merged)
+    hz.sync()
+    assert torch.equal(st.own_g, st0.own_g)
+    assert torch.equal(st.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz.gx[k], hz0.gx[k])
+    if rc == "EFLB" and name != "ragged_fp32_causal":    # and against the oracle, at the stated tolerance
+        ref = _oracle(sc, inp, k_fail)
+        check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, TOL[sc.dtype], "own")
+        check_grads(st.shadow_g.cpu().numpy(), ref.G_shadow, sc.hidden, sc.ffn, TOL[sc.dtype], "shadow")
+    for s_ in (st0, hz0.succ, st, hz.succ):
+        s_.stage_destroy()
+
+
+def test_swap_misuse_is_rejected(B):
+    sc = SMALL["tiny"]
+    inp = synth.make_stage_inputs(sc)
+    w = B.to_device(inp["own_w"].reshape(-1), sc.dtype), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype)
+    st = B.Stage(B.make_cfg(sc, swap_slots=2), *w, attach_swap=False)
+    x, y = B.to_device(inp["x"][0], sc.dtype), st.new_act()
+    st.stage_begin_iteration()
+    st.stage_fwd(0, x, y)
+    with pytest.raises(B.BambooError) as e:              # no host memory attached yet
+        st.shadow_fwd_frc(0, y)
+    assert e.value.status == B.E_STATE
+    host = torch.empty(int(st.sizes.host_stash), dtype=torch.uint8, pin_memory=True)
+    stream = torch.cuda.Stream()
+    import ctypes as C
+    args = (C.c_void_p(host.data_ptr()), int(st.sizes.host_stash), C.c_void_p(stream.cuda_stream))
+    assert B.lib.stage_swap_attach(st._h, args[0], args[1] - 1, args[2]) == B.E_ARG
+    assert B.lib.stage_swap_attach(st._h, None, args[1], args[2]) == B.E_ARG
+    assert B.lib.stage_swap_attach(st._h, *args) == 0
+    assert B.lib.stage_swap_attach(st._h, *args) == B.E_STATE
+    st.host_stash, st.stream_swap = host, stream
+    st.shadow_fwd_frc(0, y)
+    st.stage_sync()
+    st.stage_destroy()
+    st = B.Stage(B.make_cfg(sc), *w)                     # not a swapping stage
+    assert B.lib.stage_swap_attach(st._h, *args) == B.E_STATE
+    st.stage_destroy()
