@@ -12,6 +12,9 @@ Modules
             (Sections 2, 5.2)
   stage     a stage executing an instruction list with simulated neighbours
             (Sections 5.1, 5.2: eager FRC, lazy BRC, recovery)
+  ends      the two ends of the model that the wrap-around stage works on (Section 5.1: the
+            last node fetches the input samples to run the first node's layers): token and
+            position embedding at the front, LM head and mean cross-entropy at the back
   optim     Adam update (Section 7 names the optimizer) and replica weight
             synchronisation (Section 5.1 requires equal parameters)
 
