@@ -87,6 +87,29 @@ int bk_gemm_tile(int code);
 int bk_adam(int dtype, int64_t n, const float* g, float* master, float* m, float* v, void* w, float lr, float beta1,
             float beta2, float eps, int step, void* stream);
 
+/* ---- the two ends of the model, worked on by the wrap-around stage only (Section 5.1: the last
+ * node keeps the replica of the first node's layers and fetches the input samples itself).  The
+ * paper does not spell them out; they are the textbook ends of the models it trains.
+ *
+ * Front: out[t,:] = E_tok[ids[t],:] + E_pos[t mod seq,:], the sum taken in fp32 and rounded to the
+ * storage type.  ids: device int32 [T]; values outside [0, V) are clamped into the range (never
+ * read out of bounds).  H a multiple of 8; E_tok [V,H], E_pos [seq,H], out [T,H] 32-byte aligned. */
+int bk_embedding_fwd(int dtype, int T, int seq, int H, int V, const int32_t* ids, const void* E_tok, const void* E_pos,
+                     void* out, void* stream);
+/* dE_tok[V,H] (fp32) += rows of g[T,H] scattered by ids, dE_pos[seq,H] (fp32) += rows of g summed over
+ * the samples.  No atomics: rows hit by several tokens are added in token order. */
+int bk_embedding_bwd(int dtype, int T, int seq, int H, int V, const int32_t* ids, const void* g, float* dE_tok,
+                     float* dE_pos, void* stream);
+/* Back: per token t, lse[t] = log sum_v exp(logits[t,v]) and loss_tok[t] = lse[t] - logits[t,labels[t]]
+ * (fp32, from the stored logits); V a multiple of 8, logits [T,V] 32-byte aligned. */
+int bk_softmax_xent_fwd(int dtype, int T, int V, const void* logits, const int32_t* labels, float* lse,
+                        float* loss_tok, void* stream);
+/* dlogits[t,v] = (exp(logits[t,v] - lse[t]) - [v == labels[t]]) * scale; dlogits may be logits. */
+int bk_softmax_xent_bwd(int dtype, int T, int V, const void* logits, const int32_t* labels, const float* lse,
+                        float scale, void* dlogits, void* stream);
+/* out[0] = scale * (in[0] + ... + in[n-1]) in a fixed order (the mean loss of a micro-batch). */
+int bk_ordered_sum(int64_t n, const float* in, float scale, float* out, void* stream);
+
 /* Tuning and test hook: force the depth of the LDS slice ring of the pipelined MFMA
  * GEMM kernel (2, 3 or 4 buffers; a depth that does not fit the tile's LDS budget
  * or exceeds the number of K slices falls back to the next smaller one); 0 restores

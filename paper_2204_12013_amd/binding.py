@@ -91,6 +91,11 @@ _SIGS = {
     "bk_layernorm_bwd": (C.c_int, [C.c_int] * 3 + [_vp] * 10),
     "bk_layernorm_bwd_scratch_floats": (C.c_uint64, [C.c_int]),
     "bk_copy": (C.c_int, [_vp, _vp, C.c_uint64, _vp]),
+    "bk_embedding_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 5),
+    "bk_embedding_bwd": (C.c_int, [C.c_int] * 5 + [_vp] * 5),
+    "bk_softmax_xent_fwd": (C.c_int, [C.c_int] * 3 + [_vp] * 5),
+    "bk_softmax_xent_bwd": (C.c_int, [C.c_int] * 3 + [_vp] * 3 + [C.c_float, _vp, _vp]),
+    "bk_ordered_sum": (C.c_int, [C.c_int64, _vp, C.c_float, _vp, _vp]),
     "bk_gemm_tile": (C.c_int, [C.c_int]),
     "bk_gemm_stages": (C.c_int, [C.c_int]),
     "bk_adam": (C.c_int, [C.c_int, C.c_int64] + [_vp] * 5 + [C.c_float] * 4 + [C.c_int, _vp]),
@@ -412,6 +417,35 @@ def bk_adam(g, master, m, v, w, step, lr=6e-3, beta1=0.9, beta2=0.999, eps=1e-8,
     """One Adam step on flat tensors: fp32 g, master, m, v; w = storage-dtype copy of the new master."""
     _check(lib.bk_adam(_dt(w), master.numel(), _ptr(g), _ptr(master), _ptr(m), _ptr(v), _ptr(w), lr, beta1, beta2,
                        eps, step, _stream(stream)), "bk_adam")
+
+
+def bk_embedding_fwd(ids, E_tok, E_pos, out, stream=None):
+    """out[t] = E_tok[ids[t]] + E_pos[t mod seq]; ids int32 [T]."""
+    V, H = E_tok.shape
+    _check(lib.bk_embedding_fwd(_dt(E_tok), ids.numel(), E_pos.shape[0], H, V, _ptr(ids), _ptr(E_tok), _ptr(E_pos),
+                                _ptr(out), _stream(stream)), "bk_embedding_fwd")
+
+
+def bk_embedding_bwd(ids, g, dE_tok, dE_pos, stream=None):
+    V, H = dE_tok.shape
+    _check(lib.bk_embedding_bwd(_dt(g), ids.numel(), dE_pos.shape[0], H, V, _ptr(ids), _ptr(g), _ptr(dE_tok),
+                                _ptr(dE_pos), _stream(stream)), "bk_embedding_bwd")
+
+
+def bk_softmax_xent_fwd(logits, labels, lse, loss_tok, stream=None):
+    T, V = logits.shape
+    _check(lib.bk_softmax_xent_fwd(_dt(logits), T, V, _ptr(logits), _ptr(labels), _ptr(lse), _ptr(loss_tok),
+                                   _stream(stream)), "bk_softmax_xent_fwd")
+
+
+def bk_softmax_xent_bwd(logits, labels, lse, scale, dlogits, stream=None):
+    T, V = logits.shape
+    _check(lib.bk_softmax_xent_bwd(_dt(logits), T, V, _ptr(logits), _ptr(labels), _ptr(lse), float(scale),
+                                   _ptr(dlogits), _stream(stream)), "bk_softmax_xent_bwd")
+
+
+def bk_ordered_sum(x, scale, out, stream=None):
+    _check(lib.bk_ordered_sum(x.numel(), _ptr(x), float(scale), _ptr(out), _stream(stream)), "bk_ordered_sum")
 
 
 def bk_gemm_stages(n):

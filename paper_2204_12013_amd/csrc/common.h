@@ -131,6 +131,17 @@ size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);
 
+// ---- model ends (wrap-around stage) ---------------------------------------------
+hipError_t launch_embed_fwd(hipStream_t s, int dtype, int T, int S, int H, int V, const int* ids, const void* Etok,
+                            const void* Epos, void* out);
+hipError_t launch_embed_bwd(hipStream_t s, int dtype, int T, int S, int H, int V, const int* ids, const void* g,
+                            float* dEtok, float* dEpos);
+hipError_t launch_xent_fwd(hipStream_t s, int dtype, int T, int V, const void* logits, const int* labels, float* lse,
+                           float* loss_tok);
+hipError_t launch_xent_bwd(hipStream_t s, int dtype, int T, int V, const void* logits, const int* labels,
+                           const float* lse, float scale, void* dlogits);
+hipError_t launch_ordered_sum(hipStream_t s, long n, const float* in, float scale, float* out);
+
 // ---- optimizer ------------------------------------------------------------------
 // Adam on n parameters (n a multiple of 4): fp32 gradient g, fp32 master weights and moments m, v
 // updated in place, w = storage-dtype copy of the new master weights.  step counts from 1.

@@ -150,6 +150,45 @@ int bk_adam(int dtype, int64_t n, const float* g, float* master, float* m, float
   return finish(launch_adam((hipStream_t)stream, dtype, (long)n, g, master, m, v, w, lr, beta1, beta2, eps, step));
 }
 
+int bk_embedding_fwd(int dtype, int T, int seq, int H, int V, const int32_t* ids, const void* E_tok, const void* E_pos,
+                     void* out, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || seq <= 0 || H <= 0 || H % 8 || V <= 0) return BAMBOO_E_ARG;
+  if (!ids || !E_tok || !E_pos || !out) return BAMBOO_E_ARG;
+  if (((uintptr_t)E_tok | (uintptr_t)E_pos | (uintptr_t)out) & 31) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_embed_fwd((hipStream_t)stream, dtype, T, seq, H, V, ids, E_tok, E_pos, out));
+}
+
+int bk_embedding_bwd(int dtype, int T, int seq, int H, int V, const int32_t* ids, const void* g, float* dE_tok,
+                     float* dE_pos, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || seq <= 0 || T % seq || H <= 0 || V <= 0) return BAMBOO_E_ARG;
+  if (!ids || !g || !dE_tok || !dE_pos) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_embed_bwd((hipStream_t)stream, dtype, T, seq, H, V, ids, g, dE_tok, dE_pos));
+}
+
+int bk_softmax_xent_fwd(int dtype, int T, int V, const void* logits, const int32_t* labels, float* lse,
+                        float* loss_tok, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || V <= 0 || V % 8) return BAMBOO_E_ARG;
+  if (!logits || !labels || !lse || !loss_tok || ((uintptr_t)logits & 31)) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_xent_fwd((hipStream_t)stream, dtype, T, V, logits, labels, lse, loss_tok));
+}
+
+int bk_softmax_xent_bwd(int dtype, int T, int V, const void* logits, const int32_t* labels, const float* lse,
+                        float scale, void* dlogits, void* stream) {
+  if ((dtype != 0 && dtype != 1) || T <= 0 || V <= 0 || V % 8) return BAMBOO_E_ARG;
+  if (!logits || !labels || !lse || !dlogits || (((uintptr_t)logits | (uintptr_t)dlogits) & 31)) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_xent_bwd((hipStream_t)stream, dtype, T, V, logits, labels, lse, scale, dlogits));
+}
+
+int bk_ordered_sum(int64_t n, const float* in, float scale, float* out, void* stream) {
+  if (n <= 0 || !in || !out) return BAMBOO_E_ARG;
+  (void)hipGetLastError();
+  return finish(launch_ordered_sum((hipStream_t)stream, (long)n, in, scale, out));
+}
+
 int bk_gemm_tile(int code) {
   if (!gemm_tile_code_valid(code)) return BAMBOO_E_ARG;
   return set_gemm_tile(code);

@@ -145,3 +145,54 @@ def make_stage_inputs(cfg, n_microbatches=None):
     gz = rng.standard_normal((M, T, H), dtype=np.float32) / np.float32(np.sqrt(T * H))
     r = lambda a: round_to_storage(a, cfg.dtype)
     return {"own_w": r(own), "shadow_w": r(shadow), "x": r(x), "gz": r(gz)}
+
+
+# ---- the two ends of the model (wrap-around stage) ------------------------------
+# Vocabulary sizes of the paper's language models, padded up to a multiple of 64 as is usual so that the
+# head's matrices tile evenly: BERT's 30522 WordPiece entries, GPT-2's 50257 BPE entries.
+VOCAB = {"bert_large_stage": 30528, "gpt2_1p5b_stage": 50304}
+
+
+def front_param_count(arch, V, S, H):
+    """E_tok [V,H] | E_pos [S,H] | gain [H] | shift [H] (the last two only for the post-LN encoder)."""
+    return V * H + S * H + (2 * H if arch == ARCH_POST_LN_ENCODER else 0)
+
+
+def back_param_count(arch, V, H):
+    """gain [H] | shift [H] (only for the pre-LN decoder: its final LayerNorm) | W_head [H,V]."""
+    return (2 * H if arch == ARCH_PRE_LN_CAUSAL else 0) + H * V
+
+
+def zipf_ids(rng, V, shape):
+    """Token ids with Zipf's rank-frequency law (probability of id r proportional to 1/(r+1)): text corpora
+    such as the paper's Wikipedia dump repeat a few tokens very often, which is what the embedding gradient
+    has to add up."""
+    p = 1.0 / np.arange(1, V + 1, dtype=np.float64)
+    p /= p.sum()
+    return rng.choice(V, size=shape, p=p).astype(np.int32)
+
+
+def make_ends_inputs(cfg, V, n_microbatches=None):
+    """Draw the front and back parameters, token ids, labels and the gradients arriving at the front
+    stage's output, in a fixed order (its own seed stream, so the stage inputs do not move).
+
+      front_w [front_param_count]  back_w [back_param_count]   float32, rounded to the storage type
+      ids, labels [M, T] int32     g1 [M, T, H] gradients from the stage after the front stage
+    """
+    M = cfg.M if n_microbatches is None else n_microbatches
+    rng = np.random.default_rng([cfg.seed, 77])
+    H, S, T = cfg.hidden, cfg.seq, cfg.tokens
+    nrm = lambda n: rng.standard_normal(n, dtype=np.float32) * np.float32(0.02)
+    front = [nrm(V * H), nrm(S * H)]
+    if cfg.arch == ARCH_POST_LN_ENCODER:
+        front += [nrm(H) + np.float32(1.0), nrm(H)]
+    back = []
+    if cfg.arch == ARCH_PRE_LN_CAUSAL:
+        back += [nrm(H) + np.float32(1.0), nrm(H)]
+    back.append(nrm(H * V))
+    ids = zipf_ids(rng, V, (M, T))
+    labels = zipf_ids(rng, V, (M, T))
+    g1 = rng.standard_normal((M, T, H), dtype=np.float32) / np.float32(np.sqrt(T * H))
+    r = lambda a: round_to_storage(a, cfg.dtype)
+    return {"front_w": r(np.concatenate(front)), "back_w": r(np.concatenate(back)), "ids": ids, "labels": labels,
+            "g1": r(g1)}
