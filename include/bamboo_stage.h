@@ -91,6 +91,10 @@ typedef struct {
                           paper's swap-out (Section 5.2): the device keeps a ring of R shadow slots, the
                           results of every FRC are copied to pinned host memory on a third stream and copied
                           back only for BRC.  Needs stage_swap_attach before the first FRC. */
+  int32_t wrap;        /* 1: this is the last stage (stage_id == P-1) and its replica layers are the FIRST
+                          stage's (Section 5.1: the last node is the first node's predecessor and fetches
+                          the input samples itself).  FRC(k) then does not depend on FWD(k), and the
+                          failover schedule is the wrap-around one.  Not with eager BRC.  0 otherwise. */
 } bamboo_cfg_t;
 
 /* Instruction set: the paper's computation and communication instructions
@@ -172,6 +176,18 @@ int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const i
  * lost, then the rest of the 1F1B program with the victim's groups merged in.
  * Same out/cap/return convention as stage_program. */
 int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
+
+/* With cfg.wrap the victim is the first stage and the shadow the last.  The two are the two ends of
+ * the pipeline, so no traffic between them turns internal (unless P == 2).  stage_failover_program
+ * then returns: JOIN up to FRC(k_fail); BRC replay of the micro-batches the victim had
+ * back-propagated (their gradients come again from the second stage); then everything either
+ * stage still has to do, merged by start time on the failure-free slot timeline (ties: backward
+ * before forward, the victim's before the shadow's own).  The victim's forwards are FRCs on the
+ * fetched samples, all still to do beyond k_fail; their outputs are sent to the second stage
+ * only where the victim had not delivered them.
+ * stage_wrap_victim_progress: how many forwards / backwards the first stage had finished on that
+ * timeline when the last stage finishes FWD(k_fail) (host int32 outputs). */
+int stage_wrap_victim_progress(const bamboo_cfg_t* cfg, int32_t k_fail, int32_t* n_fwd, int32_t* n_bwd);
 
 /* Byte offset of stash record (slot, layer) inside a stash arena:
  * (slot * n_layers + layer) * rec_bytes.  kind 0 own, 1 shadow.  Negative status

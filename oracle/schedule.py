@@ -243,3 +243,85 @@ def fmt(prog):
         OP_NAMES[op] + ("" if mb < 0 else "(%d)" % mb) +
         ("[%d]" % arg if op in (BUBBLE,) else "") + ("@1" if lane else "")
         for op, lane, mb, arg in prog)
+
+
+# ---- wrap-around: the last stage shadows the first (Section 5.1) ------------------
+
+def wrap_victim_progress(P, M, k_fail, tick_F=1, tick_B=2):
+    """State of the first stage when the last stage finishes FWD(k_fail) in the failure-free
+    timeline: (number of forwards, number of backwards) the first stage has completed by then.
+    Both run in micro-batch order, so the counts say which ones."""
+    start, end, _ = timeline(P, M, tick_F, tick_B)
+    last = compute_order(P, P - 1, M)
+    t_star = end[P - 1][last.index(("F", k_fail))]
+    first = compute_order(P, 0, M)
+    nf = sum(1 for j, (kind, _) in enumerate(first) if kind == "F" and end[0][j] <= t_star)
+    nb = sum(1 for j, (kind, _) in enumerate(first) if kind == "B" and end[0][j] <= t_star)
+    return nf, nb
+
+
+def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2):
+    """Failover schedule of the last stage (s = P-1) after the first stage, whose replica it holds,
+    is lost.  The last stage notices right after FWD(k_fail) and its FRC, as a middle stage does.
+
+    The two merged stages are the two ends of the pipeline, so unlike the adjacent case no
+    traffic between them becomes internal (unless P = 2, where each is the other's only
+    neighbour and all of it does).  The schedule:
+      (i)   wait for the FRC stream up to FRC(k_fail);
+      (ii)  replay BRC over the micro-batches whose first-stage backward had run (their gradient
+            contributions died with the victim); the second stage sends their gradients again;
+      (iii) everything else either stage still has to do, ordered by its start time in the
+            failure-free timeline (a valid order: whatever a computation depends on started
+            earlier there), ties broken as in the adjacent case -- backward work before forward
+            work, the victim's before the shadow's own.  The victim's forwards are FRCs on the
+            samples the last node fetches itself; they are all still to do beyond k_fail, and
+            their outputs go to the second stage unless the victim had delivered them already.
+    Communication is emitted as in the normal program: the send of what the previous computation
+    of a stage produced, then the receive the next one needs, right before it.
+    """
+    assert P >= 2 and 0 <= k_fail < M
+    s = P - 1
+    C = own_slots(P, s, M)
+    start, end, _ = timeline(P, M, tick_F, tick_B)
+    nf, nb = wrap_victim_progress(P, M, k_fail, tick_F, tick_B)
+    far = P > 2                               # the victim's neighbour is not the shadow itself
+    prog = [(JOIN, 0, -1, k_fail)]
+    for k in range(nb):
+        if far:
+            prog.append((RECV_GRAD, 0, k, 1))
+        prog.append((BRC, 0, k, k))
+    own = compute_order(P, s, M)
+    j0 = own.index(("F", k_fail)) + 1
+    items = []                                # (start time, 0 backward / 1 forward, 0 victim / 1 own, kind, k)
+    for j in range(j0, len(own)):
+        kind, k = own[j]
+        items.append((start[s][j], 0 if kind == "B" else 1, 1, kind, k))
+    for j, (kind, k) in enumerate(compute_order(P, 0, M)):
+        if (kind == "F" and k > k_fail) or (kind == "B" and k >= nb):
+            items.append((start[0][j], 0 if kind == "B" else 1, 0, kind, k))
+    items.sort()
+    pending = []                              # sends owed for computations already emitted
+    for _, _, is_own, kind, k in items:
+        prog += pending
+        pending = []
+        if is_own:
+            if kind == "F":
+                if far:
+                    prog.append((RECV_ACT, 0, k, s - 1))
+                prog.append((FWD, 0, k, k % C))
+            else:
+                prog.append((BWD, 0, k, k % C))
+                if far:
+                    pending.append((SEND_GRAD, 0, k, s - 1))
+        else:
+            if kind == "F":
+                prog.append((FRC, 0, k, k))
+                if far and k >= nf:
+                    pending.append((SEND_ACT, 0, k, 1))
+            else:
+                if far:
+                    prog.append((RECV_GRAD, 0, k, 1))
+                prog.append((BRC, 0, k, k))
+    prog += pending
+    prog += [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
+    return prog

@@ -121,3 +121,76 @@ def run_with_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz, k_fail, e
     sim.run(S.prefix_until_failure(P, s, M, k_fail, rc=rc))
     sim.preempt_successor()
     return sim.run(S.failover_program(P, s, M, k_fail, rc=rc))
+
+
+# ---- wrap-around: the last stage holds the replica of the first (Section 5.1) ------------
+
+class WrapStageSim:
+    """The last stage (own layers + the model's back end: LM head and loss) shadowing the first
+    stage (the model's front end: embedding, + its layers), which takes the samples' token ids
+    as input -- the last node fetches them itself.  Backward of the own layers starts from the
+    loss; BRC starts from the gradient the second stage sends (a table here)."""
+
+    def __init__(self, arch, own_layers, back, shadow_layers, front, B, S_len, n_h, P, M,
+                 x_table, labels, ids, g1_table, eps=1e-5):
+        from . import ends as E
+        self.E = E
+        self.arch, self.B, self.S, self.n_h, self.eps = arch, B, S_len, n_h, eps
+        self.own, self.back, self.shadow, self.front = own_layers, back, shadow_layers, front
+        self.P, self.M = P, M
+        self.x, self.labels, self.ids, self.g1 = x_table, labels, ids, g1_table
+        self.C_own = S.own_slots(P, P - 1, M)
+        self.own_stash, self.shadow_stash = {}, {}
+        self.G_own = _zeros_like_params(own_layers)
+        self.G_shadow = _zeros_like_params(shadow_layers)
+        self.G_back = {n: np.zeros_like(v) for n, v in back.items()}
+        self.G_front = {n: np.zeros_like(v) for n, v in front.items()}
+        self.loss, self.z_frc, self.gx, self.dx0 = {}, {}, {}, {}
+
+    def run(self, prog):
+        E = self.E
+        for op, lane, k, arg in prog:
+            if op == S.FWD:
+                assert arg == k % self.C_own and arg not in self.own_stash
+                y, caches = L.stack_fwd(self.arch, self.own, self.x[k], self.B, self.S, self.n_h, self.eps)
+                self.loss[k], _, cb = E.back_fwd(self.arch, self.back, y, self.labels[k], self.eps)
+                self.own_stash[arg] = (k, caches, cb)
+            elif op == S.BWD:
+                kk, caches, cb = self.own_stash.pop(arg)
+                assert kk == k
+                dy, gb = E.back_bwd(self.arch, self.back, cb)
+                self.gx[k], grads = L.stack_bwd(self.arch, self.own, caches, dy)
+                _acc(self.G_own, grads)
+                for n in gb:
+                    self.G_back[n] = self.G_back[n] + gb[n]
+            elif op == S.FRC:
+                assert arg == k and k not in self.shadow_stash
+                x0, cf = E.front_fwd(self.arch, self.front, self.ids[k], self.S, self.eps)
+                self.z_frc[k], caches = L.stack_fwd(self.arch, self.shadow, x0, self.B, self.S, self.n_h, self.eps)
+                self.shadow_stash[k] = (caches, cf)
+            elif op == S.BRC:
+                caches, cf = self.shadow_stash.pop(arg)
+                self.dx0[k], grads = L.stack_bwd(self.arch, self.shadow, caches, self.g1[k])
+                _acc(self.G_shadow, grads)
+                gf = E.front_bwd(self.arch, self.front, cf, self.dx0[k])
+                for n in gf:
+                    self.G_front[n] = self.G_front[n] + gf[n]
+        return self
+
+
+def wrap_first_stage_reference(arch, layers, front, B, S_len, n_h, M, ids, g1_table, eps=1e-5):
+    """What the first stage itself accumulates over an iteration without a failure: gradients of
+    its layers and of the model's front end (what failover has to reproduce)."""
+    from . import ends as E
+    G = _zeros_like_params(layers)
+    Gf = {n: np.zeros_like(v) for n, v in front.items()}
+    z = {}
+    for k in range(M):
+        x0, cf = E.front_fwd(arch, front, ids[k], S_len, eps)
+        z[k], caches = L.stack_fwd(arch, layers, x0, B, S_len, n_h, eps)
+        dx0, grads = L.stack_bwd(arch, layers, caches, g1_table[k])
+        _acc(G, grads)
+        gf = E.front_bwd(arch, front, cf, dx0)
+        for n in gf:
+            Gf[n] = Gf[n] + gf[n]
+    return G, Gf, z

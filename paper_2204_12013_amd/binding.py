@@ -28,7 +28,7 @@ KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd"
 class Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("arch", "dtype", "hidden", "heads", "ffn", "seq", "micro_batch", "n_own", "n_shadow",
-                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float), ("swap_slots", C.c_int32)]
+                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float), ("swap_slots", C.c_int32), ("wrap", C.c_int32)]
 
 
 class Instr(C.Structure):
@@ -40,6 +40,12 @@ class Sizes(C.Structure):
                 ("own_w", "shadow_w", "own_g", "shadow_g", "own_stash", "shadow_stash", "workspace",
                  "rec_bytes", "layer_params")] + [("c_own", C.c_int32), ("c_shadow", C.c_int32)] + \
         [("own_opt", C.c_uint64), ("shadow_opt", C.c_uint64), ("host_stash", C.c_uint64)]
+
+
+class EndsSizes(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in
+                ("front_params", "back_params", "front_w", "back_w", "front_g", "back_g", "front_stash",
+                 "back_stash", "workspace")]
 
 
 class Adam(C.Structure):
@@ -59,6 +65,7 @@ _SIGS = {
     "stage_program": (C.c_int, [_cfgp, _insp, _i32]),
     "stage_program_uneven": (C.c_int, [_cfgp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _insp, _i32]),
     "stage_failover_program": (C.c_int, [_cfgp, _i32, _insp, _i32]),
+    "stage_wrap_victim_progress": (C.c_int, [_cfgp, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "stage_record_offset": (_i64, [_cfgp, _i32, _i32, _i32]),
     "stage_strerror": (C.c_char_p, [C.c_int]),
     "stage_record_fields": (C.c_int, [_cfgp, C.POINTER(C.c_uint64)]),
@@ -80,6 +87,14 @@ _SIGS = {
     "stage_destroy": (C.c_int, [_vp]),
     "stage_profile": (C.c_int, [_vp, C.c_int]),
     "stage_profile_read": (C.c_int, [_vp, _i32, C.POINTER(C.c_double), C.POINTER(_i64), C.POINTER(C.c_double)]),
+    "ends_query_sizes": (C.c_int, [_cfgp, _i32, C.POINTER(EndsSizes)]),
+    "ends_init": (C.c_int, [_cfgp, _i32, C.POINTER(EndsSizes)] + [_vp] * 7 + [C.POINTER(_vp)]),
+    "ends_front_fwd": (C.c_int, [_vp, _i32, _vp, _vp, _vp]),
+    "ends_front_bwd": (C.c_int, [_vp, _i32, _vp, _vp]),
+    "ends_back_fwd": (C.c_int, [_vp, _vp, _vp, _vp, _vp]),
+    "ends_back_bwd": (C.c_int, [_vp, _vp, _vp]),
+    "ends_begin_iteration": (C.c_int, [_vp]),
+    "ends_destroy": (C.c_int, [_vp]),
     "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
     "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
     "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
@@ -123,13 +138,19 @@ def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, rc_mode=None
     vals = dict(arch=sc.arch, dtype=sc.dtype, hidden=sc.hidden, heads=sc.heads, ffn=sc.ffn, seq=sc.seq,
                 micro_batch=sc.micro_batch, n_own=sc.n_own, n_shadow=sc.n_shadow, P=sc.P,
                 stage_id=sc.stage_id, M=sc.M, rc_mode=int(rc_mode), tick_F=tick_F, tick_B=tick_B,
-                ln_eps=ln_eps, swap_slots=0)
+                ln_eps=ln_eps, swap_slots=0, wrap=0)
     vals.update(override)
     return Cfg(**vals)
 
 
 def _instr_list(arr, n):
     return [(int(i.op), int(i.lane), int(i.mb), int(i.arg)) for i in arr[:n]]
+
+
+def stage_wrap_victim_progress(cfg, k_fail):
+    a, b = C.c_int32(), C.c_int32()
+    _check(lib.stage_wrap_victim_progress(C.byref(cfg), k_fail, C.byref(a), C.byref(b)), "stage_wrap_victim_progress")
+    return a.value, b.value
 
 
 def stage_query_sizes(cfg):
@@ -451,6 +472,61 @@ def bk_ordered_sum(x, scale, out, stream=None):
 def bk_gemm_stages(n):
     """Force the LDS ring depth of the pipelined MFMA GEMM (2..4; 0 = automatic); returns the previous value."""
     return _check(lib.bk_gemm_stages(n), "bk_gemm_stages")
+
+
+def ends_query_sizes(cfg, vocab):
+    sz = EndsSizes()
+    _check(lib.ends_query_sizes(C.byref(cfg), vocab, C.byref(sz)), "ends_query_sizes")
+    return sz
+
+
+class Ends:
+    """The model's front (embedding) and back (LM head + loss) around a wrap-around stage: owns their
+    device buffers and forwards every call to the C ABI."""
+
+    def __init__(self, cfg, vocab, front_w, back_w, device="cuda:0"):
+        import torch
+        self.torch, self.cfg, self.vocab = torch, cfg, vocab
+        self.device = torch.device(device)
+        self.sizes = sz = ends_query_sizes(cfg, vocab)
+        act = torch.bfloat16 if cfg.dtype == 1 else torch.float32
+        assert front_w.dtype == act and front_w.numel() == sz.front_params
+        assert back_w.dtype == act and back_w.numel() == sz.back_params
+        self.front_w, self.back_w = front_w.to(self.device).contiguous(), back_w.to(self.device).contiguous()
+        self.front_g = torch.zeros(int(sz.front_params), dtype=torch.float32, device=self.device)
+        self.back_g = torch.zeros(int(sz.back_params), dtype=torch.float32, device=self.device)
+        buf = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=self.device)
+        self.front_stash, self.back_stash, self.workspace = buf(sz.front_stash), buf(sz.back_stash), buf(sz.workspace)
+        self._h = C.c_void_p()
+        torch.cuda.synchronize(self.device)
+        _check(lib.ends_init(C.byref(cfg), vocab, C.byref(sz), _ptr(self.front_w), _ptr(self.front_g),
+                             _ptr(self.back_w), _ptr(self.back_g), _ptr(self.front_stash), _ptr(self.back_stash),
+                             _ptr(self.workspace), C.byref(self._h)), "ends_init")
+
+    def zero_grads(self, stream):
+        with self.torch.cuda.stream(stream):
+            self.front_g.zero_()
+            self.back_g.zero_()
+
+    def ends_begin_iteration(self):
+        _check(lib.ends_begin_iteration(self._h), "ends_begin_iteration")
+
+    def ends_front_fwd(self, k, ids, x0, stream):
+        _check(lib.ends_front_fwd(self._h, k, _ptr(ids), _ptr(x0), _stream(stream)), "ends_front_fwd")
+
+    def ends_front_bwd(self, k, dx0, stream):
+        _check(lib.ends_front_bwd(self._h, k, _ptr(dx0), _stream(stream)), "ends_front_bwd")
+
+    def ends_back_fwd(self, y, labels, loss, stream):
+        _check(lib.ends_back_fwd(self._h, _ptr(y), _ptr(labels), _ptr(loss), _stream(stream)), "ends_back_fwd")
+
+    def ends_back_bwd(self, gy, stream):
+        _check(lib.ends_back_bwd(self._h, _ptr(gy), _stream(stream)), "ends_back_bwd")
+
+    def ends_destroy(self):
+        if self._h:
+            _check(lib.ends_destroy(self._h), "ends_destroy")
+            self._h = C.c_void_p()
 
 
 # ---- numpy <-> device helpers (storage conversion only) ------------------------

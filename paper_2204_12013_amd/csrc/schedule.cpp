@@ -36,35 +36,59 @@ std::vector<int> idle_before(int P, int s, int M, int tick_F, int tick_B, int* t
   return idle_before(P, s, M, f.data(), b.data(), tail);
 }
 
-std::vector<int> idle_before(int P, int s, int M, const int* tick_F, const int* tick_B, int* tail) {
-  // Play all P stages: a stage advances through its sequence whenever the same
-  // micro-batch has finished on the neighbour it depends on (previous stage for
-  // a forward, next stage for a backward).  fwd_end/bwd_end hold finishing times.
+namespace {
+// Start and finishing time of every computation of every stage on the zero-latency timeline:
+// t[stage][0 forward / 1 backward][micro-batch].
+struct Timeline {
+  std::vector<std::vector<long>> start[2], end[2];
+  std::vector<long> clock;   // finishing time of each stage's last computation
+};
+
+// Play all P stages: a stage advances through its sequence whenever the same
+// micro-batch has finished on the neighbour it depends on (previous stage for
+// a forward, next stage for a backward).
+Timeline play(int P, int M, const int* tick_F, const int* tick_B) {
+  Timeline t;
+  for (int d = 0; d < 2; ++d) {
+    t.start[d].assign(P, std::vector<long>(M, -1));
+    t.end[d].assign(P, std::vector<long>(M, -1));
+  }
+  t.clock.assign(P, 0);
   std::vector<std::vector<Step>> seq(P);
   for (int st = 0; st < P; ++st) seq[st] = one_f_one_b(P, st, M);
-  std::vector<std::vector<long>> fwd_end(P, std::vector<long>(M, -1)), bwd_end(P, std::vector<long>(M, -1));
   std::vector<size_t> cursor(P, 0);
-  std::vector<long> clock(P, 0);
-  std::vector<int> gaps(seq[s].size(), 0);
   for (bool moved = true; moved;) {
     moved = false;
     for (int st = 0; st < P; ++st) {
       while (cursor[st] < seq[st].size()) {
         const Step c = seq[st][cursor[st]];
         long ready = 0;
-        if (!c.backward && st > 0) ready = fwd_end[st - 1][c.mb];
-        if (c.backward && st < P - 1) ready = bwd_end[st + 1][c.mb];
+        if (!c.backward && st > 0) ready = t.end[0][st - 1][c.mb];
+        if (c.backward && st < P - 1) ready = t.end[1][st + 1][c.mb];
         if (ready < 0) break;  // neighbour has not produced it yet
-        const long t0 = std::max(clock[st], ready);
-        if (st == s) gaps[cursor[st]] = (int)(t0 - clock[st]);
-        clock[st] = t0 + (c.backward ? tick_B[st] : tick_F[st]);
-        (c.backward ? bwd_end : fwd_end)[st][c.mb] = clock[st];
+        const long t0 = std::max(t.clock[st], ready);
+        t.start[c.backward][st][c.mb] = t0;
+        t.clock[st] = t0 + (c.backward ? tick_B[st] : tick_F[st]);
+        t.end[c.backward][st][c.mb] = t.clock[st];
         ++cursor[st];
         moved = true;
       }
     }
   }
-  *tail = (int)(*std::max_element(clock.begin(), clock.end()) - clock[s]);
+  return t;
+}
+}  // namespace
+
+std::vector<int> idle_before(int P, int s, int M, const int* tick_F, const int* tick_B, int* tail) {
+  const Timeline t = play(P, M, tick_F, tick_B);
+  const std::vector<Step> seq = one_f_one_b(P, s, M);
+  std::vector<int> gaps(seq.size(), 0);
+  long clock = 0;
+  for (size_t j = 0; j < seq.size(); ++j) {
+    gaps[j] = (int)(t.start[seq[j].backward][s][seq[j].mb] - clock);
+    clock = t.end[seq[j].backward][s][seq[j].mb];
+  }
+  *tail = (int)(*std::max_element(t.clock.begin(), t.clock.end()) - t.clock[s]);
   return gaps;
 }
 
@@ -196,6 +220,87 @@ std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_
       z_pending.push_back(gf->mb);
     }
   }
+  epilogue(out);
+  return out;
+}
+
+// Wrap-around (Section 5.1): the last stage holds the replica of the first stage, which is lost.
+// The last stage notices after FWD(k_fail) and its FRC.  Where the victim stood at that moment
+// comes from the zero-latency timeline: it had finished n_fwd forwards and n_bwd backwards.
+void wrap_victim_progress(const bamboo_cfg_t& c, int k_fail, int* n_fwd, int* n_bwd) {
+  const int P = c.P, M = c.M;
+  const std::vector<int> tf(P, c.tick_F), tb(P, c.tick_B);
+  const Timeline t = play(P, M, tf.data(), tb.data());
+  const long t_star = t.end[0][P - 1][k_fail];
+  *n_fwd = *n_bwd = 0;
+  for (int k = 0; k < M; ++k) {
+    *n_fwd += t.end[0][0][k] <= t_star;
+    *n_bwd += t.end[1][0][k] <= t_star;
+  }
+}
+
+// The merged node is both ends of the pipeline, so no traffic turns internal unless P = 2.
+// After the replay of the victim's finished backwards, what is left of the two stages' 1F1B
+// sequences is merged by start time on the failure-free timeline (anything a computation needs
+// started earlier there); on equal times backward work goes first, then the victim's.  Each
+// sequence is already in time order, so this is a two-way merge.
+std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, int k_fail) {
+  const int P = c.P, s = P - 1, M = c.M;
+  const int slots = own_slot_count(P, s, M);
+  const bool far = P > 2;
+  const std::vector<int> tf(P, c.tick_F), tb(P, c.tick_B);
+  const Timeline t = play(P, M, tf.data(), tb.data());
+  int n_fwd = 0, n_bwd = 0;
+  wrap_victim_progress(c, k_fail, &n_fwd, &n_bwd);
+  std::vector<bamboo_instr_t> out;
+  out.push_back(ins(BAMBOO_JOIN, 0, -1, k_fail));
+  for (int k = 0; k < n_bwd; ++k) {
+    if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, 1));
+    out.push_back(ins(BAMBOO_BRC, 0, k, k));
+  }
+  // what is left: own sequence behind FWD(k_fail); victim forwards beyond k_fail, victim backwards from n_bwd
+  std::vector<Step> own = one_f_one_b(P, s, M), vic;
+  size_t io = 0;
+  while (!(!own[io].backward && own[io].mb == k_fail)) ++io;
+  ++io;
+  for (const Step& v : one_f_one_b(P, 0, M))
+    if (v.backward ? v.mb >= n_bwd : v.mb > k_fail) vic.push_back(v);
+  size_t iv = 0;
+  auto key = [&](const Step& st, int stage) { return t.start[st.backward][stage][st.mb]; };
+  std::vector<bamboo_instr_t> owed;   // sends of the computation emitted last
+  while (io < own.size() || iv < vic.size()) {
+    bool take_victim;
+    if (io >= own.size()) take_victim = true;
+    else if (iv >= vic.size()) take_victim = false;
+    else {
+      const long tv = key(vic[iv], 0), to = key(own[io], s);
+      if (tv != to) take_victim = tv < to;
+      else if (vic[iv].backward != own[io].backward) take_victim = vic[iv].backward;
+      else take_victim = true;
+    }
+    out.insert(out.end(), owed.begin(), owed.end());
+    owed.clear();
+    if (take_victim) {
+      const Step v = vic[iv++];
+      if (v.backward) {
+        if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, v.mb, 1));
+        out.push_back(ins(BAMBOO_BRC, 0, v.mb, v.mb));
+      } else {
+        out.push_back(ins(BAMBOO_FRC, 0, v.mb, v.mb));
+        if (far && v.mb >= n_fwd) owed.push_back(ins(BAMBOO_SEND_ACT, 0, v.mb, 1));
+      }
+    } else {
+      const Step o = own[io++];
+      if (o.backward) {
+        out.push_back(ins(BAMBOO_BWD, 0, o.mb, o.mb % slots));
+        if (far) owed.push_back(ins(BAMBOO_SEND_GRAD, 0, o.mb, s - 1));
+      } else {
+        if (far) out.push_back(ins(BAMBOO_RECV_ACT, 0, o.mb, s - 1));
+        out.push_back(ins(BAMBOO_FWD, 0, o.mb, o.mb % slots));
+      }
+    }
+  }
+  out.insert(out.end(), owed.begin(), owed.end());
   epilogue(out);
   return out;
 }

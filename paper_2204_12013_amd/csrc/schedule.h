@@ -26,5 +26,8 @@ std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c);
 // per-stage durations; null arrays fall back to c.tick_F / c.tick_B for every stage
 std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c, const int* tick_F, const int* tick_B);
 std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_fail);
+// wrap-around: the last stage takes over the lost first stage (cfg.wrap)
+std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, int k_fail);
+void wrap_victim_progress(const bamboo_cfg_t& c, int k_fail, int* n_fwd, int* n_bwd);
 
 }  // namespace bamboo

@@ -132,6 +132,9 @@ int validate(const bamboo_cfg_t* c) {
   if (c->rc_mode != BAMBOO_RC_LFLB && c->rc_mode != BAMBOO_RC_EFLB && c->rc_mode != BAMBOO_RC_EFEB) return BAMBOO_E_BADCFG;
   if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
   if (c->swap_slots < 0 || c->swap_slots > c->M || (c->swap_slots > 0 && c->n_shadow <= 0)) return BAMBOO_E_BADCFG;
+  if (c->wrap != 0 && c->wrap != 1) return BAMBOO_E_BADCFG;
+  if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode == BAMBOO_RC_EFEB))
+    return BAMBOO_E_BADCFG;
   return BAMBOO_OK;
 }
 
@@ -567,13 +570,31 @@ int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const i
 int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
   const int v = validate(cfg);
   if (v != BAMBOO_OK) return v;
-  if (cfg->n_shadow <= 0 || cfg->stage_id >= cfg->P - 1) return BAMBOO_E_STATE;
+  if (cfg->n_shadow <= 0 || (cfg->stage_id >= cfg->P - 1 && !cfg->wrap)) return BAMBOO_E_STATE;
   if (k_fail < 0 || k_fail >= cfg->M) return BAMBOO_E_BADMB;
   try {
-    return copy_out(build_failover_program(*cfg, k_fail), out, cap);
+    return copy_out(cfg->wrap ? build_wrap_failover_program(*cfg, k_fail) : build_failover_program(*cfg, k_fail), out,
+                    cap);
   } catch (const std::bad_alloc&) {
     return BAMBOO_E_NOMEM;
   }
+}
+
+int stage_wrap_victim_progress(const bamboo_cfg_t* cfg, int32_t k_fail, int32_t* n_fwd, int32_t* n_bwd) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (!n_fwd || !n_bwd) return BAMBOO_E_ARG;
+  if (!cfg->wrap) return BAMBOO_E_STATE;
+  if (k_fail < 0 || k_fail >= cfg->M) return BAMBOO_E_BADMB;
+  try {
+    int a = 0, b = 0;
+    wrap_victim_progress(*cfg, k_fail, &a, &b);
+    *n_fwd = a;
+    *n_bwd = b;
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+  return BAMBOO_OK;
 }
 
 int64_t stage_record_offset(const bamboo_cfg_t* cfg, int32_t kind, int32_t slot, int32_t layer) {
@@ -695,10 +716,11 @@ int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z) {
   // lazy FRC: only the failover schedule runs it
   if (st->cfg.n_shadow <= 0 || (st->cfg.rc_mode == BAMBOO_RC_LFLB && !st->merged)) return BAMBOO_E_STATE;
   if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
-  if (!st->fwd_issued[k] || st->frc_issued[k]) return BAMBOO_E_BADMB;
+  // the replica of the first stage works on the samples, not on this stage's output
+  if ((!st->fwd_issued[k] && !st->cfg.wrap) || st->frc_issued[k]) return BAMBOO_E_BADMB;
   const int lane_id = st->merged ? 0 : 1;
   hipEvent_t ev;
-  if (lane_id == 1) {
+  if (lane_id == 1 && !st->cfg.wrap) {
     if (get_event(st->ev_fwd, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
     HIPCHK(hipStreamWaitEvent(st->lane[1], ev, 0));
   }
@@ -788,11 +810,11 @@ int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy) {
 
 int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
   if (!st) return BAMBOO_E_ARG;
-  if (st->merged || st->cfg.n_shadow <= 0 || st->cfg.stage_id >= st->cfg.P - 1) return BAMBOO_E_STATE;
+  if (st->merged || st->cfg.n_shadow <= 0 || (st->cfg.stage_id >= st->cfg.P - 1 && !st->cfg.wrap)) return BAMBOO_E_STATE;
   if (k_fail < 0 || k_fail >= st->cfg.M) return BAMBOO_E_BADMB;
   std::vector<bamboo_instr_t> prog;
   try {
-    prog = build_failover_program(st->cfg, k_fail);
+    prog = st->cfg.wrap ? build_wrap_failover_program(st->cfg, k_fail) : build_failover_program(st->cfg, k_fail);
   } catch (const std::bad_alloc&) {
     return BAMBOO_E_NOMEM;
   }

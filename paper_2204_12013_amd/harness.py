@@ -98,6 +98,61 @@ class StageHarness:
             self.succ.stage_sync()
 
 
+class WrapHarness:
+    """Interpreter around the wrap-around stage: a Stage with cfg.wrap plus the model's Ends.  The stage
+    before the last (P-2) is a table of inputs x_k, the samples are tables of token ids and labels, and the
+    second stage, which returns the gradient at the first stage's output, is the table g1_k.  Every
+    compute instruction is the pair of C ABI calls that the ends' header gives for it."""
+
+    def __init__(self, stage, ends, x, ids, labels, g1, us_per_tick=0.0):
+        torch = stage.torch
+        self.st, self.ends = stage, ends
+        self.x, self.ids, self.labels, self.g1 = x, ids, labels, g1
+        self.us_per_tick = us_per_tick
+        M = stage.cfg.M
+        self.y = [stage.new_act() for _ in range(M)]
+        self.gy = [stage.new_act() for _ in range(M)]
+        self.gx = [stage.new_act() for _ in range(M)]
+        self.x0 = [stage.new_act() for _ in range(M)]
+        self.z_frc = [stage.new_act() for _ in range(M)]
+        self.dx0 = [stage.new_act() for _ in range(M)]
+        self.loss = torch.zeros(M, dtype=torch.float32, device=stage.device)
+
+    def begin_iteration(self, zero_grads=True):
+        self.st.stage_begin_iteration()
+        self.ends.ends_begin_iteration()
+        if zero_grads:
+            self.st.zero_grads()
+            self.ends.zero_grads(self.st.stream_main)
+
+    def run(self, program):
+        st, en = self.st, self.ends
+        main = st.stream_main
+        for op, lane, k, arg in program:
+            if op == B.FWD:
+                st.stage_fwd(k, self.x[k], self.y[k])
+                en.ends_back_fwd(self.y[k], self.labels[k], self.loss[k:k + 1], main)
+            elif op == B.BWD:
+                en.ends_back_bwd(self.gy[k], main)
+                st.stage_bwd(k, self.gy[k], self.gx[k])
+            elif op == B.FRC:
+                s_frc = main if st.merged else st.stream_frc
+                en.ends_front_fwd(k, self.ids[k], self.x0[k], s_frc)
+                st.shadow_fwd_frc(k, self.x0[k], self.z_frc[k])
+            elif op == B.BRC:
+                st.shadow_bwd_brc(k, self.g1[k], self.dx0[k])
+                en.ends_front_bwd(k, self.dx0[k], main)
+            elif op == B.BUBBLE:
+                if self.us_per_tick > 0:
+                    st.stage_bubble(arg, self.us_per_tick)
+            elif op == B.JOIN:
+                st.stage_join()
+        return self
+
+    def sync(self):
+        self.st.stage_sync()
+
+
 def split_at_failure(program, k_fail):
     """The instructions that ran before the failure was noticed: up to and
     including FWD(k_fail) and its FRC."""

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared():
     names = []
-    for h in ("bamboo_stage.h", "bamboo_kernels.h"):
+    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"\b(?:int|int64_t|uint64_t|const char\s*\*)\s+(\w+)\s*\(", text)
@@ -158,3 +158,49 @@ def test_bad_configurations_are_rejected():
     # null stage handles are refused, not dereferenced
     assert B.lib.stage_fwd(None, 0, None, None) == B.E_ARG
     assert B.lib.failover_merge(None, 0, None, 0) == B.E_ARG
+
+
+def test_wrap_around_failover_program_equals_oracle_bit_exact():
+    """The last stage shadowing the first (Section 5.1): failover schedule and the victim's progress."""
+    n = 0
+    for P, M in itertools.product(range(2, 7), [1, 2, 3, 5, 8, 16]):
+        for tf, tb in ((1, 2), (2, 3)):
+            cfg = _cfg(P, P - 1, M, tick_F=tf, tick_B=tb)
+            cfg.wrap = 1
+            assert B.stage_program(cfg) == S.stage_program(P, P - 1, M, tick_F=tf, tick_B=tb)
+            for k_fail in range(M):
+                assert B.stage_wrap_victim_progress(cfg, k_fail) == S.wrap_victim_progress(P, M, k_fail, tf, tb)
+                assert B.stage_failover_program(cfg, k_fail) == S.wrap_failover_program(P, M, k_fail, tf, tb), (P, M, k_fail)
+                n += 1
+    assert n > 300
+    for bad in (dict(stage_id=1), dict(n_shadow=0), dict(rc_mode=2), dict(wrap=2)):
+        cfg = _cfg(4, 3, 4)
+        cfg.wrap = 1
+        for k, v in bad.items():
+            setattr(cfg, k, v)
+        with pytest.raises(B.BambooError) as e:
+            B.stage_query_sizes(cfg)
+        assert e.value.status == B.E_BADCFG, bad
+    with pytest.raises(B.BambooError) as e:
+        B.stage_wrap_victim_progress(_cfg(4, 3, 4), 0)          # not a wrap-around stage
+    assert e.value.status == B.E_STATE
+
+
+def test_ends_sizes():
+    sc = synth.StageConfig("w", 1, 1, 256, 2, 768, 160, 2, 2, 2, 4, 3, 4, 13)
+    cfg = B.make_cfg(sc, wrap=1)
+    V = 1000
+    sz = B.ends_query_sizes(cfg, V)
+    T, H, S_ = sc.tokens, sc.hidden, sc.seq
+    assert sz.front_params == synth.front_param_count(sc.arch, V, S_, H) == V * H + S_ * H
+    assert sz.back_params == synth.back_param_count(sc.arch, V, H) == 2 * H + H * V
+    assert sz.front_w == 2 * sz.front_params and sz.back_g == 4 * sz.back_params
+    assert sz.back_stash >= T * V * 2 + 2 * T * H * 2 and sz.front_stash >= sc.M * T * 4
+    enc = B.ends_query_sizes(B.make_cfg(sc.replace(arch=0), wrap=1), V)
+    assert enc.front_params == V * H + S_ * H + 2 * H and enc.back_params == H * V
+    for bad_v in (0, -8, 1001):
+        with pytest.raises(B.BambooError) as e:
+            B.ends_query_sizes(cfg, bad_v)
+        assert e.value.status == B.E_BADCFG
+    assert B.lib.ends_front_fwd(None, 0, None, None, None) == B.E_ARG
+    assert B.lib.ends_back_bwd(None, None, None) == B.E_ARG

@@ -227,3 +227,64 @@ def test_rc_variant_programs():
                 assert rest(f0) == rest(f1)
                 whole2 = S.prefix_until_failure(P, s, M, k_fail, rc=S.EFEB) + f2
                 assert [i[2] for i in whole2 if i[0] == S.BRC] == list(range(M))
+
+
+def test_wrap_around_victim_progress_hand_derived():
+    """The last stage shadows the first (Section 5.1).  Where the first stage stands when the last one
+    has finished FWD(k_fail), worked out by hand on the zero-latency timeline with forward 1 / backward 2
+    ticks: P=4: the last stage runs F(k) at 3+3k, so F(2) ends at 10; the first stage ran F0..F2 at 0,1,2,
+    F3 at 3 and waits for its first backward until 10.  P=2, k_fail=1: F1 of stage 1 ends at 5, stage 0
+    did F0, F1 and is inside B0 (4..6).  P=2, k_fail=3: F3 of stage 1 ends at 11; stage 0 finished B0 (6)
+    and B1 (9), B2 runs 10..12."""
+    assert S.wrap_victim_progress(4, 8, 2) == (4, 0)
+    assert S.wrap_victim_progress(2, 4, 1) == (2, 0)
+    assert S.wrap_victim_progress(2, 4, 3) == (4, 2)
+
+
+def test_wrap_around_failover_program_invariants():
+    for P, M in itertools.product(range(2, 7), [1, 2, 3, 5, 8]):
+        for k_fail in range(M):
+            for tf, tb in ((1, 2), (2, 3)):
+                prog = S.wrap_failover_program(P, M, k_fail, tf, tb)
+                nf, nb = S.wrap_victim_progress(P, M, k_fail, tf, tb)
+                assert nf > k_fail and nb <= k_fail           # the victim is ahead forwards, behind backwards
+                pos = {}
+                for i, (op, lane, k, arg) in enumerate(prog):
+                    assert lane == 0
+                    if op in (S.FWD, S.BWD, S.FRC, S.BRC):
+                        assert (op, k) not in pos
+                        pos[(op, k)] = i
+                assert prog[0] == (S.JOIN, 0, -1, k_fail) and prog[-3:] == [(S.JOIN, 0, -1, -1), (S.ALLREDUCE, 0, -1, 0), (S.APPLY, 0, -1, 0)]
+                # the shadow's own remaining work, the victim's forwards beyond k_fail, every victim backward
+                assert sorted(k for (op, k) in pos if op == S.FWD) == list(range(k_fail + 1, M))
+                assert sorted(k for (op, k) in pos if op == S.BWD) == list(range(k_fail, M))
+                assert sorted(k for (op, k) in pos if op == S.FRC) == list(range(k_fail + 1, M))
+                assert sorted(k for (op, k) in pos if op == S.BRC) == list(range(M))
+                # replayed backwards come first, in order
+                assert [ins[2] for ins in prog if ins[0] == S.BRC][:nb] == list(range(nb))
+                for k in range(M):
+                    if k > k_fail:
+                        assert pos[(S.FRC, k)] < pos[(S.BRC, k)] and pos[(S.FWD, k)] < pos[(S.BWD, k)]
+                        assert pos[(S.FRC, k)] < pos[(S.FWD, k)]      # the front of the pipeline runs first
+                    if k >= k_fail:
+                        assert pos[(S.BWD, k)] < pos[(S.BRC, k)]      # the gradient travels back to the front
+                # outputs of the victim's forwards go to the second stage only if it never got them
+                sends = sorted(ins[2] for ins in prog if ins[0] == S.SEND_ACT)
+                assert sends == ([k for k in range(k_fail + 1, M) if k >= nf] if P > 2 else [])
+                recv_g = sorted(ins[2] for ins in prog if ins[0] == S.RECV_GRAD)
+                assert recv_g == (list(range(M)) if P > 2 else [])
+                for ins in prog:
+                    if ins[0] in (S.SEND_ACT, S.RECV_GRAD):
+                        assert ins[3] == 1
+                    if ins[0] in (S.RECV_ACT, S.SEND_GRAD):
+                        assert ins[3] == P - 2 and P > 2
+                    if ins[0] in (S.FWD, S.BWD):
+                        assert ins[3] == ins[2] % S.own_slots(P, P - 1, M)
+                # own slot discipline: at most one forward in flight on the last stage
+                live = {k_fail}
+                for op, _, k, _ in prog:
+                    if op == S.FWD:
+                        assert not live
+                        live.add(k)
+                    elif op == S.BWD:
+                        live.remove(k)

@@ -136,3 +136,42 @@ def test_eager_brc_without_failure_reproduces_the_successors_gradients():
     assert not lazy.z_frc and not lazy.shadow_stash
     for k in range(5):
         assert np.array_equal(lazy.gx[k], sim.gx[k])
+
+
+def test_wrap_around_failover_rebuilds_the_first_stage_gradients():
+    """Section 5.1 for the last node: whatever micro-batch the failure falls on, running the wrap-around
+    failover schedule gives the last stage's own gradients (layers and head) of the failure-free program
+    and, in the replica, exactly what the first stage would have accumulated (layers and embedding)."""
+    from oracle import ends as E
+    rng = np.random.default_rng(21)
+    arch, H, F, n_h, Bsz, S_len, V, P, M = 1, 8, 16, 2, 2, 3, 13, 3, 4
+    T = Bsz * S_len
+    mk = lambda: L.unpack_layer(rng.normal(0, 0.3, L.layer_param_count(H, F)), H, F)
+    own, shadow = [mk()], [mk(), mk()]
+    front = E.unpack_front(rng.normal(0, 0.3, E.front_param_count(arch, V, S_len, H)), arch, V, S_len, H)
+    back = E.unpack_back(rng.normal(0, 0.3, E.back_param_count(arch, V, H)), arch, V, H)
+    x = {k: rng.normal(size=(T, H)) for k in range(M)}
+    g1 = {k: rng.normal(size=(T, H)) for k in range(M)}
+    ids = {k: rng.integers(0, V, T) for k in range(M)}
+    labels = {k: rng.integers(0, V, T) for k in range(M)}
+    args = (arch, own, back, shadow, front, Bsz, S_len, n_h, P, M, x, labels, ids, g1)
+    ref = St.WrapStageSim(*args).run(S.stage_program(P, P - 1, M))
+    Gv, Gfv, zv = St.wrap_first_stage_reference(arch, shadow, front, Bsz, S_len, n_h, M, ids, g1)
+    for k in range(M):
+        np.testing.assert_array_equal(ref.z_frc[k], zv[k])          # FRC is the first stage's forward
+    for k_fail in range(M):
+        sim = St.WrapStageSim(*args)
+        sim.run(S.prefix_until_failure(P, P - 1, M, k_fail))
+        sim.run(S.wrap_failover_program(P, M, k_fail))
+        assert not sim.own_stash and not sim.shadow_stash
+        for a, b in zip(sim.G_own, ref.G_own):
+            for n in L.PARAM_NAMES:
+                np.testing.assert_allclose(a[n], b[n], rtol=0, atol=1e-12)
+        for n in ref.G_back:
+            np.testing.assert_allclose(sim.G_back[n], ref.G_back[n], rtol=0, atol=1e-12)
+        for a, b in zip(sim.G_shadow, Gv):
+            for n in L.PARAM_NAMES:
+                np.testing.assert_allclose(a[n], b[n], rtol=0, atol=1e-12)
+        for n in Gfv:
+            np.testing.assert_allclose(sim.G_front[n], Gfv[n], rtol=0, atol=1e-12)
+        assert sim.loss == ref.loss
