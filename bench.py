@@ -350,6 +350,74 @@ def main():
             torch.cuda.empty_cache()
         out["swap_out"] = sw
 
+    # The wrap-around stage (Section 5.1): the last stage with the LM head and the loss, holding the replica of
+    # the first stage, whose FRC starts from token ids through the embedding.  Iteration time with and
+    # without FRC, and the ends on their own (event pairs around each call): the head is three GEMMs of
+    # 2 T H V flops (logits, weight gradient, input gradient) around the softmax cross-entropy, which reads
+    # the logits once forward and rewrites them as their gradient backward.
+    if not args.no_extra_modes and sc.n_shadow > 0 and sc.name in synth.VOCAB:
+        import numpy as np
+        from paper_2204_12013_amd.harness import WrapHarness
+        V = synth.VOCAB[sc.name]
+        scw = sc.replace(stage_id=sc.P - 1)
+        cfg_w = B.make_cfg(scw, wrap=1)
+        esz = B.ends_query_sizes(cfg_w, V)
+        front_w = (torch.randn(int(esz.front_params), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(act)
+        back_w = (torch.randn(int(esz.back_params), generator=gen, device=dev, dtype=torch.float32) * 0.02).to(act)
+        sw_ = B.Stage(cfg_w, st.own_w, st.shadow_w)
+        en = B.Ends(cfg_w, V, front_w, back_w)
+        rng = np.random.default_rng(sc.seed)
+        ids = [torch.from_numpy(synth.zipf_ids(rng, V, T)).to(dev) for _ in range(M)]
+        labels = [torch.from_numpy(synth.zipf_ids(rng, V, T)).to(dev) for _ in range(M)]
+        torch.cuda.synchronize()
+        hw = WrapHarness(sw_, en, x, ids, labels, gy)
+        pw_on = sw_.stage_schedule()
+        pw_off = [i for i in pw_on if i[0] != B.FRC]
+        res = {}
+        for label, prog_ in (("frc_on", pw_on), ("frc_off", pw_off)):
+            for n_ in (1, k_c):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n_):
+                    hw.begin_iteration(zero_grads=True)
+                    hw.run(prog_)
+                hw.sync()
+                torch.cuda.synchronize()
+                res[label] = (time.perf_counter() - t0) * 1e3 / n_
+        main = sw_.stream_main
+
+        def timed(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(main):
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        en.ends_begin_iteration()
+        t_bf = timed(lambda: en.ends_back_fwd(hw.y[0], labels[0], hw.loss[0:1], main))
+        t_bb = timed(lambda: (en.ends_back_fwd(hw.y[0], labels[0], hw.loss[0:1], main),
+                              en.ends_back_bwd(hw.gy[0], main))) - t_bf
+        t_ff = timed(lambda: en.ends_front_fwd(0, ids[0], hw.x0[0], main))
+        t_fb = timed(lambda: (en.ends_front_fwd(0, ids[0], hw.x0[0], main),
+                              en.ends_front_bwd(0, hw.dx0[0], main))) - t_ff
+        head_flops = 2.0 * T * H * V
+        out["wrap_around"] = {
+            "vocab": V, "stage_id": sc.P - 1, "ms_per_step_frc_on": res["frc_on"], "ms_per_step_frc_off": res["frc_off"],
+            "frc_overhead_pct_no_bubbles": 100.0 * (res["frc_on"] - res["frc_off"]) / res["frc_off"],
+            "samples_per_s_frc_on": M * sc.micro_batch / (res["frc_on"] * 1e-3),
+            "head_forward_ms": t_bf, "head_backward_ms": t_bb,
+            "head_TFLOP/s": {"forward (1 GEMM + loss)": head_flops / (t_bf * 1e-3) / 1e12,
+                             "backward (2 GEMMs + loss gradient)": 2 * head_flops / (t_bb * 1e-3) / 1e12},
+            "embedding_forward_ms": t_ff, "embedding_backward_ms": t_fb}
+        sw_.stage_destroy()
+        en.ends_destroy()
+        del sw_, en, hw, front_w, back_w
+        torch.cuda.empty_cache()
+
     # Context for the roofline fraction: the stage's four forward GEMM shapes run stand-alone on operands
     # that are not cache-resident (a ring of buffer sets larger than the Infinity Cache, as inside an
     # iteration), this library's kernel beside the vendor GEMM that torch.matmul dispatches to.  The

@@ -855,6 +855,7 @@ hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {
     return hipErrorNotSupported;
   if (a_k && !b_k) {           // forward
     switch (d.epi) {
+      case EPI_STORE: return launch_form<true, false, EPI_STORE>(s, d);   // the LM head has no bias
       case EPI_BIAS: return launch_form<true, false, EPI_BIAS>(s, d);
       case EPI_BIAS_RES: return launch_form<true, false, EPI_BIAS_RES>(s, d);
       case EPI_BIAS_GELU: return launch_form<true, false, EPI_BIAS_GELU>(s, d);

@@ -194,3 +194,42 @@ def test_wrap_misuse_is_rejected(B):
     st.stage_sync()
     st.stage_destroy()
     en.ends_destroy()
+
+
+def test_ends_at_the_bert_large_size(B):
+    """The model's ends at the size bench.py times them (4096 tokens, hidden 1024, vocabulary 30528,
+    Zipf-distributed ids): loss, head gradients, input gradient and embedding gradients against the oracle."""
+    sc = synth.CONFIGS["bert_large_stage"].replace(stage_id=3, M=1)
+    V = synth.VOCAB["bert_large_stage"]
+    cfg = B.make_cfg(sc, wrap=1)
+    ein = synth.make_ends_inputs(sc, V)
+    rng = np.random.default_rng(9)
+    y = synth.round_to_storage(rng.standard_normal((sc.tokens, sc.hidden), dtype=np.float32), sc.dtype)
+    dx0 = synth.round_to_storage(rng.standard_normal((sc.tokens, sc.hidden), dtype=np.float32) / 64, sc.dtype)
+    en = B.Ends(cfg, V, B.to_device(ein["front_w"], sc.dtype), B.to_device(ein["back_w"], sc.dtype))
+    s = torch.cuda.current_stream()
+    d_y, d_dx0 = B.to_device(y, sc.dtype), B.to_device(dx0, sc.dtype)
+    ids, labels = _ids(ein["ids"][0]), _ids(ein["labels"][0])
+    loss = torch.zeros(1, dtype=torch.float32, device=DEV)
+    gy = torch.empty_like(d_y)
+    x0 = torch.empty_like(d_y)
+    en.ends_begin_iteration()
+    en.ends_back_fwd(d_y, labels, loss, s)
+    en.ends_back_bwd(gy, s)
+    en.ends_front_fwd(0, ids, x0, s)
+    en.ends_front_bwd(0, d_dx0, s)
+    torch.cuda.synchronize()
+    tol = TOL[sc.dtype]
+    back = E.unpack_back(ein["back_w"], sc.arch, V, sc.hidden)
+    want_loss, _, cache = E.back_fwd(sc.arch, back, y.astype(np.float64), ein["labels"][0].astype(np.int64))
+    want_gy, want_gb = E.back_bwd(sc.arch, back, cache)
+    assert abs(loss.item() - want_loss) <= tol * want_loss
+    assert rel_l2(B.to_host(gy), want_gy) <= tol
+    _check_named(en.back_g, want_gb, lambda a: E.unpack_back(a, sc.arch, V, sc.hidden), tol, "back")
+    del cache, want_gb
+    front = E.unpack_front(ein["front_w"], sc.arch, V, sc.seq, sc.hidden)
+    want_x0, cf = E.front_fwd(sc.arch, front, ein["ids"][0].astype(np.int64), sc.seq)
+    assert rel_l2(B.to_host(x0), want_x0) <= tol
+    want_gf = E.front_bwd(sc.arch, front, cf, dx0.astype(np.float64))
+    _check_named(en.front_g, want_gf, lambda a: E.unpack_front(a, sc.arch, V, sc.seq, sc.hidden), tol, "front")
+    en.ends_destroy()
