@@ -42,6 +42,14 @@ int bk_linear_bwd_input(int dtype, int impl, int T, int K, int N, const void* dY
 int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X, const void* dY, float* dW,
                          float* db, float* partial, void* stream);
 
+/* n (1..4) independent weight gradients in one go: dW[i][K[i],N[i]] (fp32) += X[i][T[i],K[i]]^T dY[i][T[i],N[i]].
+ * T, K, N: host int arrays; X, dY, dW: host arrays of device pointers.  Where the MFMA kernel covers all
+ * of them with one tile shape (bf16, T a multiple of 64 and >= 192, K and N multiples of 8) they run as
+ * ONE launch whose workgroups are dealt over the problems, so that problems that do not fill the chip on
+ * their own share its rounds; otherwise one launch each.  The results do not depend on which. */
+int bk_linear_bwd_weight_group(int dtype, int n, const int* T, const int* K, const int* N, const void* const* X,
+                               const void* const* dY, float* const* dW, void* stream);
+
 /* out[N] (fp32) += sum over tokens of A[T,N]; partial: fp32 scratch of
  * bk_colsum_scratch_floats(N) floats.  Fixed summation order. */
 int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream);

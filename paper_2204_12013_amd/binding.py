@@ -98,6 +98,7 @@ _SIGS = {
     "bk_linear_fwd": (C.c_int, [C.c_int] * 5 + [_vp] * 7),
     "bk_linear_bwd_input": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
     "bk_linear_bwd_weight": (C.c_int, [C.c_int] * 5 + [_vp] * 6),
+    "bk_linear_bwd_weight_group": (C.c_int, [C.c_int, C.c_int] + [C.POINTER(C.c_int)] * 3 + [C.POINTER(_vp)] * 3 + [_vp]),
     "bk_colsum_acc": (C.c_int, [C.c_int] * 3 + [_vp] * 4),
     "bk_colsum_scratch_floats": (C.c_uint64, [C.c_int]),
     "bk_attention_fwd": (C.c_int, [C.c_int] * 7 + [_vp] * 4),
@@ -384,6 +385,16 @@ def bk_linear_bwd_weight(X, dY, dW, db=None, impl=0, stream=None):
     _check(lib.bk_linear_bwd_weight(_dt(X), impl, T, K, N, _ptr(X), _ptr(dY), _ptr(dW), _ptr(db), _ptr(partial),
                                     _stream(stream)), "bk_linear_bwd_weight")
     return partial
+
+
+def bk_linear_bwd_weight_group(Xs, dYs, dWs, stream=None):
+    """dWs[i] += Xs[i]^T dYs[i] for up to four independent problems, as one launch where possible."""
+    n = len(Xs)
+    ints = lambda v: (C.c_int * n)(*v)
+    ptrs = lambda ts: (_vp * n)(*[t.data_ptr() for t in ts])
+    _check(lib.bk_linear_bwd_weight_group(_dt(Xs[0]), n, ints([x.shape[0] for x in Xs]), ints([x.shape[1] for x in Xs]),
+                                          ints([y.shape[1] for y in dYs]), ptrs(Xs), ptrs(dYs), ptrs(dWs),
+                                          _stream(stream)), "bk_linear_bwd_weight_group")
 
 
 def bk_colsum_acc(A, out, stream=None):

@@ -69,12 +69,24 @@ struct GemmDesc {
   float* colsum_partial;
 };
 
+// up to MAX independent GEMMs for one launch; first[p] = index of problem p's first workgroup
+struct GemmGroup {
+  static constexpr int MAX = 4;
+  GemmDesc d[MAX];
+  int first[MAX + 1];
+  int n;
+};
+
 // dtype: 0 fp32, 1 bf16 (enum bamboo_dtype).  All launchers return hipError_t
 // from the launch and never synchronise.
 hipError_t launch_gemm_simple(hipStream_t s, int dtype, const GemmDesc& d);
 // bf16 MFMA path; returns hipErrorNotSupported when the shape is not covered.
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d);
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
+// n independent weight-gradient GEMMs (EPI_ACC_F32): one launch where the MFMA kernel covers them all,
+// otherwise one launch each
+hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n);
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n);
 // output tile of the MFMA kernel: 10*WM + WN forces (64*WM) x (64*WN), 0 = automatic; returns the previous code
 bool gemm_tile_code_valid(int code);
 int set_gemm_tile(int code);

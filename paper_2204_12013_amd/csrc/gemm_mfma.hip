@@ -21,6 +21,8 @@
 
 #include <type_traits>
 
+#include <string.h>
+
 #include "common.h"
 
 namespace bamboo {
@@ -318,9 +320,8 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
 // each with its own L2.  Give every XCD a contiguous range of tiles, and inside
 // the range walk down GROUP rows of tiles before moving to the next column, so
 // that the tiles an XCD works on at one time share operand slices in its L2.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int* tm, int* tn) {
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
   const int nb = tiles_m * tiles_n;
-  int pid = blockIdx.x;
   const int per = nb / 8;
   if (pid < per * 8) pid = (pid % 8) * per + pid / 8;
   constexpr int GROUP = 8;
@@ -341,7 +342,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;       // 2 x 2 wavefronts
   int tile_m, tile_n;
-  tile_of_block((d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
+  tile_of_block(blockIdx.x, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bf16_t* A = (const bf16_t*)d.A;
   const bf16_t* B = (const bf16_t*)d.B;
@@ -603,8 +604,9 @@ __device__ __forceinline__ void wait_loads_and_lds() {
 
 // Slices are kept in NS LDS buffers used round-robin; the global -> LDS loads of slice kt + NS - 1 ... are
 // in flight while slice kt feeds the MFMAs, i.e. a load has NS - 1 slices of MFMA time to land.
-template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS, int MINB>
-__global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
+// pid: index of this workgroup's tile among the tiles of problem d
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
+__device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
   typedef SmemPl<WM, WN, NS, EPI == EPI_BIAS_GELU> SM;
   typedef PlLoop<WM, WN, A_K, B_K> Loop;
   constexpr int BM = SM::BM, BN = SM::BN, NL = Loop::NL;
@@ -615,7 +617,7 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of_block((d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
+  tile_of_block(pid, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const long lda = A_K ? d.a_sm : d.a_sk;
   const long ldb = B_K ? d.b_sn : d.b_sk;
@@ -714,6 +716,26 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
   BAMBOO_SCHED_FENCE();
   if (!EARLY) ops.issue(d, m0, n0, 0);
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops, L.lds0 + SM::TABLE_OFF);
+}
+
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS, int MINB>
+__global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
+  gemm_pl_body<WM, WN, A_K, B_K, EPI, NS>(d, blockIdx.x);
+}
+
+// Several weight-gradient problems in one launch: workgroup b works on problem p where
+// first[p] <= b < first[p+1].  The problems of a layer's backward are independent of each other and
+// most of them do not fill a whole number of rounds of the 256 CUs on their own (1024 x 1024 outputs
+// are 64 tiles of 128 x 128); launched together their tiles pack, and a CU goes from one problem's
+// tile to the next one's without the chip draining in between.
+template <int WM, int WN, int NS, int MINB>
+__global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_group_kernel(GemmGroup g) {
+  const int b = blockIdx.x;
+  int p = 0;
+#pragma unroll
+  for (int q = 1; q < GemmGroup::MAX; ++q)
+    if (q < g.n && b >= g.first[q]) p = q;
+  gemm_pl_body<WM, WN, false, false, EPI_ACC_F32, NS>(g.d[p], b - g.first[p]);
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
@@ -840,6 +862,72 @@ static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
     case 11: return launch_cfg<1, 1, A_K, B_K, EPI>(s, d, ns);
     default: return hipErrorInvalidValue;
   }
+}
+
+template <int WM, int WN, int NS>
+static hipError_t launch_group_cfg(hipStream_t s, GemmGroup& g) {
+  typedef SmemPl<WM, WN, NS, false> SM;
+  static bool attr_set = false;
+  auto kern = gemm_mfma_pl_group_kernel<WM, WN, NS, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  int total = 0;
+  for (int i = 0; i < g.n; ++i) {
+    g.first[i] = total;
+    total += ((g.d[i].M + 64 * WM - 1) / (64 * WM)) * ((g.d[i].N + 64 * WN - 1) / (64 * WN));
+  }
+  for (int i = g.n; i <= GemmGroup::MAX; ++i) g.first[i] = total;
+  hipLaunchKernelGGL(kern, dim3(total), dim3(256), SM::BYTES, s, g);
+  return hipGetLastError();
+}
+
+static bool wgrad_form_ok(const GemmDesc& d) {
+  if (d.epi != EPI_ACC_F32 || d.a_sk == 1 || d.b_sk == 1 || d.a_sm != 1 || d.b_sn != 1) return false;
+  if (d.M % 8 || d.N % 8 || d.K % BK || d.a_sk % 8 || d.b_sk % 8) return false;
+  if (((uintptr_t)d.A | (uintptr_t)d.B | (uintptr_t)d.C) & 15) return false;
+  return d.M > 0 && d.N > 0;
+}
+
+// n <= GemmGroup::MAX weight-gradient GEMMs (dW += X^T dY) as one launch where the pipelined MFMA kernel
+// covers all of them with one tile shape; hipErrorNotSupported otherwise (the caller launches them singly).
+hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n) {
+  if (n < 1 || n > GemmGroup::MAX) return hipErrorNotSupported;
+  GemmGroup g;
+  memset(&g, 0, sizeof(g));
+  g.n = n;
+  int nk_min = 1 << 30;
+  for (int i = 0; i < n; ++i) {
+    if (!wgrad_form_ok(d[i])) return hipErrorNotSupported;
+    g.d[i] = d[i];
+    nk_min = d[i].K / BK < nk_min ? d[i].K / BK : nk_min;
+  }
+  if (nk_min < 3) return hipErrorNotSupported;
+  // 128 x 128 tiles with a ring of three, or 256 x 256 tiles with a ring of two: the cheaper by the cost
+  // model of the single launches, with all tiles of the group sharing the rounds
+  float cost[2] = {0.f, 0.f};
+  const int codes[2] = {22, 44}, nss[2] = {3, 2};
+  for (int c = 0; c < 2; ++c) {
+    const TileCost* t = nullptr;
+    for (const TileCost& e : kCostAcc)
+      if (e.code == codes[c] && e.ns == nss[c]) t = &e;
+    const int w = codes[c] / 10;
+    long tiles = 0;
+    double slices = 0;
+    for (int i = 0; i < n; ++i) {
+      const long ti = (long)((d[i].M + 64 * w - 1) / (64 * w)) * ((d[i].N + 64 * w - 1) / (64 * w));
+      tiles += ti;
+      slices += (double)ti * (d[i].K / BK);
+    }
+    const long rounds = (tiles + 255) / 256;
+    cost[c] = rounds * (t->a + t->b * (float)(slices / tiles)) + t->c;
+  }
+  int pick = cost[1] < cost[0] ? 44 : 22;
+  if (g_forced_tile == 22 || g_forced_tile == 44) pick = g_forced_tile;
+  else if (g_forced_tile || g_forced_stages) return hipErrorNotSupported;   // a forced shape this launch does not offer
+  return pick == 44 ? launch_group_cfg<4, 4, 2>(s, g) : launch_group_cfg<2, 2, 3>(s, g);
 }
 
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {

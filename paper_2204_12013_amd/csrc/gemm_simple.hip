@@ -109,4 +109,20 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d) {
   return launch_gemm_simple(s, dtype, d);
 }
 
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n) {
+  if (dtype == 1 && n > 1) {
+    bool plain = true;
+    for (int i = 0; i < n; ++i) plain = plain && d[i].colsum_out == nullptr;
+    if (plain) {
+      const hipError_t e = launch_gemm_group_mfma(s, d, n);
+      if (e != hipErrorNotSupported) return e;
+    }
+  }
+  for (int i = 0; i < n; ++i) {
+    const hipError_t e = launch_gemm(s, dtype, d[i]);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 }  // namespace bamboo

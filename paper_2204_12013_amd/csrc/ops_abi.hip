@@ -72,6 +72,20 @@ int bk_linear_bwd_weight(int dtype, int impl, int T, int K, int N, const void* X
   return run_gemm(dtype, impl, d, stream);
 }
 
+int bk_linear_bwd_weight_group(int dtype, int n, const int* T, const int* K, const int* N, const void* const* X,
+                               const void* const* dY, float* const* dW, void* stream) {
+  if ((dtype != 0 && dtype != 1) || n < 1 || n > GemmGroup::MAX || !T || !K || !N || !X || !dY || !dW) return BAMBOO_E_ARG;
+  GemmDesc d[GemmGroup::MAX];
+  memset(d, 0, sizeof(d));
+  for (int i = 0; i < n; ++i) {
+    if (T[i] <= 0 || K[i] <= 0 || N[i] <= 0 || !X[i] || !dY[i] || !dW[i]) return BAMBOO_E_ARG;
+    d[i].A = X[i]; d[i].B = dY[i]; d[i].C = dW[i]; d[i].M = K[i]; d[i].N = N[i]; d[i].K = T[i];
+    d[i].a_sm = 1; d[i].a_sk = K[i]; d[i].b_sk = N[i]; d[i].b_sn = 1; d[i].epi = EPI_ACC_F32;
+  }
+  (void)hipGetLastError();
+  return finish(launch_gemm_group((hipStream_t)stream, dtype, d, n));
+}
+
 int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream) {
   if ((dtype != 0 && dtype != 1) || T <= 0 || N <= 0 || N % 2 || !A || !out || !partial) return BAMBOO_E_ARG;
   (void)hipGetLastError();

@@ -88,7 +88,7 @@ RecordLayout record_layout(const bamboo_cfg_t& c) {
 // Scratch of one lane.  Lane 1 only ever runs forwards: it needs only out (where an
 // output the caller does not want is written).
 struct LaneScratch {
-  uint64_t out, dh, d1, d2, dctx, ping, pong, dqkv, delta, bytes;
+  uint64_t out, dh, d1, d2, d3, dctx, ping, pong, dqkv, delta, bytes;
   // partial rows of one layer's parameter-gradient reductions (summed by one launch at the layer's end):
   // LayerNorm 1 and 2 (gain, shift, column sums of the output), and the column sums of dh, dqkv, df
   uint64_t p_ln[2][3], p_dh, p_dqkv, p_df;
@@ -104,6 +104,7 @@ LaneScratch lane_scratch(const bamboo_cfg_t& c, bool backward) {
     w.dh = o; o = align_up(o + T * F * es);
     w.d1 = o; o = align_up(o + T * H * es);
     w.d2 = o; o = align_up(o + T * H * es);
+    w.d3 = o; o = align_up(o + T * H * es);
     w.dctx = o; o = align_up(o + T * H * es);
     w.ping = o; o = align_up(o + T * H * es);
     w.pong = o; o = align_up(o + T * H * es);
@@ -240,6 +241,14 @@ int p_gemm(bamboo_stage* st, hipStream_t s, const GemmDesc& d) {
   const int cls = d.epi == EPI_ACC_F32 ? K_GEMM_WGRAD : (d.b_sn == 1 ? K_GEMM_FWD : K_GEMM_DGRAD);
   ProfScope ps(st, cls, s, gemm_flops(d));
   HIPCHK(launch_gemm(s, st->cfg.dtype, d));
+  return BAMBOO_OK;
+}
+// the weight-gradient GEMMs of one layer, as one launch where possible
+int p_gemm_group(bamboo_stage* st, hipStream_t s, const GemmDesc* d, int n) {
+  double flops = 0;
+  for (int i = 0; i < n; ++i) flops += gemm_flops(d[i]);
+  ProfScope p(st, BAMBOO_K_GEMM_WGRAD, s, flops);
+  HIPCHK(launch_gemm_group(s, st->cfg.dtype, d, n));
   return BAMBOO_OK;
 }
 double attn_fwd_flops(const AttnDesc& a) {
@@ -392,6 +401,7 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
   void* dh = ws + w.dh;
   void* d1 = ws + w.d1;
   void* d2 = ws + w.d2;
+  void* d3 = ws + w.d3;
   void* dctx = ws + w.dctx;
   void* dqkv = ws + w.dqkv;
   const RecordLayout& r = st->rl;
@@ -418,9 +428,9 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     GemmDesc d;
     const void* df;     // gradient at the FFN output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
-      BBCHK(p_ln_bwd(st, s, ws, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d1,
+      BBCHK(p_ln_bwd(st, s, ws, T, H, dy, rec + r.r2, (const float*)(rec + r.ln2), P(st->po.g2), nullptr, d3,
                      G + st->po.g2, G + st->po.be2, G + st->po.b2, w.p_ln[1], &batch));
-      df = d1;
+      df = d3;
     } else {
       df = dy;
       BBCHK(p_colsum(st, s, ws, T, H, df, G + st->po.b2, w.p_df, &batch));
@@ -429,14 +439,18 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_MUL);   // through the activation: times GELU'(h)
     d.aux_in = rec + r.dg;
     BBCHK(p_gemm(st, s, d));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.g, df, G + st->po.W2, T, F, H)));
+    // The four weight gradients of the layer wait until its end: their operands (df, dh, da, dqkv and the
+    // record) all live that long, nothing in the layer depends on them, and launched together their tiles
+    // share the rounds of the chip.
+    GemmDesc wgrad[4];
+    wgrad[0] = gemm_tn(rec + r.g, df, G + st->po.W2, T, F, H);
     // h = fin W1 + b1
     BBCHK(p_colsum(st, s, ws, T, F, dh, G + st->po.b1, w.p_dh, &batch));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F)));
+    wgrad[1] = gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F);
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
-      d.res = d1;
+      d.res = df;
       BBCHK(p_gemm(st, s, d));
       BBCHK(p_ln_bwd(st, s, ws, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
                      G + st->po.g1, G + st->po.be1, G + st->po.bo, w.p_ln[0], &batch));
@@ -448,12 +462,12 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
       da = d2;
     }
     // a = ctx Wo + bo
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H)));
+    wgrad[2] = gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H);
     BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
     BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
     BBCHK(p_colsum(st, s, ws, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
-    BBCHK(p_gemm(st, s, gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H)));
+    wgrad[3] = gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H);
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
       d.res = da;
@@ -463,6 +477,7 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
       BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
                      G + st->po.g1, G + st->po.be1, nullptr, w.p_ln[0], &batch));   // + residual branch of x1 = x + a
     }
+    BBCHK(p_gemm_group(st, s, wgrad, 4));
     BBCHK(p_grad_reduce(st, s, batch));
     dy = dx;
   }

@@ -103,6 +103,39 @@ def test_mfma_tiles_and_pipeline_depths_agree_bitwise(B, T, N, K):
         B.bk_gemm_stages(0)
 
 
+@pytest.mark.parametrize("shapes", [
+    # (T, K, N) per problem: ragged edges, different contraction lengths, one to four problems
+    [(512, 136, 264), (192, 128, 128)],
+    [(448, 1024, 392), (448, 64, 72), (320, 520, 8), (1024, 256, 256)],
+    [(4096, 1024, 1024), (4096, 1024, 3072)],
+    [(256, 200, 96)],
+    [(100, 64, 64), (256, 64, 64)],            # a contraction length the grouped kernel does not take
+])
+def test_grouped_weight_gradients_equal_the_single_launches_bitwise(B, shapes):
+    rng = np.random.default_rng(len(shapes) * 7 + shapes[0][0])
+    Xs, dYs, inits = [], [], []
+    for T, K, N in shapes:
+        Xs.append(_dev(B, _mk(rng, (T, K), 1), 1))
+        dYs.append(_dev(B, _mk(rng, (T, N), 1), 1))
+        inits.append(torch.from_numpy(rng.normal(0, 1, (K, N)).astype(np.float32)).to(DEV))
+    single = [w.clone() for w in inits]
+    for X, dY, dW in zip(Xs, dYs, single):
+        B.bk_linear_bwd_weight(X, dY, dW)
+    try:
+        for tile in (0, 22, 44):
+            B.bk_gemm_tile(tile)
+            grouped = [w.clone() for w in inits]
+            B.bk_linear_bwd_weight_group(Xs, dYs, grouped)
+            torch.cuda.synchronize()
+            for a, b in zip(grouped, single):
+                assert torch.equal(a, b), tile
+    finally:
+        B.bk_gemm_tile(0)
+    T, K, N = shapes[0]
+    want = inits[0].cpu().numpy().astype(np.float64) + B.to_host(Xs[0]).T @ B.to_host(dYs[0])
+    assert rel_l2(single[0].cpu().numpy(), want) <= 1e-5
+
+
 def test_mfma_kernel_refuses_what_it_does_not_cover(B):
     X, W, b = _empty((12, 16), 1), _empty((16, 24), 1), _empty((24,), 1)
     with pytest.raises(B.BambooError) as e:
