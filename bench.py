@@ -48,8 +48,8 @@ def _profiled_traffic(workload):
 
 def _cpu_baseline(sc, seconds_budget=20.0):
     """The oracle as it stands, timed on the host: layers of this workload forward + backward on one
-    micro-batch (as many of the stage's layers as fit the time budget, at least one), extrapolated
-    linearly to an iteration (flops are linear in layers x micro-batches)."""
+    micro-batch (as many layer passes as fit the time budget, at least one, at most four times the
+    stage's layer count), extrapolated linearly to an iteration (flops are linear in layers x micro-batches)."""
     import numpy as np
     from oracle import layer as L
     from paper_2204_12013_amd import synth
@@ -60,7 +60,8 @@ def _cpu_baseline(sc, seconds_budget=20.0):
     g = inp["gz"][0].astype(np.float64)
     t_f = t_b = 0.0
     n = 0
-    while n < sc.n_own and (n == 0 or (t_f + t_b) * (n + 1) / n <= seconds_budget):
+    # layers beyond the stage's own count are further samples of the same measurement (same shapes)
+    while n < 4 * sc.n_own and (n == 0 or (t_f + t_b) * (n + 1) / n <= seconds_budget):
         t0 = time.perf_counter()
         x, cache = L.layer_fwd(sc.arch, p, x, sc.micro_batch, sc.seq, sc.heads)
         t1 = time.perf_counter()
