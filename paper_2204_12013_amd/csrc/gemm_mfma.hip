@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
   constexpr int BM = SM::BM, BN = SM::BN;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* smem = (bf16_t*)smem_raw;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;       // 2 x 2 wavefronts
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
@@ -470,22 +470,40 @@ struct PlK {
     return *(lds_bf16x8_ptr)(lds_base + t[ks] + blk * 32 * BK * 2);
   }
 };
-// Row-contiguous operand, 64 k-rows x ROWS per slice; chunk c of k-row k at position c ^ swz(k).
-// A transposing 8-byte read is served for 32 lanes per cycle, which address 4 consecutive k-rows x
-// 64 bytes: swz moves those four 64-byte pieces to distinct quarters of the 256-byte bank line.
+// Row-contiguous operand, 64 k-rows x ROWS per slice; the 16-byte chunk g of k-row k sits at chunk position
+// place(g, k) of that row.  A transposing 8-byte read is served for 32 lanes per cycle, which address 4
+// consecutive k-rows x 64 bytes: the placement moves those four 64-byte pieces to distinct quarters of the
+// 256-byte bank line.  Rows of 128 or 256 bytes and more: XOR with a k-dependent chunk offset.  Rows of 384
+// bytes (ROWS = 192) already alternate between the two halves of the bank line from one k-row to the
+// next; rotating every second pair of k-rows by 64 bytes (modulo the row) separates the rest.
 template <int ROWS>
 struct PlMN {
   static constexpr int NLOAD = ROWS / 32;
   static constexpr int BYTES = ROWS * BK * 2;
   static constexpr int CPR = ROWS / 8;
-  __device__ static __forceinline__ int swz(int k) { return ROWS >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1); }
+  static constexpr bool ROTATE = (CPR & (CPR - 1)) != 0;
+  static_assert(!ROTATE || ROWS == 192, "placement derived for rows of 384 bytes only");
+  __device__ static __forceinline__ int swz(int k) {
+    return ROTATE ? 4 * ((k >> 1) & 1) : (ROWS >= 128 ? 4 * (k & 3) : 4 * ((k >> 1) & 1));
+  }
+  // position of chunk g in k-row k, and the chunk found at position p
+  __device__ static __forceinline__ int place(int g, int k) {
+    if (!ROTATE) return g ^ swz(k);
+    const int p = g + swz(k);
+    return p >= CPR ? p - CPR : p;
+  }
+  __device__ static __forceinline__ int chunk_at(int p, int k) {
+    if (!ROTATE) return p ^ swz(k);
+    const int g = p - swz(k);
+    return g < 0 ? g + CPR : g;
+  }
   __device__ static __forceinline__ void load_offsets(unsigned (&off)[NLOAD], long ld, int row0, int row_lim) {
     const int tid = threadIdx.x;
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
       const int c = i * 256 + tid;
       const int kr = c / CPR, p = c % CPR;
-      const int col = min(row0 + ((p ^ swz(kr)) << 3), row_lim - 8) - row0;
+      const int col = min(row0 + (chunk_at(p, kr) << 3), row_lim - 8) - row0;
       off[i] = (unsigned)((long)kr * ld * 2 + col * 2);
     }
   }
@@ -500,7 +518,7 @@ struct PlMN {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int col = wave_row0 + b * 32 + ((l >> 4) & 1) * 16 + (i & 3) * 4;
-      t[b] = (unsigned)(k * ROWS * 2 + (((col >> 3) ^ swz(k)) << 4) + (col & 7) * 2);
+      t[b] = (unsigned)(k * ROWS * 2 + (place(col >> 3, k) << 4) + (col & 7) * 2);
     }
   }
   __device__ static __forceinline__ bf16x8 frag(const unsigned (&t)[4], unsigned lds_base, int blk, int ks) {
@@ -789,7 +807,9 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d, int ns) {
 }
 
 static int g_forced_tile = 0;
-bool gemm_tile_code_valid(int code) { return code == 0 || code == 44 || code == 42 || code == 24 || code == 22 || code == 11; }
+bool gemm_tile_code_valid(int code) {
+  return code == 0 || code == 44 || code == 43 || code == 42 || code == 24 || code == 22 || code == 11;
+}
 int set_gemm_tile(int code) {
   const int prev = g_forced_tile;
   g_forced_tile = code;
@@ -809,22 +829,27 @@ struct TileCost { int code, ns; float a, b, c; };
 static const TileCost kCostStore[] = {     // bf16 output (forward and input-gradient forms)
     {11, 2, 1.96f, 0.377f, 3.94f}, {11, 4, 1.48f, 0.396f, 5.05f}, {22, 2, 5.04f, 0.949f, 0.35f},
     {22, 3, 4.52f, 0.545f, 1.60f}, {24, 2, 4.93f, 1.068f, 5.59f}, {24, 3, 7.76f, 0.816f, 1.45f},
-    {42, 2, 1.85f, 1.107f, 8.18f}, {42, 3, 5.44f, 0.874f, 2.50f}, {44, 2, 14.98f, 1.281f, 0.58f}};
+    {42, 2, 1.85f, 1.107f, 8.18f}, {42, 3, 5.44f, 0.874f, 2.50f}, {44, 2, 14.98f, 1.281f, 0.58f},
+    // 256 x 192 (offered for the bias-only forward form: N = 3 H of the QKV projection is 16 x 192 when
+    // H = 1024, i.e. with 4096 tokens exactly 256 tiles); coefficients scaled from the 256 x 256 tile's
+    {43, 2, 11.6f, 0.98f, 0.58f}};
 static const TileCost kCostAcc[] = {       // fp32 read-modify-write output (weight-gradient form)
     {11, 2, 0.f, 0.487f, 1.98f}, {11, 4, 0.f, 0.504f, 0.f}, {22, 2, 0.f, 0.983f, 0.f},
     {22, 3, 0.f, 0.616f, 2.88f}, {24, 2, 0.f, 1.216f, 6.12f}, {24, 3, 0.f, 1.072f, 1.03f},
     {42, 2, 0.f, 1.102f, 11.56f}, {42, 3, 0.f, 0.997f, 4.55f}, {44, 2, 0.f, 1.737f, 0.f}};
 
-static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* code, int* ns) {
+static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* code, int* ns, bool offer_43 = false) {
   const int nk = d.K / BK;
   const TileCost* tab = acc_form ? kCostAcc : kCostStore;
+  const int ntab = acc_form ? (int)(sizeof(kCostAcc) / sizeof(kCostAcc[0])) : (int)(sizeof(kCostStore) / sizeof(kCostStore[0]));
   float best = 0.f;
   bool found = false;
   *code = 22;
   *ns = 2;
-  for (int i = 0; i < 9; ++i) {
+  for (int i = 0; i < ntab; ++i) {
     const TileCost& t = tab[i];
     if (t.ns > nk && t.ns > 2) continue;
+    if (t.code == 43 && !offer_43) continue;
     const int wm = t.code / 10, wn = t.code % 10;
     const long tiles = (long)((d.M + 64 * wm - 1) / (64 * wm)) * ((d.N + 64 * wn - 1) / (64 * wn));
     const long stage = (long)(wm + wn) * 64 * BK * 2, epi = 4L * 32 * (32 * wn + 4) * 4;
@@ -845,7 +870,10 @@ static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* c
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
   int pick, ns;
-  choose_tile(d, EPI == EPI_ACC_F32, EPI == EPI_BIAS_GELU ? kGeluBytes : 0, &pick, &ns);
+  // the 256 x 192 tile exists in the pipelined kernel only (K a multiple of the slice depth)
+  constexpr bool HAS_43 = A_K && !B_K && EPI == EPI_BIAS;
+  choose_tile(d, EPI == EPI_ACC_F32, EPI == EPI_BIAS_GELU ? kGeluBytes : 0, &pick, &ns,
+              HAS_43 && d.K % BK == 0 && d.K >= 2 * BK && !g_forced_stages);
   if (EPI == EPI_BIAS_GELU) {
     const hipError_t e = ensure_gelu_table(s);
     if (e != hipSuccess) return e;
@@ -853,6 +881,15 @@ static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
   if (g_forced_tile) {
     pick = g_forced_tile;
     ns = 2;
+    // 256 x 192 where this form and shape have it, the next larger tile otherwise
+    if (pick == 43 && !(HAS_43 && d.K % BK == 0 && d.K >= 2 * BK)) pick = 44;
+  }
+  if constexpr (HAS_43) {
+    if (pick == 43) {
+      if (d.K % BK != 0 || d.K < 2 * BK) return hipErrorNotSupported;
+      const int tiles = ((d.M + 255) / 256) * ((d.N + 191) / 192);
+      return launch_pl<4, 3, A_K, B_K, EPI, 2>(s, d, tiles);
+    }
   }
   switch (pick) {
     case 44: return launch_cfg<4, 4, A_K, B_K, EPI>(s, d, ns);

@@ -335,7 +335,6 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
   const uint64_t es = esize(st);
   hipStream_t s = st->lane[lane_id];
   (void)hipGetLastError();  // do not inherit an unrelated earlier error of this thread
-  char* ws = st->wsbase + (lane_id == 0 ? 0 : st->ws0.bytes);
   const RecordLayout& r = st->rl;
   char* rec0 = st->stash[kind] + (uint64_t)slot * n * r.bytes;
   HIPCHK(hipMemcpyAsync(rec0 + r.x, x, (uint64_t)T * H * es, hipMemcpyDeviceToDevice, s));

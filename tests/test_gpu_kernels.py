@@ -79,19 +79,20 @@ def test_mfma_tiles_and_pipeline_depths_agree_bitwise(B, T, N, K):
     Xd, Wd, bd, dYd, Rd = (_dev(B, a, 1) for a in (X, W, b, dY, R))
     ref = None
     try:
-        for tile in (22, 11, 24, 42, 44):
+        for tile in (22, 11, 24, 42, 44, 43):
             for depth in (2, 3, 4):
                 B.bk_gemm_tile(tile)
                 B.bk_gemm_stages(depth)
                 Y, G, dX = _empty((T, N), 1), _empty((T, N), 1), _empty((T, K), 1)
                 dW = torch.zeros(K, N, dtype=torch.float32, device=DEV)
                 B.bk_linear_fwd(Xd, Wd, bd, Y, gelu_out=G, impl=2)
-                Y2 = _empty((T, N), 1)
+                Y2, Y3 = _empty((T, N), 1), _empty((T, N), 1)
                 B.bk_linear_fwd(Xd, Wd, bd, Y2, res=Rd, impl=2)
+                B.bk_linear_fwd(Xd, Wd, bd, Y3, impl=2)          # bias only: the form that has the 256 x 192 tile
                 B.bk_linear_bwd_input(dYd, Wd, dX, mul=Xd, impl=2)
                 B.bk_linear_bwd_weight(Xd, dYd, dW, impl=2)
                 torch.cuda.synchronize()
-                got = (Y, G, Y2, dX, dW)
+                got = (Y, G, Y2, Y3, dX, dW)
                 if ref is None:
                     ref = got
                     assert rel_l2(B.to_host(Y2), X.astype(np.float64) @ W.astype(np.float64) + b + R) <= TOL[1]
