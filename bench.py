@@ -33,6 +33,22 @@ def _iteration_flops(sc, frc):
     return sc.M * (sc.n_own * (fwd + bwd) + (sc.n_shadow * fwd if frc else 0.0))
 
 
+def _replay_end(B, merged):
+    """Index where the failover schedule stops rebuilding lost state and resumes the merged 1F1B
+    groups: the first send of an FRC output to the stage after the victim, or, where there is no
+    such stage, the BRC that belongs to the first backward group."""
+    for i, ins in enumerate(merged):
+        if ins[0] == B.SEND_ACT:
+            return i
+        if ins[0] in (B.BWD, B.FWD):
+            while i > 0 and merged[i - 1][0] in (B.BRC, B.RECV_GRAD, B.RECV_ACT, B.SEND_GRAD):
+                i -= 1
+                if merged[i][0] == B.BRC:
+                    break
+            return i
+    return len(merged)
+
+
 def _profiled_traffic(workload):
     """HBM bytes per stage-GEMM launch from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel yardstick), or None."""
@@ -209,7 +225,7 @@ def main():
             hv.begin_iteration(zero_grads=True)
             hv.run(split_at_failure(pv, k_fail))
             merged = sv.failover_merge(k_fail)
-            first_group = next(i for i, ins in enumerate(merged) if ins[0] == B.SEND_ACT)
+            first_group = _replay_end(B, merged)
             hv.sync()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -330,7 +346,7 @@ def main():
             hv.begin_iteration(zero_grads=True)
             hv.run(split_at_failure(pv, k_fail))
             merged = sv.failover_merge(k_fail)
-            first_group = next(i for i, ins in enumerate(merged) if ins[0] == B.SEND_ACT)
+            first_group = _replay_end(B, merged)
             hv.sync()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
