@@ -203,9 +203,23 @@ struct EpiOperands {
   static constexpr bool BF = EPI == EPI_BIAS_RES || EPI == EPI_RES || EPI == EPI_MUL;
   static constexpr bool F32 = EPI == EPI_ACC_F32;
   static constexpr bool PRE = BF || F32;
+  static constexpr bool HASB = EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU;
   static constexpr int NLOADS = BF ? ITS : (F32 ? 2 * ITS : 0);   // load instructions per lane and row block
   bf16x8 b[BF ? ITS : 1];
   f32x4 f[F32 ? ITS : 1][2];
+  // The bias of a lane's columns is the same for every row block: fetched once per tile, at its start
+  // (a load inside the row-block loop would put its latency on every block).
+  bf16x8 bias[HASB ? ITS : 1];
+  __device__ __forceinline__ void issue_bias(const GemmDesc& d, int n0) {
+    if (!HASB) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wn = wave & 1;
+#pragma unroll
+    for (int it = 0; it < ITS; ++it) {
+      const int n = min(n0 + wn * 32 * WN + ((lane + it * 64) % CHUNKS) * 8, d.N - 8);
+      bias[it] = *(const bf16x8*)((const bf16_t*)d.bias + n);
+    }
+  }
   // Rows / columns past the edge are clamped to the last valid ones (their values are never used), so
   // that every lane issues exactly NLOADS loads: the main loop counts them in its vmcnt waits.
   __device__ __forceinline__ void issue(const GemmDesc& d, int m0, int n0, int i) {
@@ -231,7 +245,7 @@ struct EpiOperands {
 // epilogue on 8 consecutive outputs of one row; `pb` / `pf` are the operands fetched ahead
 template <int EPI>
 __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb,
-                                          const f32x4 (&pf)[2], unsigned gelu_tab) {
+                                          const f32x4 (&pf)[2], const bf16x8& pbias, unsigned gelu_tab) {
   const long i = (long)m * d.N + n;
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
@@ -246,9 +260,8 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
 #pragma unroll
   for (int j = 0; j < 8; ++j) v[j] = acc[j];
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
-    const bf16x8 b = *(const bf16x8*)((const bf16_t*)d.bias + n);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] += (float)b[j];
+    for (int j = 0; j < 8; ++j) v[j] += (float)pbias[j];
   }
   if (EPI == EPI_BIAS_RES || EPI == EPI_RES) {
 #pragma unroll
@@ -309,7 +322,8 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
       const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
       if (m < d.M && n < d.N) {
         const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], gelu_tab);
+        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], first.bias[Ops::HASB ? it : 0],
+                       gelu_tab);
       }
     }
     __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
@@ -411,6 +425,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
     __syncthreads();
   }
   EpiOperands<WM, WN, EPI> ops;
+  ops.issue_bias(d, n0);
   ops.issue(d, m0, n0, 0);
   write_tile<WM, WN, EPI, SM::EPI_LD>(d, acc, (float*)smem_raw, m0, n0, ops, gelu_tab);
 }
@@ -672,6 +687,12 @@ __device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
                     L.lds0 + SM::TABLE_OFF + c0 * 16);
     }
   }
+  // The bias is requested before any slice load: the waits below count the loads that are YOUNGER than
+  // the slice they wait for, so however many bias loads the compiler keeps (the columns of a lane often
+  // repeat) and wherever it puts them before this point, they can never stand in for a slice load there.
+  EpiOperands<WM, WN, EPI> ops;
+  ops.issue_bias(d, n0);
+  BAMBOO_SCHED_FENCE();
   // four fragment register sets: k-step s of a slice computes from set s while set (s + 2) % 4 is
   // filled for the k-step after the next one, so an LDS read has more than a whole k-step to return
   bf16x8 fa[4][WM], fb[4][WN];
@@ -705,7 +726,6 @@ __device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
   // slice load, hence simply add to the number of loads that may still be in flight at the waits below.
   // (256 x 256 tiles have no registers to spare for them until the fragments are dead.)
   constexpr bool EARLY = WM * WN <= 8;
-  EpiOperands<WM, WN, EPI> ops;
   if (EARLY) ops.issue(d, m0, n0, 0);
   constexpr int NEPI = EARLY ? EpiOperands<WM, WN, EPI>::NLOADS : 0;
   BAMBOO_SCHED_FENCE();
