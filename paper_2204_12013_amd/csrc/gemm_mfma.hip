@@ -728,6 +728,8 @@ __device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
   constexpr bool EARLY = WM * WN <= 8;
   if (EARLY) ops.issue(d, m0, n0, 0);
   constexpr int NEPI = EARLY ? EpiOperands<WM, WN, EPI>::NLOADS : 0;
+  // the waits below assume these NEPI loads are in flight from here on: keep the compiler from moving them
+  asm volatile("" ::: "memory");
   BAMBOO_SCHED_FENCE();
   // slice nk-1-J still has J slices after it, J-1 of which may be in flight
   auto tail = [&](auto jc) __attribute__((always_inline)) {
