@@ -238,3 +238,82 @@ def test_rc_variants_recover_the_failure_free_gradients(B, name, k_fail, rc):
         assert torch.equal(hz2.z_frc[k], hz0.z_succ[k])
     for s_ in (st0, hz0.succ, st1, hz1.succ, st2, hz2.succ):
         s_.stage_destroy()
+
+
+#                              name  arch dtype H heads  F  seq B own shadow P s M seed
+DEGENERATE = {
+    # one micro-batch, two stages: the program has a single forward and backward
+    "one_microbatch": synth.StageConfig("d0", 0, 0, 64, 2, 128, 8, 2, 1, 1, 2, 0, 1, 41),
+    # sequence length 1: every softmax is over one key; 3 tokens in all (the MFMA kernels do not cover it)
+    "one_position_bf16": synth.StageConfig("d1", 1, 1, 64, 1, 128, 1, 3, 1, 1, 3, 1, 2, 42),
+    # one head as wide as the model, one sample
+    "one_head_one_sample": synth.StageConfig("d2", 1, 1, 128, 1, 256, 72, 1, 1, 1, 4, 2, 3, 43),
+    # more replica layers than own layers (uneven partition), deep pipeline, few micro-batches
+    "uneven_layers": synth.StageConfig("d3", 0, 1, 128, 2, 256, 40, 2, 1, 3, 6, 1, 2, 44),
+}
+
+
+@pytest.mark.parametrize("name", list(DEGENERATE))
+def test_degenerate_configurations_match_oracle_with_and_without_failure(B, name):
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc = DEGENERATE[name]
+    tol = TOL[sc.dtype]
+    inp, st, hz = _build(B, sc)
+    prog = st.stage_schedule()
+    assert prog == S.stage_program(sc.P, sc.stage_id, sc.M)
+    hz.begin_iteration()
+    hz.run(prog)
+    hz.sync()
+    ref = _oracle(sc, inp)
+    for k in range(sc.M):
+        assert rel_l2(B.to_host(hz.y[k]), ref.y[k]) <= tol
+        assert rel_l2(B.to_host(hz.gx[k]), ref.gx[k]) <= tol
+        assert torch.equal(hz.z_frc[k], hz.z_succ[k])
+    check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, tol, "own")
+    check_grads(hz.succ.own_g.cpu().numpy(), ref.G_succ, sc.hidden, sc.ffn, tol, "successor")
+    k_fail = sc.M - 1
+    _, st2, hz2 = _build(B, sc)
+    hz2.begin_iteration()
+    hz2.run(split_at_failure(st2.stage_schedule(), k_fail))
+    hz2.succ.stage_sync()
+    hz2.succ.own_g.zero_()
+    merged = st2.failover_merge(k_fail)
+    assert merged == S.failover_program(sc.P, sc.stage_id, sc.M, k_fail)
+    hz2.run(merged)
+    hz2.sync()
+    assert torch.equal(st2.own_g, st.own_g)
+    assert torch.equal(st2.shadow_g, hz.succ.own_g)
+    for s_ in (st, st2, hz.succ, hz2.succ):
+        s_.stage_destroy()
+
+
+def test_single_stage_pipeline_without_replica(B):
+    """P = 1: no neighbours, no replica, no bubbles; only FNC and BNC remain."""
+    from paper_2204_12013_amd.harness import StageHarness
+    sc = synth.StageConfig("d4", 0, 1, 128, 2, 256, 24, 2, 2, 0, 1, 0, 3, 45)
+    inp = synth.make_stage_inputs(sc)
+    st = B.Stage(B.make_cfg(sc, frc_enabled=False), B.to_device(inp["own_w"].reshape(-1), sc.dtype), None)
+    prog = st.stage_schedule()
+    assert prog == S.stage_program(1, 0, sc.M, frc=False)
+    assert not any(i[0] in (B.FRC, B.BRC, B.BUBBLE, B.SEND_ACT, B.RECV_GRAD) for i in prog)
+    x = [B.to_device(inp["x"][k], sc.dtype) for k in range(sc.M)]
+    gy = [B.to_device(inp["gz"][k], sc.dtype) for k in range(sc.M)]
+    torch.cuda.synchronize()
+    hz = StageHarness(st, x, gz=gy, gy_table=gy)
+    hz.begin_iteration()
+    hz.run(prog)
+    hz.sync()
+    own = oracle_layers(inp["own_w"], sc.hidden, sc.ffn)
+    from oracle import layer as L
+    G = None
+    for k in range(sc.M):
+        y, caches = L.stack_fwd(sc.arch, own, inp["x"][k].astype(np.float64), sc.micro_batch, sc.seq, sc.heads)
+        gx, grads = L.stack_bwd(sc.arch, own, caches, inp["gz"][k].astype(np.float64))
+        assert rel_l2(B.to_host(hz.y[k]), y) <= TOL[sc.dtype]
+        assert rel_l2(B.to_host(hz.gx[k]), gx) <= TOL[sc.dtype]
+        G = grads if G is None else [{n: a[n] + b[n] for n in a} for a, b in zip(G, grads)]
+    check_grads(st.own_g.cpu().numpy(), G, sc.hidden, sc.ffn, TOL[sc.dtype], "own")
+    with pytest.raises(B.BambooError) as e:
+        st.failover_merge(0)
+    assert e.value.status == B.E_STATE
+    st.stage_destroy()
