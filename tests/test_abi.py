@@ -204,3 +204,17 @@ def test_ends_sizes():
         assert e.value.status == B.E_BADCFG
     assert B.lib.ends_front_fwd(None, 0, None, None, None) == B.E_ARG
     assert B.lib.ends_back_bwd(None, None, None) == B.E_ARG
+
+
+def test_largest_micro_batch_count():
+    """M = 32767 is the most the 16-bit micro-batch field of an instruction holds: the program still
+    equals the oracle's, one more is rejected."""
+    P, s, M = 4, 1, 32767
+    got = B.stage_program(_cfg(P, s, M))
+    assert got == S.stage_program(P, s, M)
+    assert sum(1 for i in got if i[0] == S.FWD) == M and max(i[2] for i in got) == M - 1
+    fo = B.stage_failover_program(_cfg(P, s, M), M - 1)
+    assert fo == S.failover_program(P, s, M, M - 1)
+    with pytest.raises(B.BambooError) as e:
+        B.stage_program(_cfg(P, s, M + 1))
+    assert e.value.status == B.E_BADCFG
