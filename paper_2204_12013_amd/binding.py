@@ -232,6 +232,7 @@ class Stage:
         self.stream_main = torch.cuda.Stream(device=self.device)
         self.stream_frc = torch.cuda.Stream(device=self.device)
         self._h = C.c_void_p()
+        self._shadow_g_dirty = False       # shadow_g starts as zeros
         self.merged = False
         self.own_opt = self.shadow_opt = None
         torch.cuda.synchronize(self.device)
@@ -267,9 +268,13 @@ class Stage:
         return self.torch.empty(self.T, self.H, dtype=self.act_dtype, device=self.device)
 
     def zero_grads(self):
+        """Zeroes the gradient buffers on the main stream.  The replica's gradients are only ever written
+        by BRC, so they are cleared only after one has run (a failure-free iteration leaves them zero)."""
         with self.torch.cuda.stream(self.stream_main):
             self.own_g.zero_()
-            self.shadow_g.zero_()
+            if self._shadow_g_dirty:
+                self.shadow_g.zero_()
+                self._shadow_g_dirty = False
 
     def stage_schedule(self):
         n = _check(lib.stage_schedule(self._h, None, 0), "stage_schedule")
@@ -290,6 +295,7 @@ class Stage:
         _check(lib.stage_bwd(self._h, k, _ptr(gy), _ptr(gx)), "stage_bwd")
 
     def shadow_bwd_brc(self, k, gz, gy=None):
+        self._shadow_g_dirty = True
         _check(lib.shadow_bwd_brc(self._h, k, _ptr(gz), _ptr(gy)), "shadow_bwd_brc")
 
     def failover_merge(self, k_fail):
@@ -508,6 +514,7 @@ class Ends:
         self.back_g = torch.zeros(int(sz.back_params), dtype=torch.float32, device=self.device)
         buf = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=self.device)
         self.front_stash, self.back_stash, self.workspace = buf(sz.front_stash), buf(sz.back_stash), buf(sz.workspace)
+        self._front_g_dirty = False        # front_g starts as zeros
         self._h = C.c_void_p()
         torch.cuda.synchronize(self.device)
         _check(lib.ends_init(C.byref(cfg), vocab, C.byref(sz), _ptr(self.front_w), _ptr(self.front_g),
@@ -516,7 +523,9 @@ class Ends:
 
     def zero_grads(self, stream):
         with self.torch.cuda.stream(stream):
-            self.front_g.zero_()
+            if self._front_g_dirty:        # written by the front's backward (BRC) only
+                self.front_g.zero_()
+                self._front_g_dirty = False
             self.back_g.zero_()
 
     def ends_begin_iteration(self):
@@ -526,6 +535,7 @@ class Ends:
         _check(lib.ends_front_fwd(self._h, k, _ptr(ids), _ptr(x0), _stream(stream)), "ends_front_fwd")
 
     def ends_front_bwd(self, k, dx0, stream):
+        self._front_g_dirty = True
         _check(lib.ends_front_bwd(self._h, k, _ptr(dx0), _stream(stream)), "ends_front_bwd")
 
     def ends_back_fwd(self, y, labels, loss, stream):
