@@ -218,3 +218,18 @@ def test_largest_micro_batch_count():
     with pytest.raises(B.BambooError) as e:
         B.stage_program(_cfg(P, s, M + 1))
     assert e.value.status == B.E_BADCFG
+
+
+def test_headers_are_plain_c(tmp_path):
+    """The boundary is a C ABI: every public header compiles as C99 on its own."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h"):
+        src = tmp_path / (h + ".c")
+        src.write_text('#include "%s"\nint main(void) { return 0; }\n' % h)
+        r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
+                            "-c", str(src), "-o", str(tmp_path / (h + ".o"))], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
