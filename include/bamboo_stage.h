@@ -20,7 +20,7 @@
  *     only the pointers.  "host" pointers are ordinary host memory.
  *   - Streams are hipStream_t values passed as void*; they stay the caller's.
  *   - Every compute call enqueues work and returns; nothing blocks the host
- *     except stage_sync.  Calls on one stage must come from one host thread.
+ *     except stage_sync (and stage_init, once per process, see there).  Calls on one stage must come from one host thread.
  *   - Return value: 0 (BAMBOO_OK) or a negative bamboo_status; no exception
  *     crosses this boundary and nothing aborts.
  *   - Tensors are row-major [tokens, features], tokens = micro_batch * seq,
@@ -225,7 +225,9 @@ const char* stage_strerror(int status);
  *                     to them, the caller zeroes them at the start of an iteration.
  *   stashes, workspace device scratch owned by the caller for the stage's life.
  *   stream_main/frc   hipStream_t of lane 0 and lane 1 (default priority).
- * The replica is assumed equal to the successor's parameters at iteration start. */
+ * The replica is assumed equal to the successor's parameters at iteration start.
+ * The first stage_init of a process with the bf16 dtype fills a 30 KB device table (GELU lookup)
+ * on stream_main and waits for it: set-up is the one place that blocks, so that no compute call does. */
 int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void* own_w, const void* shadow_w,
                void* own_g, void* shadow_g, void* own_stash, void* shadow_stash, void* workspace,
                void* stream_main, void* stream_frc, bamboo_stage_t** out);

@@ -83,6 +83,8 @@ hipError_t launch_gemm_simple(hipStream_t s, int dtype, const GemmDesc& d);
 // bf16 MFMA path; returns hipErrorNotSupported when the shape is not covered.
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d);
 hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
+// one-time device tables of the MFMA GEMM (GELU lookup): filled and waited for here, at set-up
+hipError_t prepare_gemm_tables(hipStream_t s);
 // n independent weight-gradient GEMMs (EPI_ACC_F32): one launch where the MFMA kernel covers them all,
 // otherwise one launch each
 hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n);

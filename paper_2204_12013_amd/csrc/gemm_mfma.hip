@@ -55,8 +55,9 @@ __global__ void gelu_table_init_kernel() {
   g_gelu_table[i] = make_float2(phi, phi + h * expf(-0.5f * h * h) * 0.39894228040143268f);
 }
 
-// Fills the table once per process (the one launcher call that waits for the device: the first GEMM
-// with a GELU epilogue).
+// Fills the table once per process and waits for the fill: done by prepare_gemm_tables at set-up
+// (stage_init); a GEMM with a GELU epilogue that finds it missing (the kernel used on its own, without a
+// stage) does it on its first launch, the one launcher call that waits for the device.
 static hipError_t ensure_gelu_table(hipStream_t s) {
   static bool ready = false;
   if (ready) return hipSuccess;
@@ -66,6 +67,9 @@ static hipError_t ensure_gelu_table(hipStream_t s) {
   if (e == hipSuccess) ready = true;
   return e;
 }
+
+// Set-up hook: fill the table now (and wait), so that no later launch has to.
+hipError_t prepare_gemm_tables(hipStream_t s) { return ensure_gelu_table(s); }
 
 // (GELU(h), GELU'(h)) from the table in LDS at byte address `tab`
 __device__ __forceinline__ void gelu_pair_lookup(float h, unsigned tab, float* g, float* dg) {

@@ -684,6 +684,11 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     delete st;
     return BAMBOO_E_NOMEM;
   }
+  if (cfg->dtype == BAMBOO_BF16 && prepare_gemm_tables((hipStream_t)stream_main) != hipSuccess) {
+    (void)hipGetLastError();
+    delete st;
+    return BAMBOO_E_HIP;
+  }
   if (hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming) != hipSuccess) {
     (void)hipGetLastError();
     delete st;
