@@ -34,11 +34,11 @@ def _ids(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
 
 
-def _build(B, sc, V):
+def _build(B, sc, V, swap_slots=0):
     from paper_2204_12013_amd.harness import WrapHarness
     inp = synth.make_stage_inputs(sc)
     ein = synth.make_ends_inputs(sc, V)
-    cfg = B.make_cfg(sc, wrap=1)
+    cfg = B.make_cfg(sc, wrap=1, swap_slots=swap_slots)
     st = B.Stage(cfg, B.to_device(inp["own_w"].reshape(-1), sc.dtype), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype))
     en = B.Ends(cfg, V, B.to_device(ein["front_w"], sc.dtype), B.to_device(ein["back_w"], sc.dtype))
     x = [B.to_device(inp["x"][k], sc.dtype) for k in range(sc.M)]
@@ -169,6 +169,30 @@ def test_failover_rebuilds_the_first_stage_gradients(B, name, k_fail):
     for k in range(sc.M):
         assert torch.equal(hz.gx[k], hz0.gx[k])
         assert torch.equal(hz.z_frc[k], zs[k])
+    for o in (st0, st):
+        o.stage_destroy()
+    for o in (en0, en):
+        o.ends_destroy()
+
+
+@pytest.mark.parametrize("name,k_fail,slots", [("fp32_encoder", 1, 1), ("bf16_decoder", 2, 2), ("bf16_encoder", 3, 2)])
+def test_wrap_around_with_swap_out_of_the_replica_stash(B, name, k_fail, slots):
+    """The replica layers' FRC results swapped out to the host (the front end's small stash stays on the
+    device): failover gives bitwise the gradients of the device-resident failure-free run."""
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc, V = WRAP[name]
+    inp, ein, st0, en0, hz0 = _build(B, sc, V)
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+    _, first_g, first_front_g = _first_stage(B, sc, V, inp, ein)
+    _, _, st, en, hz = _build(B, sc, V, swap_slots=slots)
+    hz.begin_iteration()
+    hz.run(split_at_failure(st.stage_schedule(), k_fail))
+    hz.run(st.failover_merge(k_fail))
+    hz.sync()
+    assert torch.equal(st.own_g, st0.own_g) and torch.equal(en.back_g, en0.back_g) and torch.equal(hz.loss, hz0.loss)
+    assert torch.equal(st.shadow_g, first_g) and torch.equal(en.front_g, first_front_g)
     for o in (st0, st):
         o.stage_destroy()
     for o in (en0, en):
