@@ -94,7 +94,7 @@ typedef struct {
   int32_t wrap;        /* 1: this is the last stage (stage_id == P-1) and its replica layers are the FIRST
                           stage's (Section 5.1: the last node is the first node's predecessor and fetches
                           the input samples itself).  FRC(k) then does not depend on FWD(k), and the
-                          failover schedule is the wrap-around one.  Not with eager BRC.  0 otherwise. */
+                          failover schedule is the wrap-around one.  Only with rc_mode EFLB.  0 otherwise. */
 } bamboo_cfg_t;
 
 /* Instruction set: the paper's computation and communication instructions

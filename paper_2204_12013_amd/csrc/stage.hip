@@ -134,7 +134,8 @@ int validate(const bamboo_cfg_t* c) {
   if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
   if (c->swap_slots < 0 || c->swap_slots > c->M || (c->swap_slots > 0 && c->n_shadow <= 0)) return BAMBOO_E_BADCFG;
   if (c->wrap != 0 && c->wrap != 1) return BAMBOO_E_BADCFG;
-  if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode == BAMBOO_RC_EFEB))
+  // the wrap-around failover schedule exists for the paper's own variant only (eager FRC, lazy BRC)
+  if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode != BAMBOO_RC_EFLB))
     return BAMBOO_E_BADCFG;
   return BAMBOO_OK;
 }
