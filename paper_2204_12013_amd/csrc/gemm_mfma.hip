@@ -968,29 +968,40 @@ hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n) {
     nk_min = d[i].K / BK < nk_min ? d[i].K / BK : nk_min;
   }
   if (nk_min < 3) return hipErrorNotSupported;
-  // 128 x 128 tiles with a ring of three, or 256 x 256 tiles with a ring of two: the cheaper by the cost
-  // model of the single launches, with all tiles of the group sharing the rounds
-  float cost[2] = {0.f, 0.f};
-  const int codes[2] = {22, 44}, nss[2] = {3, 2};
-  for (int c = 0; c < 2; ++c) {
+  // Tile shape for the whole group: 128 x 128, 128 x 256 or 256 x 128 with a ring of three, or 256 x 256
+  // with a ring of two -- the cheapest by the cost model of the single launches, with all tiles of the
+  // group sharing the rounds.
+  const int codes[4] = {22, 44, 24, 42}, nss[4] = {3, 2, 3, 3};
+  int pick = 0;
+  float best = 0.f;
+  for (int c = 0; c < 4; ++c) {
     const TileCost* t = nullptr;
     for (const TileCost& e : kCostAcc)
       if (e.code == codes[c] && e.ns == nss[c]) t = &e;
-    const int w = codes[c] / 10;
+    if (!t) continue;
+    const int wm = codes[c] / 10, wn = codes[c] % 10;
     long tiles = 0;
     double slices = 0;
     for (int i = 0; i < n; ++i) {
-      const long ti = (long)((d[i].M + 64 * w - 1) / (64 * w)) * ((d[i].N + 64 * w - 1) / (64 * w));
+      const long ti = (long)((d[i].M + 64 * wm - 1) / (64 * wm)) * ((d[i].N + 64 * wn - 1) / (64 * wn));
       tiles += ti;
       slices += (double)ti * (d[i].K / BK);
     }
     const long rounds = (tiles + 255) / 256;
-    cost[c] = rounds * (t->a + t->b * (float)(slices / tiles)) + t->c;
+    const float cost = rounds * (t->a + t->b * (float)(slices / tiles)) + t->c;
+    if (pick == 0 || cost < best) {
+      pick = codes[c];
+      best = cost;
+    }
   }
-  int pick = cost[1] < cost[0] ? 44 : 22;
-  if (g_forced_tile == 22 || g_forced_tile == 44) pick = g_forced_tile;
+  if (g_forced_tile == 22 || g_forced_tile == 44 || g_forced_tile == 24 || g_forced_tile == 42) pick = g_forced_tile;
   else if (g_forced_tile || g_forced_stages) return hipErrorNotSupported;   // a forced shape this launch does not offer
-  return pick == 44 ? launch_group_cfg<4, 4, 2>(s, g) : launch_group_cfg<2, 2, 3>(s, g);
+  switch (pick) {
+    case 44: return launch_group_cfg<4, 4, 2>(s, g);
+    case 24: return launch_group_cfg<2, 4, 3>(s, g);
+    case 42: return launch_group_cfg<4, 2, 3>(s, g);
+    default: return launch_group_cfg<2, 2, 3>(s, g);
+  }
 }
 
 hipError_t launch_gemm_mfma(hipStream_t s, const GemmDesc& d) {

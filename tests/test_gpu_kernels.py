@@ -123,7 +123,7 @@ def test_grouped_weight_gradients_equal_the_single_launches_bitwise(B, shapes):
     for X, dY, dW in zip(Xs, dYs, single):
         B.bk_linear_bwd_weight(X, dY, dW)
     try:
-        for tile in (0, 22, 44):
+        for tile in (0, 22, 44, 24, 42):
             B.bk_gemm_tile(tile)
             grouped = [w.clone() for w in inits]
             B.bk_linear_bwd_weight_group(Xs, dYs, grouped)
