@@ -121,3 +121,17 @@ def test_ordered_sum_is_reproducible(B):
             outs.append(o.item())
         assert outs[0] == outs[1]
         assert abs(outs[0] - 0.5 * x.astype(np.float64).sum()) <= 1e-5 * max(1.0, np.abs(x).sum())
+
+
+def test_bad_arguments_are_rejected(B):
+    t = torch.zeros(16, 16, device=DEV)
+    lab = _dev_ids([0] * 16)
+    f = torch.zeros(16, device=DEV)
+    p = B._ptr
+    assert B.lib.bk_softmax_xent_fwd(0, 16, 12, p(t), p(lab), p(f), p(f), None) == B.E_ARG          # V not a multiple of 8
+    assert B.lib.bk_softmax_xent_fwd(0, 0, 16, p(t), p(lab), p(f), p(f), None) == B.E_ARG
+    assert B.lib.bk_softmax_xent_fwd(0, 16, 16, None, p(lab), p(f), p(f), None) == B.E_ARG
+    assert B.lib.bk_softmax_xent_bwd(2, 16, 16, p(t), p(lab), p(f), 1.0, p(t), None) == B.E_ARG      # unknown dtype
+    assert B.lib.bk_embedding_bwd(0, 16, 5, 16, 16, p(lab), p(t), p(t), p(t), None) == B.E_ARG       # tokens not a multiple of seq
+    assert B.lib.bk_ordered_sum(0, p(f), 1.0, p(f), None) == B.E_ARG
+    assert B.lib.bk_ordered_sum(16, None, 1.0, p(f), None) == B.E_ARG
