@@ -67,6 +67,13 @@ struct GemmDesc {
   // the same dY; colsum_partial is scratch of colsum_partial_floats(N) floats
   float* colsum_out;
   float* colsum_partial;
+  // EPI_MUL only: tile_colsum (device fp32, reduce_max_partials() rows of N) receives one row of column
+  // sums of the stored outputs per row of output tiles, and *tile_colsum_parts (host) the number of rows
+  // written -- the bias gradient of the linear layer whose pre-activation gradient this GEMM produces,
+  // without reading the output again.  Honoured by launch_gemm (kernels that cannot do it get a
+  // column-sum launch behind them).
+  float* tile_colsum;
+  int* tile_colsum_parts;
 };
 
 // up to MAX independent GEMMs for one launch; first[p] = index of problem p's first workgroup

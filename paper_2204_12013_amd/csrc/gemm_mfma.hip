@@ -249,7 +249,8 @@ struct EpiOperands {
 // epilogue on 8 consecutive outputs of one row; `pb` / `pf` are the operands fetched ahead
 template <int EPI>
 __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const float (&acc)[8], const bf16x8& pb,
-                                          const f32x4 (&pf)[2], const bf16x8& pbias, unsigned gelu_tab) {
+                                          const f32x4 (&pf)[2], const bf16x8& pbias, unsigned gelu_tab,
+                                          float* stored = nullptr) {
   const long i = (long)m * d.N + n;
   if (EPI == EPI_ACC_F32) {
     float* c = (float*)d.C + i;
@@ -274,7 +275,10 @@ __device__ __forceinline__ void epilogue8(const GemmDesc& d, int m, int n, const
   bf16x8 o;
   if (EPI == EPI_MUL) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) o[j] = (bf16_t)(v[j] * (float)pb[j]);
+    for (int j = 0; j < 8; ++j) {
+      o[j] = (bf16_t)(v[j] * (float)pb[j]);
+      if (stored != nullptr) stored[j] = (float)o[j];
+    }
   } else if (EPI == EPI_BIAS_GELU) {
     bf16x8 g;
 #pragma unroll
@@ -303,6 +307,11 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
   float* stage = stage_all + wave * 32 * EPI_LD;
   Ops ops[2];
   ops[0] = first;
+  // Column sums of the stored outputs (EPI_MUL with d.tile_colsum): where 64 is a multiple of the chunks per
+  // staged row, a lane meets the same 8 columns in every pass, so it keeps 8 running sums over its rows.
+  constexpr bool CAN_SUM = EPI == EPI_MUL && 64 % Ops::CHUNKS == 0;
+  const bool sum_cols = CAN_SUM && d.tile_colsum != nullptr;
+  float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < WM; ++i) {
     if (i + 1 < WM) ops[(i + 1) & 1].issue(d, m0, n0, i + 1);
@@ -326,11 +335,43 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
       const f32x4 hi = *(const f32x4*)(stage + row * EPI_LD + ch * 8 + 4);
       if (m < d.M && n < d.N) {
         const float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], first.bias[Ops::HASB ? it : 0],
-                       gelu_tab);
+        if (CAN_SUM) {
+          float st8[8];
+          epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], first.bias[Ops::HASB ? it : 0],
+                         gelu_tab, st8);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) cs[j] += st8[j];
+        } else {
+          epilogue8<EPI>(d, m, n, v, cur.b[Ops::BF ? it : 0], cur.f[Ops::F32 ? it : 0], first.bias[Ops::HASB ? it : 0],
+                         gelu_tab);
+        }
       }
     }
     __builtin_amdgcn_wave_barrier();      // reads done before the next row block overwrites the stage
+  }
+  if (CAN_SUM) {
+    if (sum_cols) {     // uniform over the workgroup
+      // lanes that share a chunk (same lane % CHUNKS), in a fixed order; then the two wavefronts that share
+      // the columns (wm = 0, 1), again in a fixed order
+#pragma unroll
+      for (int o = Ops::CHUNKS; o < 64; o <<= 1)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cs[j] += __shfl_xor(cs[j], o, 64);
+      float* xch = stage_all;               // [2 wn][CHUNKS][8]: the staging area is free now
+      __syncthreads();
+      if (wm == 1 && lane < Ops::CHUNKS)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) xch[(wn * Ops::CHUNKS + lane) * 8 + j] = cs[j];
+      __syncthreads();
+      if (wm == 0 && lane < Ops::CHUNKS) {
+        const int n = n0 + wn * 32 * WN + lane * 8;
+        if (n < d.N) {
+          float* dst = d.tile_colsum + (long)(m0 / (64 * WM)) * d.N + n;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dst[j] = cs[j] + xch[(wn * Ops::CHUNKS + lane) * 8 + j];
+        }
+      }
+    }
   }
 }
 
@@ -910,6 +951,8 @@ static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
     // 256 x 192 where this form and shape have it, the next larger tile otherwise
     if (pick == 43 && !(HAS_43 && d.K % BK == 0 && d.K >= 2 * BK)) pick = 44;
   }
+  if (EPI == EPI_MUL && d.tile_colsum != nullptr && d.tile_colsum_parts != nullptr)
+    *d.tile_colsum_parts = (d.M + 64 * (pick / 10) - 1) / (64 * (pick / 10));   // one row of column sums per tile row
   if constexpr (HAS_43) {
     if (pick == 43) {
       if (d.K % BK != 0 || d.K < 2 * BK) return hipErrorNotSupported;

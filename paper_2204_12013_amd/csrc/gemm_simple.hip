@@ -106,7 +106,11 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d) {
     hipError_t e = launch_gemm_mfma(s, d);
     if (e != hipErrorNotSupported) return e;
   }
-  return launch_gemm_simple(s, dtype, d);
+  const hipError_t e = launch_gemm_simple(s, dtype, d);
+  if (e != hipSuccess) return e;
+  if (d.tile_colsum != nullptr && d.tile_colsum_parts != nullptr)   // the MFMA epilogue would have summed the columns
+    return launch_colsum_partials(s, dtype, d.M, d.N, d.C, d.tile_colsum, d.tile_colsum_parts);
+  return hipSuccess;
 }
 
 hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n) {

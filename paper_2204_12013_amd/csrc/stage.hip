@@ -438,14 +438,27 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     // f = g W2 + b2
     d = gemm_nt(df, P(st->po.W2), dh, T, F, H, EPI_MUL);   // through the activation: times GELU'(h)
     d.aux_in = rec + r.dg;
+    // the column sums of dh (the gradient of b1) come out of the same kernel, one partial row per tile row
+    // (as long as the smallest tile's rows, T / 64, fit the partial buffer)
+    const bool fused_sum = (size_t)((T + 63) / 64) <= reduce_max_partials();
+    int dh_parts = 0;
+    if (fused_sum) {
+      d.tile_colsum = (float*)(ws + w.p_dh);
+      d.tile_colsum_parts = &dh_parts;
+    }
     BBCHK(p_gemm(st, s, d));
+    if (fused_sum) {
+      if (!grad_reduce_add(&batch, F, dh_parts, (const float*)(ws + w.p_dh), G + st->po.b1, nullptr, nullptr))
+        return BAMBOO_E_STATE;
+    } else {
+      BBCHK(p_colsum(st, s, ws, T, F, dh, G + st->po.b1, w.p_dh, &batch));
+    }
     // The four weight gradients of the layer wait until its end: their operands (df, dh, da, dqkv and the
     // record) all live that long, nothing in the layer depends on them, and launched together their tiles
     // share the rounds of the chip.
     GemmDesc wgrad[4];
     wgrad[0] = gemm_tn(rec + r.g, df, G + st->po.W2, T, F, H);
     // h = fin W1 + b1
-    BBCHK(p_colsum(st, s, ws, T, F, dh, G + st->po.b1, w.p_dh, &batch));
     wgrad[1] = gemm_tn(rec + r.fin, dh, G + st->po.W1, T, H, F);
     const void* da;     // gradient at the attention block's output
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
