@@ -112,9 +112,11 @@ __device__ __forceinline__ void load_row_frags(bf16x8 (&f)[D / 16], const bf16_t
 
 // Write a wavefront's transposed result (lane = output row, accumulator rows =
 // feature index) through its private LDS area to global rows of D features.
-template <int D>
-__device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float mul, bf16_t* stage, bf16_t* g,
-                                           long row_stride, int row0, int row_lim) {
+// cs (optional): the lane's running sums of the 8 columns it stores (every pass meets the same 8, as 64 is a
+// multiple of the chunks per row), over the rows it stores.
+template <int D, bool SUM>
+__device__ __forceinline__ void store_rows_impl(const f32x16 (&acc)[D / 32], float mul, bf16_t* stage, bf16_t* g,
+                                                long row_stride, int row0, int row_lim, float (&cs)[8]) {
   constexpr int LD = D + 8;
   const int l = threadIdx.x & 63;
 #pragma unroll
@@ -133,9 +135,52 @@ __device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float mu
     const int idx = l + it * 64;
     const int row = idx / (D / 8), ch = (idx % (D / 8)) * 8;
     const bf16x8 t = *(const bf16x8*)(stage + row * LD + ch);
-    if (row0 + row < row_lim) *(bf16x8*)(g + (long)(row0 + row) * row_stride + ch) = t;
+    if (row0 + row < row_lim) {
+      *(bf16x8*)(g + (long)(row0 + row) * row_stride + ch) = t;
+      if (SUM) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cs[j] += (float)t[j];
+      }
+    }
   }
   __builtin_amdgcn_wave_barrier();
+}
+
+template <int D>
+__device__ __forceinline__ void store_rows(const f32x16 (&acc)[D / 32], float mul, bf16_t* stage, bf16_t* g,
+                                           long row_stride, int row0, int row_lim) {
+  float unused[8];
+  store_rows_impl<D, false>(acc, mul, stage, g, row_stride, row0, row_lim, unused);
+}
+template <int D>
+__device__ __forceinline__ void store_rows_sum(const f32x16 (&acc)[D / 32], float mul, bf16_t* stage, bf16_t* g,
+                                               long row_stride, int row0, int row_lim, float (&cs)[8]) {
+  store_rows_impl<D, true>(acc, mul, stage, g, row_stride, row0, row_lim, cs);
+}
+
+// Column sums of what the workgroup's four wavefronts stored with store_rows (D columns, 128 rows): lanes that
+// share a chunk first, then the wavefronts, both in a fixed order; written to dst[0..D).  xch: 4 * D floats of
+// LDS that nobody else uses between the two barriers.  Must be reached by the whole workgroup.
+template <int D>
+__device__ __forceinline__ void block_colsum_write(float (&cs)[8], float* xch, float* dst) {
+  constexpr int CH = D / 8;
+  static_assert(64 % CH == 0, "a lane must keep its columns across passes");
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+#pragma unroll
+  for (int o = CH; o < 64; o <<= 1)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) cs[j] += __shfl_xor(cs[j], o, 64);
+  __syncthreads();
+  if (l < CH)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xch[wave * D + l * 8 + j] = cs[j];
+  __syncthreads();
+  if (wave == 0 && l < CH)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int c = l * 8 + j;
+      dst[c] = ((xch[c] + xch[D + c]) + xch[2 * D + c]) + xch[3 * D + c];
+    }
 }
 
 // =============================================================== forward
@@ -388,7 +433,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
     __syncthreads();
   }
   bf16_t* stage = (bf16_t*)smem_raw + wave * 32 * (D + 8);
-  store_rows<D>(dq, scale, stage, (bf16_t*)a.dqkv + (long)b * S * rs + h * D, rs, qw0, S);
+  float* xch = (float*)((bf16_t*)smem_raw + 4 * 32 * (D + 8));     // behind the four staging areas
+  if (a.dqkv_colsum != nullptr) {                                  // uniform over the grid
+    float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_rows_sum<D>(dq, scale, stage, (bf16_t*)a.dqkv + (long)b * S * rs + h * D, rs, qw0, S, cs);
+    float* part = a.dqkv_colsum + ((long)b * ((S + 127) / 128) + qblk) * rs;
+    block_colsum_write<D>(cs, xch, part + h * D);
+  } else {
+    store_rows<D>(dq, scale, stage, (bf16_t*)a.dqkv + (long)b * S * rs + h * D, rs, qw0, S);
+  }
 }
 
 // dK, dV: a wavefront owns 32 keys (lane = key) and streams 64-query tiles.
@@ -518,8 +571,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
   }
   bf16_t* stage = (bf16_t*)smem_raw + wave * 32 * (D + 8);
   bf16_t* out = (bf16_t*)a.dqkv + (long)b * S * rs + h * D;
-  store_rows<D>(dk, scale, stage, out + H, rs, kw0, S);
-  store_rows<D>(dv, 1.f, stage, out + 2 * H, rs, kw0, S);
+  float* xch = (float*)((bf16_t*)smem_raw + 4 * 32 * (D + 8));     // behind the four staging areas
+  if (a.dqkv_colsum != nullptr) {                                  // uniform over the grid
+    float* part = a.dqkv_colsum + ((long)b * ((S + 127) / 128) + kblk) * rs;
+    float cs[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_rows_sum<D>(dk, scale, stage, out + H, rs, kw0, S, cs);
+    block_colsum_write<D>(cs, xch, part + H + h * D);
+    float cv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_rows_sum<D>(dv, 1.f, stage, out + 2 * H, rs, kw0, S, cv);
+    block_colsum_write<D>(cv, xch, part + 2 * H + h * D);
+  } else {
+    store_rows<D>(dk, scale, stage, out + H, rs, kw0, S);
+    store_rows<D>(dv, 1.f, stage, out + 2 * H, rs, kw0, S);
+  }
 }
 
 // ------------------------------------------------------------------ launchers
@@ -566,6 +630,7 @@ static hipError_t bwd_launch(hipStream_t s, const AttnDesc& a) {
   dim3 grid(((a.S + 127) / 128) * a.B * a.heads);
   hipLaunchKernelGGL(kq, grid, dim3(256), BYTES_DQ, s, a);
   hipLaunchKernelGGL(kkv, grid, dim3(256), BYTES_DKV, s, a);
+  if (a.dqkv_colsum != nullptr && a.dqkv_colsum_parts != nullptr) *a.dqkv_colsum_parts = a.B * ((a.S + 127) / 128);
   return hipGetLastError();
 }
 

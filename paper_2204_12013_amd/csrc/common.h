@@ -113,6 +113,12 @@ struct AttnDesc {
   const void* dctx;     // bwd in
   void* dqkv;           // bwd out [T,3H]
   float* delta;         // bwd scratch [B,heads,S]
+  // bwd, optional: dqkv_colsum (device fp32, B * ceil(S/128) rows of 3H) receives, per sample and block of
+  // 128 tokens, the column sums of the dqkv rows the MFMA kernels store (the bias gradient of the QKV
+  // projection, without reading dqkv again); *dqkv_colsum_parts (host) = number of rows written, left
+  // untouched by a kernel that does not do it.
+  float* dqkv_colsum;
+  int* dqkv_colsum_parts;
 };
 hipError_t launch_attention_fwd_simple(hipStream_t s, int dtype, const AttnDesc& d);
 hipError_t launch_attention_bwd_simple(hipStream_t s, int dtype, const AttnDesc& d);

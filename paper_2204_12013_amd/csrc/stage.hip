@@ -477,9 +477,21 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     // a = ctx Wo + bo
     wgrad[2] = gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H);
     BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
+    // the MFMA kernels also leave the column sums of dqkv (the gradient of bqkv), one partial row per sample
+    // and block of 128 tokens; any other kernel leaves dqkv_parts at 0 and a column-sum launch follows
+    int dqkv_parts = 0;
+    if ((size_t)c.micro_batch * ((c.seq + 127) / 128) <= reduce_max_partials()) {
+      a.dqkv_colsum = (float*)(ws + w.p_dqkv);
+      a.dqkv_colsum_parts = &dqkv_parts;
+    }
     BBCHK(p_attn_bwd(st, s, a));
     // qkv = ain Wqkv + bqkv
-    BBCHK(p_colsum(st, s, ws, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
+    if (dqkv_parts > 0) {
+      if (!grad_reduce_add(&batch, 3 * H, dqkv_parts, (const float*)(ws + w.p_dqkv), G + st->po.bqkv, nullptr, nullptr))
+        return BAMBOO_E_STATE;
+    } else {
+      BBCHK(p_colsum(st, s, ws, T, 3 * H, dqkv, G + st->po.bqkv, w.p_dqkv, &batch));
+    }
     wgrad[3] = gemm_tn(rec + r.ain, dqkv, G + st->po.Wqkv, T, H, 3 * H);
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
