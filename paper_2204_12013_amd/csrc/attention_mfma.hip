@@ -316,31 +316,6 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
 }
 
 // =============================================================== backward
-// delta[b,h,q] = sum over the head's features of ctx * dctx
-template <int D>
-__global__ __launch_bounds__(256) void attn_delta_mfma_kernel(AttnDesc a) {
-  constexpr int G = D / 8;                        // lanes per (token, head)
-  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
-  const int H = a.heads * D;
-  const long total = (long)a.B * a.S * H / 8;
-  float s = 0.f;
-  if (idx < total) {
-    const bf16x8 x = *((const bf16x8*)a.ctx + idx);
-    const bf16x8 y = *((const bf16x8*)a.dctx + idx);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) s += (float)x[j] * (float)y[j];
-  }
-#pragma unroll
-  for (int o = G / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-  if (idx < total && (threadIdx.x % G) == 0) {
-    const long e = idx * 8;
-    const long token = e / H;
-    const int h = (int)((e % H) / D);
-    const int b = (int)(token / a.S), q = (int)(token % a.S);
-    a.delta[((long)b * a.heads + h) * a.S + q] = s;
-  }
-}
-
 // dQ: a wavefront owns 32 queries (lane = query) and streams 64-key tiles.
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
@@ -364,7 +339,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
   load_row_frags<D>(dof, dbase, H, qw0, S);
   const int query = qw0 + (lane & 31);
   const long sidx = ((long)b * a.heads + h) * S + min(query, S - 1);
-  const float lse2 = a.lse[sidx] * kLog2e, delta = a.delta[sidx];
+  const float lse2 = a.lse[sidx] * kLog2e;
+  // delta[q] = sum over the head's features of ctx * dctx: the two lanes of a query hold the two halves of
+  // every 16-feature group of dctx already; the same pieces of ctx are read once.  The dK/dV kernel, which
+  // runs after this one, takes delta from memory.
+  float delta = 0.f;
+  {
+    bf16x8 of[D / 16];
+    load_row_frags<D>(of, (const bf16_t*)a.ctx + (long)b * S * H + h * D, H, qw0, S);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) delta += (float)of[ks][j] * (float)dof[ks][j];
+    delta += __shfl_xor(delta, 32, 64);
+    if (lane < 32 && query < S) a.delta[sidx] = delta;
+  }
   f32x16 dq[D / 32];
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -625,8 +614,6 @@ static hipError_t bwd_launch(hipStream_t s, const AttnDesc& a) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  const long chunks = (long)a.B * a.S * a.heads * D / 8;
-  hipLaunchKernelGGL(attn_delta_mfma_kernel<D>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, a);
   dim3 grid(((a.S + 127) / 128) * a.B * a.heads);
   hipLaunchKernelGGL(kq, grid, dim3(256), BYTES_DQ, s, a);
   hipLaunchKernelGGL(kkv, grid, dim3(256), BYTES_DKV, s, a);
