@@ -76,12 +76,19 @@ struct GemmDesc {
   int* tile_colsum_parts;
 };
 
-// up to MAX independent GEMMs for one launch; first[p] = index of problem p's first workgroup
+// Ordered final sums of partial rows (see launch_grad_reduce below): out0[c] += sum_y p0[y][c] over `parts`
+// rows of N floats, the same for the optional pair p1/out1; block0 = first workgroup of the segment.
+struct GradReduceSeg { const float* p0; float* out0; const float* p1; float* out1; int N, parts, block0; };
+struct GradReduceBatch { GradReduceSeg seg[8]; int n; };
+
+// up to MAX independent GEMMs for one launch; first[p] = index of problem p's first workgroup.
+// Workgroups from first[MAX] on (there are grad_reduce_blocks(tail) of them) do the reductions of `tail`.
 struct GemmGroup {
   static constexpr int MAX = 4;
   GemmDesc d[MAX];
   int first[MAX + 1];
   int n;
+  GradReduceBatch tail;
 };
 
 // dtype: 0 fp32, 1 bf16 (enum bamboo_dtype).  All launchers return hipError_t
@@ -94,8 +101,12 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d);
 hipError_t prepare_gemm_tables(hipStream_t s);
 // n independent weight-gradient GEMMs (EPI_ACC_F32): one launch where the MFMA kernel covers them all,
 // otherwise one launch each
-hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n);
-hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n);
+// tail (optional): reductions that depend on nothing in the group, done by extra workgroups of the same
+// launch, which find idle CUs while the last GEMM tiles run; *tail_done says whether the launch took them
+// (a path that does not leaves them to the caller's launch_grad_reduce).
+hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n, const GradReduceBatch* tail = nullptr);
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n, const GradReduceBatch* tail = nullptr,
+                             bool* tail_done = nullptr);
 // output tile of the MFMA kernel: 10*WM + WN forces (64*WM) x (64*WN), 0 = automatic; returns the previous code
 bool gemm_tile_code_valid(int code);
 int set_gemm_tile(int code);
@@ -148,11 +159,10 @@ hipError_t launch_layernorm_bwd_partials(hipStream_t s, int dtype, int T, int H,
                                          const float* stats, const void* gamma, const void* add, void* dr, float* pg,
                                          float* pb, float* pc, int* parts);
 hipError_t launch_colsum_partials(hipStream_t s, int dtype, int T, int N, const void* a, float* partial, int* parts);
-struct GradReduceSeg { const float* p0; float* out0; const float* p1; float* out1; int N, parts, block0; };
-struct GradReduceBatch { GradReduceSeg seg[8]; int n; };
 // appends out0[c] += sum_y p0[y][c] (and the same for the optional second pair p1/out1); false when full
 bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, float* out0, const float* p1, float* out1);
 hipError_t launch_grad_reduce(hipStream_t s, const GradReduceBatch& b);
+int grad_reduce_blocks(const GradReduceBatch& b);   // workgroups (of 64 columns each) the batch needs
 size_t reduce_max_partials();
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);

@@ -24,6 +24,7 @@
 #include <string.h>
 
 #include "common.h"
+#include "reduce_device.h"
 
 namespace bamboo {
 
@@ -816,6 +817,11 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
 template <int WM, int WN, int NS, int MINB>
 __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_group_kernel(GemmGroup g) {
   const int b = blockIdx.x;
+  if (b >= g.first[GemmGroup::MAX]) {              // behind the GEMM tiles: the reductions riding along
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    colreduce_batch_block(g.tail, b - g.first[GemmGroup::MAX], (float*)smem_raw);
+    return;
+  }
   int p = 0;
 #pragma unroll
   for (int q = 1; q < GemmGroup::MAX; ++q)
@@ -986,6 +992,8 @@ static hipError_t launch_group_cfg(hipStream_t s, GemmGroup& g) {
     total += ((g.d[i].M + 64 * WM - 1) / (64 * WM)) * ((g.d[i].N + 64 * WN - 1) / (64 * WN));
   }
   for (int i = g.n; i <= GemmGroup::MAX; ++i) g.first[i] = total;
+  static_assert(SM::BYTES >= kReduceLdsFloats * 4, "the tail workgroups use the front of the tile ring");
+  total += grad_reduce_blocks(g.tail);
   hipLaunchKernelGGL(kern, dim3(total), dim3(256), SM::BYTES, s, g);
   return hipGetLastError();
 }
@@ -999,11 +1007,12 @@ static bool wgrad_form_ok(const GemmDesc& d) {
 
 // n <= GemmGroup::MAX weight-gradient GEMMs (dW += X^T dY) as one launch where the pipelined MFMA kernel
 // covers all of them with one tile shape; hipErrorNotSupported otherwise (the caller launches them singly).
-hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n) {
+hipError_t launch_gemm_group_mfma(hipStream_t s, const GemmDesc* d, int n, const GradReduceBatch* tail) {
   if (n < 1 || n > GemmGroup::MAX) return hipErrorNotSupported;
   GemmGroup g;
   memset(&g, 0, sizeof(g));
   g.n = n;
+  if (tail != nullptr) g.tail = *tail;
   int nk_min = 1 << 30;
   for (int i = 0; i < n; ++i) {
     if (!wgrad_form_ok(d[i])) return hipErrorNotSupported;

@@ -113,13 +113,18 @@ hipError_t launch_gemm(hipStream_t s, int dtype, const GemmDesc& d) {
   return hipSuccess;
 }
 
-hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n) {
+hipError_t launch_gemm_group(hipStream_t s, int dtype, const GemmDesc* d, int n, const GradReduceBatch* tail,
+                             bool* tail_done) {
+  if (tail_done) *tail_done = false;
   if (dtype == 1 && n > 1) {
     bool plain = true;
     for (int i = 0; i < n; ++i) plain = plain && d[i].colsum_out == nullptr;
     if (plain) {
-      const hipError_t e = launch_gemm_group_mfma(s, d, n);
-      if (e != hipErrorNotSupported) return e;
+      const hipError_t e = launch_gemm_group_mfma(s, d, n, tail_done ? tail : nullptr);
+      if (e != hipErrorNotSupported) {
+        if (tail_done) *tail_done = e == hipSuccess && tail != nullptr;
+        return e;
+      }
     }
   }
   for (int i = 0; i < n; ++i) {

@@ -6,6 +6,7 @@
 // ordered sum), so results are bitwise reproducible -- needed for FRC == FNC
 // and for failover == failure-free gradients.
 #include "common.h"
+#include "reduce_device.h"
 
 namespace bamboo {
 
@@ -428,38 +429,8 @@ __global__ __launch_bounds__(1024) void colreduce_final_kernel(int N, int splits
 // The same ordered final sum for up to eight reductions in one launch (the parameter-gradient
 // reductions of one layer's backward): workgroup b serves the segment whose block range holds b.
 __global__ __launch_bounds__(1024) void colreduce_final_batch_kernel(GradReduceBatch batch) {
-  __shared__ float red[2][kFinalWaves][64];
-  int si = 0;
-#pragma unroll
-  for (int k = 1; k < 8; ++k)
-    if (k < batch.n && (int)blockIdx.x >= batch.seg[k].block0) si = k;
-  const GradReduceSeg sg = batch.seg[si];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c = ((int)blockIdx.x - sg.block0) * 64 + lane;
-  const int per = (sg.parts + kFinalWaves - 1) / kFinalWaves;
-  float s = 0.f, q = 0.f;
-  if (c < sg.N) {
-    const int y_end = min(sg.parts, (w + 1) * per);
-#pragma unroll 8
-    for (int y = w * per; y < y_end; ++y) s += sg.p0[(long)y * sg.N + c];
-    if (sg.p1 != nullptr) {
-#pragma unroll 8
-      for (int y = w * per; y < y_end; ++y) q += sg.p1[(long)y * sg.N + c];
-    }
-  }
-  red[0][w][lane] = s;
-  red[1][w][lane] = q;
-  __syncthreads();
-  if (w == 0 && c < sg.N) {
-    float a = 0.f, b = 0.f;
-#pragma unroll
-    for (int k = 0; k < kFinalWaves; ++k) {
-      a += red[0][k][lane];
-      b += red[1][k][lane];
-    }
-    sg.out0[c] += a;
-    if (sg.p1 != nullptr) sg.out1[c] += b;
-  }
+  __shared__ float red[kReduceLdsFloats];
+  colreduce_batch_block(batch, (int)blockIdx.x, red);
 }
 
 bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, float* out0, const float* p1, float* out1) {
@@ -470,9 +441,13 @@ bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, floa
   ++b->n;
   return true;
 }
+int grad_reduce_blocks(const GradReduceBatch& b) {
+  return b.n <= 0 ? 0 : b.seg[b.n - 1].block0 + (b.seg[b.n - 1].N + 63) / 64;
+}
 hipError_t launch_grad_reduce(hipStream_t s, const GradReduceBatch& b) {
   if (b.n <= 0) return hipSuccess;
-  const int blocks = b.seg[b.n - 1].block0 + (b.seg[b.n - 1].N + 63) / 64;
+  static_assert(kReduceGroups == kFinalWaves, "one group of partial rows per wavefront");
+  const int blocks = grad_reduce_blocks(b);
   hipLaunchKernelGGL(colreduce_final_batch_kernel, dim3(blocks), dim3(1024), 0, s, b);
   return hipGetLastError();
 }

@@ -245,11 +245,13 @@ int p_gemm(bamboo_stage* st, hipStream_t s, const GemmDesc& d) {
   return BAMBOO_OK;
 }
 // the weight-gradient GEMMs of one layer, as one launch where possible
-int p_gemm_group(bamboo_stage* st, hipStream_t s, const GemmDesc* d, int n) {
+// tail: reductions that may ride in the same launch; *tail_done tells whether they did
+int p_gemm_group(bamboo_stage* st, hipStream_t s, const GemmDesc* d, int n, const GradReduceBatch* tail,
+                 bool* tail_done) {
   double flops = 0;
   for (int i = 0; i < n; ++i) flops += gemm_flops(d[i]);
   ProfScope p(st, BAMBOO_K_GEMM_WGRAD, s, flops);
-  HIPCHK(launch_gemm_group(s, st->cfg.dtype, d, n));
+  HIPCHK(launch_gemm_group(s, st->cfg.dtype, d, n, tail, tail_done));
   return BAMBOO_OK;
 }
 double attn_fwd_flops(const AttnDesc& a) {
@@ -502,8 +504,11 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
       BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
                      G + st->po.g1, G + st->po.be1, nullptr, w.p_ln[0], &batch));   // + residual branch of x1 = x + a
     }
-    BBCHK(p_gemm_group(st, s, wgrad, 4));
-    BBCHK(p_grad_reduce(st, s, batch));
+    // The ordered final sums of the layer's partial rows ride in the weight-gradient launch where the
+    // grouped MFMA kernel runs it (its last tiles leave CUs idle); otherwise a launch of their own.
+    bool reduced = false;
+    BBCHK(p_gemm_group(st, s, wgrad, 4, &batch, &reduced));
+    if (!reduced) BBCHK(p_grad_reduce(st, s, batch));
     dy = dx;
   }
   return BAMBOO_OK;

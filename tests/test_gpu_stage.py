@@ -317,3 +317,35 @@ def test_single_stage_pipeline_without_replica(B):
         st.failover_merge(0)
     assert e.value.status == B.E_STATE
     st.stage_destroy()
+
+
+@pytest.mark.parametrize("name", ["bf16_post_ln", "bf16_causal_d128"])
+def test_gradients_do_not_depend_on_how_the_weight_gradients_are_launched(B, name):
+    """With a token count the grouped weight-gradient launch covers (a multiple of 64), the four weight
+    gradients of a layer and the ordered sums behind its bias / LayerNorm gradients go out as one launch;
+    with a forced 64 x 64 tile every GEMM is launched singly and the sums get a launch of their own.  Both
+    must match the oracle, and each other bitwise (the order of every sum is fixed by the data layout, not
+    by the launch)."""
+    sc = SMALL[name].replace(seq=128, micro_batch=2)
+    assert (sc.micro_batch * sc.seq) % 64 == 0 and sc.micro_batch * sc.seq >= 192
+    ref = None
+    grads = []
+    for tile in (0, 11):
+        B.bk_gemm_tile(tile)
+        try:
+            inp, st, hz = _build(B, sc)
+            hz.begin_iteration()
+            hz.run(st.stage_schedule())
+            hz.sync()
+        finally:
+            B.bk_gemm_tile(0)
+        if ref is None:
+            ref = _oracle(sc, inp)
+        check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, TOL[sc.dtype], "own, tile %d" % tile)
+        grads.append((st.own_g.clone(), hz.succ.own_g.clone(), [hz.gx[k].clone() for k in range(sc.M)]))
+        st.stage_destroy()
+        hz.succ.stage_destroy()
+    assert torch.equal(grads[0][0], grads[1][0])
+    assert torch.equal(grads[0][1], grads[1][1])
+    for a, b in zip(grads[0][2], grads[1][2]):
+        assert torch.equal(a, b)
