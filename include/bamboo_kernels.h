@@ -55,6 +55,19 @@ int bk_linear_bwd_weight_group(int dtype, int n, const int* T, const int* K, con
 int bk_colsum_acc(int dtype, int T, int N, const void* A, float* out, float* partial, void* stream);
 uint64_t bk_colsum_scratch_floats(int N);
 
+/* bk_colsum_acc for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same result as bk_colsum_acc (the same two kernels
+ * in the same order), but the partial rows live in a device array inside the library (2 MiB per GPU,
+ * held until the process ends) instead of a caller buffer; the call allocates and frees nothing.
+ * A, out: device pointers as for bk_colsum_acc (out is added to).  BAMBOO_E_ARG if the shape needs
+ * more than bk_colsum_static_max_floats() = 2^19 floats of partial rows (partial rows x N; the launch
+ * shape keeps that product below 2^18 until a single row exceeds the array, i.e. every N <= 524288
+ * fits with any T), decided before anything is launched.  All calls on one GPU share that GPU's array: calls that overlap on one GPU (two
+ * streams, two threads) race; calls on one stream, one after the other, are safe, and nothing needs
+ * clearing between them. */
+int bk_colsum_acc_static(int dtype, int T, int N, const void* A, float* out, void* stream);
+uint64_t bk_colsum_static_max_floats(void);
+
 /* Softmax attention.  qkv[T,3H] = queries | keys | values, head h = columns
  * h*d..(h+1)*d-1 of each third; scores scaled by 1/sqrt(d); causal != 0 masks
  * keys after the query.  ctx[T,H]; lse[batch,heads,seq] fp32 = log-sum-exp of

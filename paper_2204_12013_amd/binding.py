@@ -101,6 +101,8 @@ _SIGS = {
     "bk_linear_bwd_weight_group": (C.c_int, [C.c_int, C.c_int] + [C.POINTER(C.c_int)] * 3 + [C.POINTER(_vp)] * 3 + [_vp]),
     "bk_colsum_acc": (C.c_int, [C.c_int] * 3 + [_vp] * 4),
     "bk_colsum_scratch_floats": (C.c_uint64, [C.c_int]),
+    "bk_colsum_acc_static": (C.c_int, [C.c_int] * 3 + [_vp] * 3),
+    "bk_colsum_static_max_floats": (C.c_uint64, []),
     "bk_attention_fwd": (C.c_int, [C.c_int] * 7 + [_vp] * 4),
     "bk_attention_bwd": (C.c_int, [C.c_int] * 7 + [_vp] * 7),
     "bk_layernorm_fwd": (C.c_int, [C.c_int] * 3 + [_f32] + [_vp] * 6),
@@ -409,6 +411,12 @@ def bk_colsum_acc(A, out, stream=None):
     partial = torch.empty(int(lib.bk_colsum_scratch_floats(N)), dtype=torch.float32, device=A.device)
     _check(lib.bk_colsum_acc(_dt(A), T, N, _ptr(A), _ptr(out), _ptr(partial), _stream(stream)), "bk_colsum_acc")
     return partial
+
+
+def bk_colsum_acc_static(A, out, stream=None):
+    """bk_colsum_acc without any allocation: the partial rows live inside the library."""
+    T, N = A.shape
+    _check(lib.bk_colsum_acc_static(_dt(A), T, N, _ptr(A), _ptr(out), _stream(stream)), "bk_colsum_acc_static")
 
 
 def bk_attention_fwd(qkv, ctx, lse, batch, seq, heads, causal, impl=0, stream=None):

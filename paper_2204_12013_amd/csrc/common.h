@@ -164,6 +164,7 @@ bool grad_reduce_add(GradReduceBatch* b, int N, int parts, const float* p0, floa
 hipError_t launch_grad_reduce(hipStream_t s, const GradReduceBatch& b);
 int grad_reduce_blocks(const GradReduceBatch& b);   // workgroups (of 64 columns each) the batch needs
 size_t reduce_max_partials();
+int colsum_partial_rows(int dtype, int T, int N);   // partial rows launch_colsum_partials writes for this shape
 size_t colsum_partial_floats(int N);
 size_t ln_bwd_partial_floats(int H);
 hipError_t launch_bubble(hipStream_t s, float microseconds);

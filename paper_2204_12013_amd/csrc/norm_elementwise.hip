@@ -468,15 +468,26 @@ size_t reduce_max_partials() { return kMaxPartials; }
 size_t colsum_partial_floats(int N) { return (size_t)kMaxPartials * N; }
 size_t ln_bwd_partial_floats(int H) { return (size_t)2 * kMaxPartials * H; }
 
+// launch shape of the column-sum kernel: workgroups across the columns (64 vectors of V each), rows per
+// workgroup and workgroups along the token axis (= partial rows written)
+static void colsum_shape(int V, int T_rows, int N, int* col_blocks, int* rows_per_block, int* row_blocks) {
+  *col_blocks = (N + 64 * V - 1) / (64 * V);
+  int max_blocks = 512 / *col_blocks;           // about two workgroups per CU in total
+  if (max_blocks > kMaxPartials) max_blocks = kMaxPartials;
+  if (max_blocks < 1) max_blocks = 1;
+  split_rows(T_rows, max_blocks, rows_per_block, row_blocks);
+}
+int colsum_partial_rows(int dtype, int T, int N) {
+  int cb, rpb, rb;
+  colsum_shape(dtype == 0 ? Vec<float>::N : Vec<bf16_t>::N, T, N, &cb, &rpb, &rb);
+  return rb;
+}
+
 template <typename T>
 static hipError_t colsum_partials_impl(hipStream_t s, int T_rows, int N, const void* a, float* partial, int* parts) {
   constexpr int V = Vec<T>::N;
-  const int col_blocks = (N + 64 * V - 1) / (64 * V);
-  int max_blocks = 512 / col_blocks;            // about two workgroups per CU in total
-  if (max_blocks > kMaxPartials) max_blocks = kMaxPartials;
-  if (max_blocks < 1) max_blocks = 1;
-  int rpb, rb;
-  split_rows(T_rows, max_blocks, &rpb, &rb);
+  int col_blocks, rpb, rb;
+  colsum_shape(V, T_rows, N, &col_blocks, &rpb, &rb);
   hipLaunchKernelGGL((colreduce_kernel<T, 0>), dim3(col_blocks, rb), dim3(256), 0, s, T_rows, N, rpb, (const T*)a,
                      (const T*)nullptr, (const float*)nullptr, partial, (float*)nullptr);
   *parts = rb;
