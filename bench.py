@@ -49,27 +49,33 @@ def _replay_end(B, merged):
     return len(merged)
 
 
-def _profiled_traffic(workload):
-    """HBM bytes per stage-GEMM launch from the committed rocprofv3 counter summary
-    (FETCH_SIZE + WRITE_SIZE, scaled by the copy-kernel yardstick), or None."""
+def _profiled_traffic(workload, site):
+    """HBM bytes per launch of one launch site (or of the average stage-GEMM launch, site "stage_gemm") from
+    the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, each scaled by what the same counter
+    reads for the library's copy kernel of known size), or None where no summary covers it."""
     path = os.path.join(ROOT, "profiles", "%s_pmc_traffic.txt" % workload)
     try:
         for line in open(path):
-            if line.startswith("stage_gemm_traffic_bytes_per_launch="):
+            if line.startswith("%s_traffic_bytes_per_launch=" % site):
                 return int(line.split("=")[1])
     except OSError:
         pass
     return None
 
 
-def _cpu_baseline(sc, seconds_budget=20.0):
-    """The oracle as it stands, timed on the host: layers of this workload forward + backward on one
-    micro-batch (as many layer passes as fit the time budget, at least one, at most four times the
-    stage's layer count), extrapolated linearly to an iteration (flops are linear in layers x micro-batches)."""
+def _cpu_baseline(sc, seconds_budget=12.0, flop_rate_guess=2.0e11):
+    """The oracle as it stands (numpy/BLAS fp64), timed on the host: layers of this workload forward + backward
+    on one micro-batch -- as many layer passes as fit the time budget, at least one, at most four times the
+    stage's layer count --, extrapolated linearly to an iteration (flops are linear in layers x micro-batches).
+    Where one layer pass at the full sequence length would blow the budget (the large-layer stage: 4.5e13 flop),
+    the sample is a micro-batch of the same layer at a shorter sequence, scaled by the token count."""
     import numpy as np
     from oracle import layer as L
     from paper_2204_12013_amd import synth
-    one = sc.replace(n_own=1, n_shadow=0)
+    seq = sc.seq
+    while seq > 64 and 72.0 * sc.micro_batch * seq * sc.hidden ** 2 > seconds_budget * flop_rate_guess:
+        seq //= 2
+    one = sc.replace(n_own=1, n_shadow=0, seq=seq)
     inp = synth.make_stage_inputs(one, n_microbatches=1)
     p = L.unpack_layer(inp["own_w"][0].astype(np.float64), sc.hidden, sc.ffn)
     x = inp["x"][0].astype(np.float64)
@@ -79,21 +85,177 @@ def _cpu_baseline(sc, seconds_budget=20.0):
     # layers beyond the stage's own count are further samples of the same measurement (same shapes)
     while n < 4 * sc.n_own and (n == 0 or (t_f + t_b) * (n + 1) / n <= seconds_budget):
         t0 = time.perf_counter()
-        x, cache = L.layer_fwd(sc.arch, p, x, sc.micro_batch, sc.seq, sc.heads)
+        x, cache = L.layer_fwd(sc.arch, p, x, one.micro_batch, one.seq, sc.heads)
         t1 = time.perf_counter()
         g, _ = L.layer_bwd(sc.arch, p, cache, g)
         t2 = time.perf_counter()
         t_f, t_b, n = t_f + (t1 - t0), t_b + (t2 - t1), n + 1
-    t_iter = sc.M * (sc.n_own * (t_f + t_b) + sc.n_shadow * t_f) / n
+    scale = sc.seq / seq
+    t_iter = sc.M * (sc.n_own * (t_f + t_b) + sc.n_shadow * t_f) / n * scale
     try:
         import threadpoolctl
         cores = max([i.get("num_threads", 1) for i in threadpoolctl.threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
     return {"value": sc.M * sc.micro_batch / t_iter, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": "fp64 oracle, %d layer(s) forward (%.2f s) + backward (%.2f s) on 1 micro-batch of %s, "
-                      "extrapolated to the FRC-on iteration (%d micro-batches x (%d own fwd+bwd + %d replica fwd))"
-                      % (n, t_f, t_b, sc.name, sc.M, sc.n_own, sc.n_shadow)}
+            "sample": "fp64 oracle (numpy, matrix products through BLAS), %d layer(s) forward (%.2f s) + backward "
+                      "(%.2f s) on 1 micro-batch of %s%s, extrapolated to the FRC-on iteration (%d micro-batches x "
+                      "(%d own fwd+bwd + %d replica fwd))"
+                      % (n, t_f, t_b, sc.name,
+                         "" if seq == sc.seq else " cut to sequence length %d (times scaled by %d tokens / %d)"
+                         % (seq, sc.tokens, one.tokens), sc.M, sc.n_own, sc.n_shadow)}
+
+
+GEMM_SITES = ("gemm_qkv", "gemm_attn_out", "gemm_ffn1", "gemm_ffn2", "dgrad_ffn2", "dgrad_ffn1", "dgrad_attn_out",
+              "dgrad_qkv", "wgrad_group")
+SITE_KERNEL = {   # what each timed site launches
+    "gemm_qkv": "gemm_mfma_pl_kernel, forward form with bias (QKV projection)",
+    "gemm_attn_out": "gemm_mfma_pl_kernel, forward form with bias + residual (attention output projection)",
+    "gemm_ffn1": "gemm_mfma_pl_kernel, forward form with bias + GELU and its derivative (first FFN GEMM)",
+    "gemm_ffn2": "gemm_mfma_pl_kernel, forward form with bias + residual (second FFN GEMM)",
+    "dgrad_ffn2": "gemm_mfma_pl_kernel, input-gradient form times the stored GELU derivative, with column sums",
+    "dgrad_ffn1": "gemm_mfma_pl_kernel, input-gradient form (through the first FFN GEMM)",
+    "dgrad_attn_out": "gemm_mfma_pl_kernel, input-gradient form (through the attention output projection)",
+    "dgrad_qkv": "gemm_mfma_pl_kernel, input-gradient form (through the QKV projection)",
+    "wgrad_group": "gemm_mfma_pl_group_kernel: the four weight gradients of a layer in one launch, fp32 accumulate",
+}
+
+
+def _make_inputs(torch, synth, sc, dev):
+    """Parameters and per-micro-batch tensors of the workload's distributions, drawn on the device."""
+    act = torch.bfloat16 if sc.dtype == 1 else torch.float32
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(sc.seed)
+
+    def layer_stack(n):
+        H, F = sc.hidden, sc.ffn
+        out = []
+        for _ in range(n):
+            for name in synth.PARAM_NAMES:
+                numel = 1
+                for s_ in synth.param_shapes(H, F)[name]:
+                    numel *= s_
+                v = torch.randn(numel, generator=gen, device=dev, dtype=torch.float32) * 0.02
+                if name in ("g1", "g2"):
+                    v += 1.0
+                out.append(v.to(act))
+                del v
+        return torch.cat(out)
+    T, H, M = sc.tokens, sc.hidden, sc.M
+    own, shadow = layer_stack(sc.n_own), layer_stack(sc.n_shadow)
+    x = [torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32).to(act) for _ in range(M)]
+    gy = [(torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32) / (T * H) ** 0.5).to(act)
+          for _ in range(M)]
+    return gen, act, own, shadow, x, gy
+
+
+def _time_iters(torch, hz, prog, n, us_per_tick=0.0):
+    """n iterations of the instruction list, bracketed by device synchronisation; ms per iteration."""
+    hz.us_per_tick = us_per_tick
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        hz.begin_iteration(zero_grads=True)
+        hz.run(prog)
+    hz.sync()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / max(n, 1)
+
+
+def _site_profile(B, st, torch, hz, prog, k_p):
+    """The iteration again with an event pair around every launch, on the launch's own stream."""
+    st.stage_profile(True)
+    _time_iters(torch, hz, prog, k_p)
+    sites = {}
+    for i, name in enumerate(B.KERNEL_CLASSES):
+        ms, n, work = st.stage_profile_read(i)
+        if n:
+            sites[name] = {"launches": n, "avg_us": ms * 1e3 / n, "ms_per_step": ms / k_p, "rate": work / (ms * 1e-3),
+                           "work_per_launch": work / n}
+    st.stage_profile(False)
+    return sites
+
+
+def _roofline(sc, sites, k_p, two_lanes):
+    """`roofline` of one workload: the single launch site with the most time per iteration (the dominant
+    kernel), measured live (algorithmic flops per launch / average launch duration), beside the aggregate
+    over all stage GEMM launches, which is what the 60 % target is stated on."""
+    gemm = {k: v for k, v in sites.items() if k in GEMM_SITES}
+    dom = max(gemm, key=lambda k: gemm[k]["ms_per_step"])
+    d = gemm[dom]
+    g_ms = sum(v["avg_us"] * v["launches"] for v in gemm.values()) * 1e-3
+    g_work = sum(v["work_per_launch"] * v["launches"] for v in gemm.values())
+    g_n = sum(v["launches"] for v in gemm.values())
+    agg = g_work / (g_ms * 1e-3)
+    measured = ("HIP event pair around every launch of %d iteration(s), %s"
+                % (k_p, "FRC on (two lanes)" if two_lanes else "FRC off (one lane, no contention between lanes)"))
+    return {"kernel": SITE_KERNEL[dom], "site": dom, "bound": "mfma", "achieved": d["rate"] / 1e12,
+            "peak": PEAK["mfma_bf16"] / 1e12, "unit": "TFLOP/s", "frac": d["rate"] / PEAK["mfma_bf16"],
+            "traffic": _profiled_traffic(sc.name, dom), "avg_launch_us": d["avg_us"],
+            "flops_per_launch": d["work_per_launch"], "launches_per_step": d["launches"] // k_p,
+            "share_of_gemm_time": d["ms_per_step"] * k_p / g_ms,
+            "stage_gemms": {"achieved": agg / 1e12, "frac": agg / PEAK["mfma_bf16"], "launches_per_step": g_n // k_p,
+                            "avg_launch_us": g_ms * 1e3 / g_n, "flops_per_launch": g_work / g_n,
+                            "traffic": _profiled_traffic(sc.name, "stage_gemm")},
+            "measured": measured}
+
+
+def _kernel_table(sites, k_p):
+    flop_sites = GEMM_SITES + ("attn_fwd", "attn_bwd")
+    out = {}
+    for k, v in sites.items():
+        unit = "TFLOP/s" if k in flop_sites else "GB/s"
+        rate = v["rate"] / (1e12 if k in flop_sites else 1e9)
+        out[k] = {"avg_us": v["avg_us"], "launches_per_step": v["launches"] // k_p, "ms_per_step": v["ms_per_step"],
+                  unit: rate, "frac_of_peak": v["rate"] / (PEAK["mfma_bf16"] if k in flop_sites else PEAK["hbm"])}
+    return out
+
+
+def measure_core(B, synth, torch, sc, steps, warmup, two_lanes=False, cpu_baseline=True):
+    """Modes A, B, C, the per-site timing and the roofline of one workload; returns (record, live objects)."""
+    from paper_2204_12013_amd.harness import StageHarness
+    dev = torch.device("cuda:0")
+    gen, act, own, shadow, x, gy = _make_inputs(torch, synth, sc, dev)
+    cfg = B.make_cfg(sc, frc_enabled=True)
+    st = B.Stage(cfg, own, shadow)
+    del own, shadow
+    M = sc.M
+    torch.cuda.synchronize()
+    hz = StageHarness(st, x, gz=gy, gy_table=gy)
+    prog_on = st.stage_schedule()
+    prog_off = [i for i in prog_on if i[0] != B.FRC]
+    _time_iters(torch, hz, prog_on, warmup)
+    ms_on = _time_iters(torch, hz, prog_on, steps)                       # mode B: the headline
+    rec = {"value": M * sc.micro_batch / (ms_on * 1e-3), "unit": "samples/s", "steps": steps, "warmup": warmup,
+           "ms_per_step": ms_on, "dtype": "bf16" if sc.dtype == 1 else "f32",
+           "config": {"workload": sc.name, "arch": "post-LN encoder" if sc.arch == 0 else "pre-LN causal decoder",
+                      "hidden": sc.hidden, "heads": sc.heads, "ffn": sc.ffn, "seq": sc.seq,
+                      "micro_batch": sc.micro_batch, "micro_batches": M, "own_layers": sc.n_own,
+                      "replica_layers": sc.n_shadow, "pipeline_depth": sc.P, "stage_id": sc.stage_id,
+                      "mode": "B: FRC on, no simulated bubbles"}}
+    rec["mfma_util_end_to_end"] = _iteration_flops(sc, True) / (ms_on * 1e-3) / PEAK["mfma_bf16"]
+    _time_iters(torch, hz, prog_off, 1)
+    ms_off = _time_iters(torch, hz, prog_off, steps)                     # mode A
+    rec["samples_per_s_frc_off"] = M * sc.micro_batch / (ms_off * 1e-3)
+    rec["ms_per_step_frc_off"] = ms_off
+    rec["frc_overhead_pct_no_bubbles"] = 100.0 * (ms_on - ms_off) / ms_off
+    # mode C: bubbles sized from the failure-free iteration (one tick = one forward)
+    us_per_tick = ms_off * 1e3 / (M * (cfg.tick_F + cfg.tick_B))
+    k_c = max(2, min(steps, 5))
+    ms_c_off = _time_iters(torch, hz, prog_off, k_c, us_per_tick)
+    ms_c_on = _time_iters(torch, hz, prog_on, k_c, us_per_tick)
+    rec["bubble_mode"] = {"us_per_tick": us_per_tick, "ms_per_step_frc_off": ms_c_off, "ms_per_step_frc_on": ms_c_on,
+                          "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
+    if sc.dtype == 1:
+        k_p = max(1, min(steps, 3))
+        sites = _site_profile(B, st, torch, hz, prog_on if two_lanes else prog_off, k_p)
+        rec["roofline"] = _roofline(sc, sites, k_p, two_lanes)
+        rec["mfma_util_stage_gemms"] = rec["roofline"]["stage_gemms"]["frac"]
+        rec["kernel_sites"] = _kernel_table(sites, k_p)
+    live = {"st": st, "hz": hz, "x": x, "gy": gy, "gen": gen, "act": act, "prog_on": prog_on, "prog_off": prog_off,
+            "ms_on": ms_on, "ms_off": ms_off, "ms_c_on": ms_c_on, "us_per_tick": us_per_tick, "k_c": k_c, "cfg": cfg}
+    rec["cpu_baseline"] = None
+    return rec, live
 
 
 def main():
@@ -101,11 +263,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="bert_large_stage")
+    ap.add_argument("--workload", default="bert_large_stage", help="the headline workload (value, ms_per_step)")
+    ap.add_argument("--also", default="gpt2_1p5b_stage,large_layer_stage,tiny",
+                    help="further workloads reported as sub-records under `workloads` (comma-separated, may be empty)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extra-modes", action="store_true", help="time mode B only (for profiler runs)")
+    ap.add_argument("--no-extra-modes", action="store_true",
+                    help="time modes A, B, C and the per-site pass of the headline workload only (profiler runs)")
     ap.add_argument("--profile-two-lanes", action="store_true",
-                    help="run the per-kernel-class pass with FRC on (two lanes: a kernel's event time then "
+                    help="run the per-site pass with FRC on (two lanes: a kernel's event time then "
                          "includes the time it shares the GPU with the other lane's kernels)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 256 MiB device copy (yardstick for the HBM byte counters)")
@@ -123,77 +288,15 @@ def main():
         return 3
     sc = synth.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
-    act = torch.bfloat16 if sc.dtype == 1 else torch.float32
-    gen = torch.Generator(device=dev)
-    gen.manual_seed(sc.seed)
-
-    def layer_stack(n):
-        """n layers drawn on the device with the workload's distributions."""
-        H, F = sc.hidden, sc.ffn
-        out = []
-        for _ in range(n):
-            for name in synth.PARAM_NAMES:
-                shp = synth.param_shapes(H, F)[name]
-                numel = 1
-                for s_ in shp:
-                    numel *= s_
-                v = torch.randn(numel, generator=gen, device=dev, dtype=torch.float32) * 0.02
-                if name in ("g1", "g2"):
-                    v += 1.0
-                out.append(v.to(act))
-        return torch.cat(out)
-
-    cfg = B.make_cfg(sc, frc_enabled=True)
-    st = B.Stage(cfg, layer_stack(sc.n_own), layer_stack(sc.n_shadow))
+    rec, live = measure_core(B, synth, torch, sc, args.steps, args.warmup, args.profile_two_lanes)
+    st, hz, x, gy, gen, act = (live[k] for k in ("st", "hz", "x", "gy", "gen", "act"))
+    cfg, ms_on, ms_off, ms_c_on, us_per_tick, k_c = (live[k] for k in ("cfg", "ms_on", "ms_off", "ms_c_on", "us_per_tick", "k_c"))
     T, H, M = sc.tokens, sc.hidden, sc.M
-    x = [torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32).to(act) for _ in range(M)]
-    gy = [(torch.randn(T, H, generator=gen, device=dev, dtype=torch.float32) / (T * H) ** 0.5).to(act)
-          for _ in range(M)]
-    torch.cuda.synchronize()
-    hz = StageHarness(st, x, gz=gy, gy_table=gy)
-    prog_on = st.stage_schedule()
-    prog_off = [i for i in prog_on if i[0] != B.FRC]
-
-    def run_iters(prog, n, us_per_tick=0.0):
-        hz.us_per_tick = us_per_tick
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n):
-            hz.begin_iteration(zero_grads=True)
-            hz.run(prog)
-        hz.sync()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / max(n, 1)
-
-    run_iters(prog_on, args.warmup)
-    ms_on = run_iters(prog_on, args.steps)                       # mode B: the headline
     out = {"metric": "stage samples/s (FRC on/off), FRC overhead %, MFMA util vs bf16 peak",
-           "value": M * sc.micro_batch / (ms_on * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
-           "warmup": args.warmup, "ms_per_step": ms_on, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "bf16" if sc.dtype == 1 else "f32", "data": "synthetic",
-           "config": {"workload": sc.name, "arch": "post-LN encoder" if sc.arch == 0 else "pre-LN causal decoder",
-                      "hidden": sc.hidden, "heads": sc.heads, "ffn": sc.ffn, "seq": sc.seq,
-                      "micro_batch": sc.micro_batch, "micro_batches": M, "own_layers": sc.n_own,
-                      "replica_layers": sc.n_shadow, "pipeline_depth": sc.P, "stage_id": sc.stage_id,
-                      "mode": "B: FRC on, no simulated bubbles"}}
-    flops_on = _iteration_flops(sc, True)
-    out["mfma_util_end_to_end"] = flops_on / (ms_on * 1e-3) / PEAK["mfma_bf16"]
-
-    if not args.no_extra_modes:
-        run_iters(prog_off, 1)
-        ms_off = run_iters(prog_off, args.steps)                 # mode A
-        out["samples_per_s_frc_off"] = M * sc.micro_batch / (ms_off * 1e-3)
-        out["ms_per_step_frc_off"] = ms_off
-        out["frc_overhead_pct_no_bubbles"] = 100.0 * (ms_on - ms_off) / ms_off
-        # mode C: bubbles sized from the failure-free forward time (one tick = one forward)
-        n_fwd_bwd = M * (cfg.tick_F + cfg.tick_B)
-        us_per_tick = ms_off * 1e3 / n_fwd_bwd
-        k_c = max(2, min(args.steps, 5))
-        ms_c_off = run_iters(prog_off, k_c, us_per_tick)
-        ms_c_on = run_iters(prog_on, k_c, us_per_tick)
-        out["bubble_mode"] = {"us_per_tick": us_per_tick, "ms_per_step_frc_off": ms_c_off,
-                              "ms_per_step_frc_on": ms_c_on,
-                              "frc_overhead_pct": 100.0 * (ms_c_on - ms_c_off) / ms_c_off, "steps": k_c}
+           "value": rec["value"], "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": rec["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": rec["dtype"], "data": "synthetic"}
+    out.update({k: v for k, v in rec.items() if k not in out})
 
     # The redundant-computation variants of the paper's microbenchmarks (Section 7.4, Table 4) on this
     # stage, in bubble mode: time of a failure-free iteration relative to running nothing redundant, and
@@ -279,31 +382,49 @@ def main():
         out["rc_variants"] = {"mode": "simulated bubbles, %d iterations each, preemption at micro-batch %d" % (k_c, k_fail),
                               **variants}
 
-    # Pure data parallelism (Section 5.2 "over-batching", Section 7.6): there is no bubble, so eager FRC means
-    # that a node also processes its neighbour's minibatch, i.e. twice the batch; the paper reports about 1.5x
-    # the time on its GPUs.  Measured here as the own layers' forward + backward at twice the micro-batch.
+    # Pure data parallelism (Section 5.2 "Support for Pure Data Parallelism", Section 7.6): the node holds the
+    # whole model (here: the own layers) and the replica of a peer's model; there is no bubble, so eager FRC is
+    # over-batching: the forward of the peer's minibatch beside the node's own.  The paper reports about 1.5x
+    # the time for twice the batch on its GPUs.  Measured with the library's data-parallel mode: iteration
+    # without redundancy, with eager FRC on the second lane, the merged node after the peer is lost (both
+    # minibatches forward and backward), and the pause (BRC over the whole iteration's stash).
     if not args.no_extra_modes:
-        sc2 = sc.replace(micro_batch=2 * sc.micro_batch, n_shadow=0, stage_id=sc.P - 1)
-        s2 = B.Stage(B.make_cfg(sc2, frc_enabled=False), st.own_w, None)
-        x2 = [torch.cat([x[k], x[(k + 1) % M]]) for k in range(M)]
-        g2 = [torch.cat([gy[k], gy[(k + 1) % M]]) for k in range(M)]
-        h2 = StageHarness(s2, x2, gz=g2, gy_table=g2)
-        p2 = [i for i in s2.stage_schedule() if i[0] != B.BUBBLE]
-        t2 = None
-        for n_ in (1, k_c):
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(n_):
-                h2.begin_iteration(zero_grads=True)
-                h2.run(p2)
-            h2.sync()
-            torch.cuda.synchronize()
-            t2 = (time.perf_counter() - t0) * 1e3 / n_
-        out["over_batching"] = {"ms_per_step_batch": ms_off, "ms_per_step_twice_the_batch": t2,
-                                "time_ratio": t2 / ms_off}
-        s2.stage_destroy()
-        del s2, h2, x2, g2
-        torch.cuda.empty_cache()
+        from paper_2204_12013_amd.harness import split_at_failure
+        scd = sc.replace(P=1, stage_id=0, n_shadow=sc.n_own)
+        xn = [x[(k + 1) % M] for k in range(M)]
+        dp = {}
+        for label, mode in (("no_redundancy", B.RC_LFLB), ("eager_frc", B.RC_EFLB)):
+            sd = B.Stage(B.make_cfg(scd, rc_mode=mode, data_parallel=1), st.own_w, st.own_w.clone())
+            hd = StageHarness(sd, x, gz=gy, gy_table=gy, frc_in=xn)
+            pd = sd.stage_schedule()
+            _time_iters(torch, hd, pd, 1)
+            dp[label] = _time_iters(torch, hd, pd, k_c)
+            if mode == B.RC_EFLB:
+                hd.begin_iteration(zero_grads=True)
+                hd.run(split_at_failure(pd, M - 1))
+                merged = sd.failover_merge(M - 1)
+                first_group = _replay_end(B, merged)
+                hd.sync()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                hd.run(merged[:first_group])
+                hd.sync()
+                torch.cuda.synchronize()
+                dp["pause_ms"] = (time.perf_counter() - t0) * 1e3
+                hd.run(merged[first_group:])
+                hd.sync()
+                hd.begin_iteration(zero_grads=True)      # the merged node's whole-iteration program is installed here
+                pm = sd.stage_schedule()
+                _time_iters(torch, hd, pm, 1)
+                dp["merged_node"] = _time_iters(torch, hd, pm, k_c)
+            sd.stage_destroy()
+            del sd, hd
+            torch.cuda.empty_cache()
+        out["data_parallel"] = {"ms_per_step_no_redundancy": dp["no_redundancy"], "ms_per_step_eager_frc": dp["eager_frc"],
+                                "eager_frc_time_ratio": dp["eager_frc"] / dp["no_redundancy"],
+                                "ms_per_step_merged_node_two_minibatches": dp["merged_node"],
+                                "merged_node_time_ratio": dp["merged_node"] / dp["no_redundancy"],
+                                "pause_ms_peer_lost_at_end_of_iteration": dp["pause_ms"]}
 
     # Swap-out of the FRC results to host memory (Section 5.2; Section 7.4 puts the GPU-memory cost of eager
     # FRC at about 1.5x): the device keeps a ring of two shadow slots, every FRC's records go to pinned host
@@ -497,38 +618,6 @@ def main():
                          "replica_sync_GB/s": 2.0 * n_sh * (12.0 + es) / (t_sync * 1e-3) / 1e9,
                          "parameters_own": n_own, "parameters_replica": n_sh}
 
-    # per-kernel-class roofline: the iteration again with an event pair around every launch, on the
-    # launch's own stream.  By default FRC is left out of this pass: with two lanes active a kernel
-    # shares the GPU with the other lane's kernels and its event time is no longer its own.
-    st.stage_profile(True)
-    k_p = max(1, min(args.steps, 3))
-    run_iters(prog_on if args.profile_two_lanes else prog_off, k_p)
-    classes = {}
-    for i, name in enumerate(B.KERNEL_CLASSES):
-        ms, n, work = st.stage_profile_read(i)
-        if n:
-            classes[name] = {"launches": n, "avg_us": ms * 1e3 / n, "total_ms_per_step": ms / k_p,
-                             "rate": work / (ms * 1e-3), "work_per_launch": work / n}
-    st.stage_profile(False)
-    gemm = [classes[c] for c in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if c in classes]
-    g_ms = sum(c["avg_us"] * c["launches"] for c in gemm) * 1e-3
-    g_work = sum(c["work_per_launch"] * c["launches"] for c in gemm)
-    g_n = sum(c["launches"] for c in gemm)
-    achieved = g_work / (g_ms * 1e-3) / 1e12
-    out["roofline"] = {"kernel": "stage GEMMs (forward, input-gradient, weight-gradient launches)", "bound": "mfma",
-                       "achieved": achieved, "peak": PEAK["mfma_bf16"] / 1e12, "unit": "TFLOP/s",
-                       "frac": achieved * 1e12 / PEAK["mfma_bf16"], "traffic": _profiled_traffic(sc.name),
-                       "launches_per_step": g_n // k_p, "avg_launch_us": g_ms * 1e3 / g_n,
-                       "flops_per_launch": g_work / g_n,
-                       "measured": "HIP event pair around every GEMM launch of %d iteration(s), %s"
-                                   % (k_p, "FRC on (two lanes)" if args.profile_two_lanes else
-                                      "FRC off (one lane, no contention between lanes)")}
-    out["mfma_util_stage_gemms"] = out["roofline"]["frac"]
-    out["kernel_classes"] = {
-        k: {"avg_us": v["avg_us"], "launches_per_step": v["launches"] // k_p, "ms_per_step": v["total_ms_per_step"],
-            ("TFLOP/s" if k.startswith(("gemm", "attn")) else "GB/s"):
-                v["rate"] / (1e12 if k.startswith(("gemm", "attn")) else 1e9)}
-        for k, v in classes.items()}
     if args.calibration_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
@@ -538,12 +627,26 @@ def main():
         torch.cuda.synchronize()
         del a, b
     st.stage_destroy()
-    del st, hz
+    del st, hz, x, gy, live
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(sc)
-    else:
-        out["cpu_baseline"] = None
+
+    # The other workloads of the table, each with its own modes A / B / C, roofline and host baseline (fewer
+    # steps where an iteration is long; the fp32 tiny workload is a correctness configuration: times only).
+    others = {}
+    for name in [n for n in args.also.split(",") if n and n != sc.name]:
+        so = synth.CONFIGS[name]
+        est_ms = ms_on * _iteration_flops(so, True) / _iteration_flops(sc, True)     # about 4 s of mode B each
+        steps_o = max(3, min(args.steps, int(4000.0 / max(est_ms, 1e-3))))
+        r, lv = measure_core(B, synth, torch, so, steps_o, max(1, min(args.warmup, 2)), args.profile_two_lanes)
+        lv["st"].stage_destroy()
+        del lv
+        torch.cuda.empty_cache()
+        if not args.no_cpu_baseline and so.dtype == 1:
+            r["cpu_baseline"] = _cpu_baseline(so, seconds_budget=8.0)
+        others[name] = r
+    out["workloads"] = others
     print(json.dumps(out))
     return 0
 

@@ -90,18 +90,6 @@ int bk_layernorm_bwd(int dtype, int T, int H, const void* dout, const void* r, c
                      const void* add, void* dr, float* dgamma, float* dbeta, float* partial, void* stream);
 uint64_t bk_layernorm_bwd_scratch_floats(int H);
 
-/* Measurement aid (not part of the method): plain device copy of `bytes` bytes
- * (multiple of 16, 16-byte aligned pointers).  Its known traffic calibrates the
- * HBM byte counters read for the other kernels. */
-int bk_copy(const void* src, void* dst, uint64_t bytes, void* stream);
-
-/* Tuning and test aid (not part of the method): choose the output tile of the MFMA
- * GEMM kernel for all later calls in this process.  code = 10*WM + WN selects a
- * (64*WM) x (64*WN) tile, one of 44, 42, 24, 22, 11; 0 restores the automatic
- * choice.  Returns the previous code, or BAMBOO_E_ARG for a code that is not
- * offered.  Not thread-safe against concurrent launches. */
-int bk_gemm_tile(int code);
-
 /* One Adam step (Section 7 names the optimizer) over n parameters, n a multiple of 4, step >= 1:
  * g fp32 gradient; master, m, v fp32 master weights and moments, updated in place; w[n] (storage
  * dtype) = the new master weights rounded to storage.  All device pointers, 16-byte aligned. */
@@ -130,12 +118,6 @@ int bk_softmax_xent_bwd(int dtype, int T, int V, const void* logits, const int32
                         float scale, void* dlogits, void* stream);
 /* out[0] = scale * (in[0] + ... + in[n-1]) in a fixed order (the mean loss of a micro-batch). */
 int bk_ordered_sum(int64_t n, const float* in, float scale, float* out, void* stream);
-
-/* Tuning and test hook: force the depth of the LDS slice ring of the pipelined MFMA
- * GEMM kernel (2, 3 or 4 buffers; a depth that does not fit the tile's LDS budget
- * or exceeds the number of K slices falls back to the next smaller one); 0 restores
- * the automatic choice.  Returns the previous value, or BAMBOO_E_ARG. */
-int bk_gemm_stages(int n);
 
 #ifdef __cplusplus
 }

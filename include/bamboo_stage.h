@@ -95,6 +95,12 @@ typedef struct {
                           stage's (Section 5.1: the last node is the first node's predecessor and fetches
                           the input samples itself).  FRC(k) then does not depend on FWD(k), and the
                           failover schedule is the wrap-around one.  Only with rc_mode EFLB.  0 otherwise. */
+  int32_t data_parallel; /* 1: pure data parallelism (Section 5.2, "Support for Pure Data Parallelism"): the
+                          node holds the whole model (P == 1, stage_id == 0) and its replica layers are a
+                          copy of ANOTHER node's model (n_shadow == n_own).  There is no bubble: eager FRC
+                          is "over-batching", FRC(k) runs the other node's micro-batch k (the caller passes
+                          it as `y`) beside the node's own and does not depend on FWD(k); BRC(k) takes
+                          the other node's upstream gradient.  rc_mode LFLB or EFLB.  0 otherwise. */
 } bamboo_cfg_t;
 
 /* Instruction set: the paper's computation and communication instructions
@@ -177,6 +183,16 @@ int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const i
  * Same out/cap/return convention as stage_program. */
 int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
 
+/* A whole iteration of the stage AFTER it has taken over the victim's layers (Section 5.2: until the
+ * pipeline is reconfigured, the shadow node executes all of the victim's instructions): the stage's
+ * own 1F1B order with the victim's computation of the same micro-batch merged in under rules 1-4
+ * -- the last part of stage_failover_program started at the first computation, with nothing to
+ * join and nothing to replay; FRC and BRC run on lane 0; no bubbles are simulated.  With cfg.wrap:
+ * both ends' computations merged by failure-free start time as in the wrap-around failover
+ * schedule.  With cfg.data_parallel: both nodes' minibatches, no communication.  Same
+ * out/cap/return convention as stage_program; BAMBOO_E_STATE where there is nothing to take over. */
+int stage_merged_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap);
+
 /* With cfg.wrap the victim is the first stage and the shadow the last.  The two are the two ends of
  * the pipeline, so no traffic between them turns internal (unless P == 2).  stage_failover_program
  * then returns: JOIN up to FRC(k_fail); BRC replay of the micro-batches the victim had
@@ -237,7 +253,8 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
 int stage_schedule(const bamboo_stage_t* st, bamboo_instr_t* out, int32_t cap);
 
 /* Forget all stash contents and events: start of a new iteration.  Does not
- * touch gradients.  After failover_merge the stage stays merged. */
+ * touch gradients.  After failover_merge the stage stays merged, and from the first
+ * stage_begin_iteration after the merge on stage_schedule returns stage_merged_program. */
 int stage_begin_iteration(bamboo_stage_t* st);
 
 /* FNC_s(k): y = own layers(x) on lane 0; intermediates go to own slot k mod c_own.
@@ -257,16 +274,65 @@ int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z);
  * Frees the slot. */
 int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx);
 
-/* BRC(k): gy = shadow backward(gz) on lane 0 from shadow slot k; shadow_g +=.
- * gy may be NULL (replayed micro-batch whose own backward already ran).  Only
- * valid after failover_merge.  Frees the slot. */
+/* BRC(k): gy = shadow backward(gz) from shadow slot k; shadow_g +=.  gy may be NULL (a replayed
+ * micro-batch whose own backward already ran, or eager BRC beside a live successor, whose g_y is the
+ * successor's to deliver).  Lazy BRC (rc_mode LFLB, EFLB; Section 5.2) is valid only after
+ * failover_merge and runs on lane 0, behind the FRC of the same micro-batch.  Eager BRC (rc_mode
+ * EFEB; Section 7.4) is also valid before a preemption and then runs on lane 1, behind FRC(k) in
+ * that lane's order; after failover_merge it runs on lane 0 like the lazy one.  BAMBOO_E_STATE when
+ * neither applies or slot k holds no FRC results.  Frees the slot. */
 int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy);
 
 /* The successor was found dead while handing over micro-batch k_fail: lane 0
  * waits for the FRC lane, the stage switches to merged mode (FRC on lane 0, BRC
- * allowed) and the failover schedule is written to out.  BAMBOO_E_STATE when
- * called twice or with n_shadow == 0.  Returns the instruction count. */
+ * allowed) and the failover schedule is written to out (host array of cap entries).
+ * BAMBOO_E_STATE when called twice or with n_shadow == 0; BAMBOO_E_ARG when out is
+ * NULL or cap is too small -- the stage is then left as it was (ask
+ * stage_failover_program for the count beforehand: it has no side effects).
+ * Returns the instruction count. */
 int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap);
+
+/* ---- interpreting an instruction list inside the library ---------------------------------
+ * Section 4: a worker interprets its static schedule, instruction by instruction; a communication
+ * instruction is where a lost neighbour shows.  stage_run does that for a list produced by
+ * stage_schedule / failover_merge: every computation instruction becomes the call named beside it,
+ * on the buffers of its micro-batch; communication instructions, which on one GPU move nothing,
+ * are handed to the caller's hook, which stands for the neighbours.
+ *   FWD(k)  stage_fwd(k, x[k], y[k])
+ *   FRC(k)  shadow_fwd_frc(k, frc_in ? frc_in[k] : y[k], z ? z[k] : NULL)
+ *   BWD(k)  stage_bwd(k, gy[k], gx[k])
+ *   BRC(k)  before a merge (eager BRC beside a live successor): shadow_bwd_brc(k, gz[k], NULL);
+ *           after it: shadow_bwd_brc(k, gz[k], gy[k]) -- the gradient the victim would have sent --
+ *           unless BWD(k) already ran in this iteration (a replayed micro-batch) or the victim is a
+ *           data-parallel peer (its input gradient feeds nothing here): then the output goes to
+ *           gy_replay[k], or nowhere if gy_replay is NULL
+ *   BUBBLE  stage_bubble(ticks, us_per_tick) if us_per_tick > 0       JOIN  stage_join
+ *   APPLY   stage_apply(adam, ++step) if adam != NULL and stage_optimizer_init has been called
+ *   RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, ALLREDUCE: comm(user, &instruction) if comm != NULL;
+ *           a nonzero return means the peer is gone: stage_run stops BEFORE that instruction and
+ *           returns its index, and the caller goes on with failover_merge.
+ * All table entries are device pointers to [tokens, hidden] tensors in the storage dtype, M per
+ * table, owned by the caller; tables whose instructions do not occur in the list may be NULL
+ * (BAMBOO_E_ARG if one that is needed is).  BAMBOO_E_STATE for a stage with cfg.wrap, whose
+ * instructions are pairs of calls into the stage and the model's ends (bamboo_ends.h) that the
+ * caller composes.  Returns n when the whole list has been issued, the
+ * index of the refused communication instruction, or a negative status from the failing call. */
+typedef int (*bamboo_comm_fn)(void* user, const bamboo_instr_t* instr);
+typedef struct {
+  const void* const* x;       /* inputs of FWD (stand for RECV_ACT from stage s-1) */
+  void* const* y;             /* outputs of FWD */
+  const void* const* frc_in;  /* inputs of FRC when they are not y (data parallel: the peer's minibatch), or NULL */
+  void* const* z;             /* outputs of FRC, or NULL */
+  void* const* gy;            /* gradients at y: read by BWD; written by BRC once merged */
+  void* const* gx;            /* outputs of BWD */
+  const void* const* gz;      /* upstream gradients of the replica's layers, read by BRC */
+  void* const* gy_replay;     /* outputs of replayed BRCs, or NULL */
+  float us_per_tick;          /* length of one simulated bubble tick; 0: bubbles are skipped */
+  const bamboo_adam_t* adam;  /* hyper-parameters for APPLY, or NULL: APPLY is skipped */
+  bamboo_comm_fn comm;        /* hook for communication instructions, or NULL */
+  void* user;
+} bamboo_tables_t;
+int stage_run(bamboo_stage_t* st, const bamboo_instr_t* program, int32_t n, const bamboo_tables_t* tables);
 
 /* ---- the APPLY instruction and the replica's weight synchronisation ----------------------
  * Section 5.1: node n keeps a replica of node n+1's layers together with their optimizer state,
@@ -319,26 +385,6 @@ int stage_join(bamboo_stage_t* st);
 
 /* JOIN and block the host until all lanes are idle. */
 int stage_sync(bamboo_stage_t* st);
-
-/* Per-kernel-class timing for roofline measurements (not part of the method).
- * stage_profile(st, 1) clears earlier records and brackets every later kernel
- * launch with a HIP event pair on the launch's own stream; stage_profile(st, 0)
- * stops.  stage_profile_read synchronises, then reports for one class the summed
- * launch durations in ms, the number of launches and the summed algorithmic work
- * (flops for GEMM and attention classes, bytes for the others). */
-enum bamboo_kernel_class {
-  BAMBOO_K_GEMM_FWD = 0,   /* Y = X W (+bias, residual, GELU) */
-  BAMBOO_K_GEMM_DGRAD = 1, /* dX = dY W^T */
-  BAMBOO_K_GEMM_WGRAD = 2, /* dW += X^T dY */
-  BAMBOO_K_ATTN_FWD = 3,
-  BAMBOO_K_ATTN_BWD = 4,
-  BAMBOO_K_LN_FWD = 5,
-  BAMBOO_K_LN_BWD = 6,
-  BAMBOO_K_COLSUM = 7,
-  BAMBOO_K_COUNT = 8
-};
-int stage_profile(bamboo_stage_t* st, int enable);
-int stage_profile_read(bamboo_stage_t* st, int32_t kernel_class, double* total_ms, int64_t* launches, double* work);
 
 int stage_destroy(bamboo_stage_t* st);
 

@@ -165,48 +165,23 @@ def prefix_until_failure(P, s, M, k_fail, frc=True, tick_F=1, tick_B=2, bubbles=
     return prog[:last + 1]
 
 
-def failover_program(P, s, M, k_fail, rc=EFLB):
-    """Failover schedule of shadow stage s after its successor s+1 is lost while
-    stage s tries to send it the activation of micro-batch k_fail.
-
-    rc = EFLB is the paper's design and the description below.  With EFEB step (ii) is empty
-    (BRC of those micro-batches already ran, eagerly).  With LFLB nothing redundant has been
-    computed yet: step (ii) runs FRC before each BRC, and the FRC of the micro-batches the
-    victim had forwarded but not yet back-propagated follows before step (iii) -- this is the
-    longer pause that eager FRC avoids (Section 7.4).
-
-    (i)   wait for the FRC stream up to FRC(k_fail);
-    (ii)  replay: BRC over the micro-batches whose successor-side backward had
-          already run (their weight-gradient contributions died with the victim);
-    (iii) the rest of stage s's 1F1B program with the victim's groups merged in:
-          communication first, victim<->shadow traffic removed, the victim's
-          external traffic before the shadow's, backward work before forward work.
-    """
-    assert 0 <= s < P - 1 and 0 <= k_fail < M
-    seq = compute_order(P, s, M)
-    C = own_slots(P, s, M)
-    has_far = s + 2 < P                     # the victim had a successor of its own
-    b = lost_backwards(P, s, M, k_fail)
-    prog = [(JOIN, 0, -1, k_fail)]
-    if rc != EFEB:
-        for k in range(b):
-            if has_far:
-                prog.append((RECV_GRAD, 0, k, s + 2))
-            if rc == LFLB:
-                prog.append((FRC, 0, k, k))
-            prog.append((BRC, 0, k, k))
-    if rc == LFLB:
-        prog += [(FRC, 0, k, k) for k in range(b, k_fail + 1)]
-    rest = seq[seq.index(("F", k_fail)) + 1:]
-    # groups: a backward starts a new group; a forward joins the group of the
-    # backward just before it (backward work is ordered first inside a group)
+def _merge_groups(rest, C, s, has_far, unsent_act):
+    """Rules (1)-(4) of Section 5.2 over the 1F1B computations in `rest`: the instruction list of the
+    shadow stage doing its own work and the victim's, up to (not including) the closing
+    JOIN / ALLREDUCE / APPLY.  A backward opens a group and the forward that follows it in 1F1B order
+    joins that group; inside a group communication comes first -- the victim's external traffic (with
+    the stage after it, if has_far) before the shadow's own (with stage s-1, if s > 0), traffic between
+    victim and shadow is gone --, then backward work (victim's BRC, own BWD), then forward work (own
+    FWD, victim's FRC, now on lane 0).  unsent_act: FRC outputs the stage after the victim still has
+    to be sent when the list starts."""
+    prog = []
     groups = []
     for item in rest:
         if item[0] == "B" or not groups or groups[-1][-1][0] == "F":
             groups.append([item])
         else:
             groups[-1].append(item)
-    unsent_act = [k_fail]                   # FRC outputs the far stage has not got
+    unsent_act = list(unsent_act)           # FRC outputs the far stage has not got
     unsent_grad = []                        # own input-gradients not yet sent back
     for grp in groups + [[]]:
         # victim's external communication first
@@ -234,8 +209,65 @@ def failover_program(P, s, M, k_fail, rc=EFLB):
                 prog.append((FWD, 0, k, k % C))
                 prog.append((FRC, 0, k, k))
                 unsent_act.append(k)
+    return prog
+
+
+def failover_program(P, s, M, k_fail, rc=EFLB, data_parallel=False):
+    """Failover schedule of shadow stage s after its successor s+1 is lost while
+    stage s tries to send it the activation of micro-batch k_fail.
+
+    rc = EFLB is the paper's design and the description below.  With EFEB step (ii) is empty
+    (BRC of those micro-batches already ran, eagerly).  With LFLB nothing redundant has been
+    computed yet: step (ii) runs FRC before each BRC, and the FRC of the micro-batches the
+    victim had forwarded but not yet back-propagated follows before step (iii) -- this is the
+    longer pause that eager FRC avoids (Section 7.4).
+
+    (i)   wait for the FRC stream up to FRC(k_fail);
+    (ii)  replay: BRC over the micro-batches whose successor-side backward had
+          already run (their weight-gradient contributions died with the victim);
+    (iii) the rest of stage s's 1F1B program with the victim's groups merged in:
+          communication first, victim<->shadow traffic removed, the victim's
+          external traffic before the shadow's, backward work before forward work.
+
+    data_parallel (Section 5.2, "Support for Pure Data Parallelism"): the node holds the whole model
+    (P = 1) and the victim is the node whose replica it keeps, working through the same schedule on
+    its own minibatch; the loss is noticed after FWD(k_fail) and its FRC as above.  Nothing is
+    exchanged between the two before the all-reduce, so the schedule has no communication at all.
+    """
+    if data_parallel:
+        assert P == 1 and s == 0 and 0 <= k_fail < M and rc != EFEB
+    else:
+        assert 0 <= s < P - 1 and 0 <= k_fail < M
+    seq = compute_order(P, s, M)
+    C = own_slots(P, s, M)
+    has_far = s + 2 < P                     # the victim had a successor of its own
+    b = lost_backwards(P, s, M, k_fail)
+    prog = [(JOIN, 0, -1, k_fail)]
+    if rc != EFEB:
+        for k in range(b):
+            if has_far:
+                prog.append((RECV_GRAD, 0, k, s + 2))
+            if rc == LFLB:
+                prog.append((FRC, 0, k, k))
+            prog.append((BRC, 0, k, k))
+    if rc == LFLB:
+        prog += [(FRC, 0, k, k) for k in range(b, k_fail + 1)]
+    rest = seq[seq.index(("F", k_fail)) + 1:]
+    prog += _merge_groups(rest, C, s, has_far, [k_fail])
     prog += [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
     return prog
+
+
+def merged_program(P, s, M):
+    """A whole iteration of the stage once it has taken over its successor's layers (Section 5.2:
+    until the pipeline is reconfigured the shadow node executes all of the victim's instructions):
+    the stage's own 1F1B order, every computation merged with the victim's of the same micro-batch
+    under the same four rules as the failover schedule -- which is that schedule's part (iii) started
+    at the first computation, with nothing to join and nothing to replay.  No bubbles are simulated.
+    With P = 1 this is the merged node of pure data parallelism (both minibatches, no communication)."""
+    assert (0 <= s < P - 1 or (P == 1 and s == 0)) and M >= 1
+    prog = _merge_groups(compute_order(P, s, M), own_slots(P, s, M), s, s + 2 < P, [])
+    return prog + [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
 
 
 def fmt(prog):
@@ -317,6 +349,49 @@ def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2):
             if kind == "F":
                 prog.append((FRC, 0, k, k))
                 if far and k >= nf:
+                    pending.append((SEND_ACT, 0, k, 1))
+            else:
+                if far:
+                    prog.append((RECV_GRAD, 0, k, 1))
+                prog.append((BRC, 0, k, k))
+    prog += pending
+    prog += [(JOIN, 0, -1, -1), (ALLREDUCE, 0, -1, 0), (APPLY, 0, -1, 0)]
+    return prog
+
+
+def wrap_merged_program(P, M, tick_F=1, tick_B=2):
+    """A whole iteration of the last stage once it has taken over the first stage's layers: every
+    computation of both stages, ordered as in part (iii) of wrap_failover_program (start time on the
+    failure-free timeline; backward before forward, the victim's before the shadow's own), with the
+    same placement of the communication.  Nothing to join, nothing to replay."""
+    assert P >= 2 and M >= 1
+    s = P - 1
+    C = own_slots(P, s, M)
+    start, end, _ = timeline(P, M, tick_F, tick_B)
+    far = P > 2
+    items = []
+    for j, (kind, k) in enumerate(compute_order(P, s, M)):
+        items.append((start[s][j], 0 if kind == "B" else 1, 1, kind, k))
+    for j, (kind, k) in enumerate(compute_order(P, 0, M)):
+        items.append((start[0][j], 0 if kind == "B" else 1, 0, kind, k))
+    items.sort()
+    prog, pending = [], []
+    for _, _, is_own, kind, k in items:
+        prog += pending
+        pending = []
+        if is_own:
+            if kind == "F":
+                if far:
+                    prog.append((RECV_ACT, 0, k, s - 1))
+                prog.append((FWD, 0, k, k % C))
+            else:
+                prog.append((BWD, 0, k, k % C))
+                if far:
+                    pending.append((SEND_GRAD, 0, k, s - 1))
+        else:
+            if kind == "F":
+                prog.append((FRC, 0, k, k))
+                if far:
                     pending.append((SEND_ACT, 0, k, 1))
             else:
                 if far:

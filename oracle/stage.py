@@ -194,3 +194,62 @@ def wrap_first_stage_reference(arch, layers, front, B, S_len, n_h, M, ids, g1_ta
         for n in gf:
             Gf[n] = Gf[n] + gf[n]
     return G, Gf, z
+
+
+# ---- pure data parallelism (Section 5.2, "Support for Pure Data Parallelism") ------------------
+
+class DataParallelSim:
+    """A node of a pure data-parallel job: it holds the whole model and, as redundancy, the replica of
+    another node's parameters (and optimizer state).  There is no bubble; eager FRC means the node
+    also runs the forward of the OTHER node's micro-batch k through the replica ("over-batching": its
+    own minibatch plus a redundant one) and keeps the intermediates; lazy BRC back-propagates them,
+    with the other node's upstream gradient, once that node is lost.
+
+    own_layers / replica_layers: this node's and the other node's parameters (equal values in a
+    synchronous job, kept as separate copies as the paper keeps them);
+    x, g: this node's micro-batches and the gradients at its output (stand-ins for the loss);
+    xn, gn: the same for the node whose replica is held.
+    The other node is simulated until preempted: G_neigh accumulates what it computes itself."""
+
+    def __init__(self, arch, own_layers, replica_layers, B, S_len, n_h, M, x, g, xn, gn, eps=1e-5):
+        self.arch, self.B, self.S, self.n_h, self.eps = arch, B, S_len, n_h, eps
+        self.own, self.shadow, self.M = own_layers, replica_layers, M
+        self.x, self.g, self.xn, self.gn = x, g, xn, gn
+        self.own_stash, self.shadow_stash = {}, {}
+        self.G_own = _zeros_like_params(own_layers)
+        self.G_shadow = _zeros_like_params(replica_layers)
+        self.G_neigh = _zeros_like_params(replica_layers)
+        self.y, self.z_frc, self.gx, self.gxn = {}, {}, {}, {}
+        self.neigh_alive = True
+
+    def _neighbour_step(self, k):
+        """The other node's own forward + backward of its micro-batch k (while it lives)."""
+        z, caches = L.stack_fwd(self.arch, self.shadow, self.xn[k], self.B, self.S, self.n_h, self.eps)
+        _, grads = L.stack_bwd(self.arch, self.shadow, caches, self.gn[k])
+        _acc(self.G_neigh, grads)
+        return z
+
+    def preempt_neighbour(self):
+        self.neigh_alive = False
+        self.G_neigh = None
+
+    def run(self, prog):
+        for op, lane, k, arg in prog:
+            if op == S.FWD:
+                assert arg == 0 and arg not in self.own_stash        # one slot: forward, then its backward
+                self.y[k], caches = L.stack_fwd(self.arch, self.own, self.x[k], self.B, self.S, self.n_h, self.eps)
+                self.own_stash[arg] = (k, caches)
+            elif op == S.FRC:
+                assert arg == k and k not in self.shadow_stash
+                self.z_frc[k], caches = L.stack_fwd(self.arch, self.shadow, self.xn[k], self.B, self.S, self.n_h,
+                                                    self.eps)
+                self.shadow_stash[k] = caches
+            elif op == S.BWD:
+                kk, caches = self.own_stash.pop(arg)
+                assert kk == k
+                self.gx[k], grads = L.stack_bwd(self.arch, self.own, caches, self.g[k])
+                _acc(self.G_own, grads)
+            elif op == S.BRC:
+                self.gxn[k], grads = L.stack_bwd(self.arch, self.shadow, self.shadow_stash.pop(arg), self.gn[k])
+                _acc(self.G_shadow, grads)
+        return self

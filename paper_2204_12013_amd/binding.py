@@ -22,13 +22,16 @@ lib = C.CDLL(LIB_PATH)
 
 OK, E_BADCFG, E_BADMB, E_STATE, E_HIP, E_ARG, E_NOMEM = 0, -1, -2, -3, -4, -5, -6
 (RECV_ACT, SEND_ACT, RECV_GRAD, SEND_GRAD, FWD, BWD, FRC, BRC, BUBBLE, JOIN, ALLREDUCE, APPLY) = range(12)
-KERNEL_CLASSES = ("gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")
+# launch sites of the per-site timing (enum bamboo_kernel_class in bamboo_debug.h)
+KERNEL_CLASSES = ("gemm_qkv", "gemm_attn_out", "gemm_ffn1", "gemm_ffn2", "dgrad_ffn2", "dgrad_ffn1", "dgrad_attn_out",
+                  "dgrad_qkv", "wgrad_group", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum")
 
 
 class Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("arch", "dtype", "hidden", "heads", "ffn", "seq", "micro_batch", "n_own", "n_shadow",
-                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float), ("swap_slots", C.c_int32), ("wrap", C.c_int32)]
+                 "P", "stage_id", "M", "rc_mode", "tick_F", "tick_B")] + [("ln_eps", C.c_float), ("swap_slots", C.c_int32), ("wrap", C.c_int32),
+                                                                        ("data_parallel", C.c_int32)]
 
 
 class Instr(C.Structure):
@@ -52,6 +55,17 @@ class Adam(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float)]
 
 
+COMM_FN = C.CFUNCTYPE(C.c_int, C.c_void_p, C.POINTER(Instr))
+
+
+class Tables(C.Structure):
+    """bamboo_tables_t: per-micro-batch buffer tables and the hooks of stage_run."""
+    _fields_ = [("x", C.POINTER(C.c_void_p)), ("y", C.POINTER(C.c_void_p)), ("frc_in", C.POINTER(C.c_void_p)),
+                ("z", C.POINTER(C.c_void_p)), ("gy", C.POINTER(C.c_void_p)), ("gx", C.POINTER(C.c_void_p)),
+                ("gz", C.POINTER(C.c_void_p)), ("gy_replay", C.POINTER(C.c_void_p)), ("us_per_tick", C.c_float),
+                ("adam", C.POINTER(Adam)), ("comm", COMM_FN), ("user", C.c_void_p)]
+
+
 class BambooError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -65,10 +79,13 @@ _SIGS = {
     "stage_program": (C.c_int, [_cfgp, _insp, _i32]),
     "stage_program_uneven": (C.c_int, [_cfgp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), _insp, _i32]),
     "stage_failover_program": (C.c_int, [_cfgp, _i32, _insp, _i32]),
+    "stage_merged_program": (C.c_int, [_cfgp, _insp, _i32]),
+    "stage_run": (C.c_int, [_vp, _insp, _i32, C.POINTER(Tables)]),
     "stage_wrap_victim_progress": (C.c_int, [_cfgp, _i32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "stage_record_offset": (_i64, [_cfgp, _i32, _i32, _i32]),
     "stage_strerror": (C.c_char_p, [C.c_int]),
     "stage_record_fields": (C.c_int, [_cfgp, C.POINTER(C.c_uint64)]),
+    "stage_workspace_fields": (C.c_int, [_cfgp, C.POINTER(C.c_uint64)]),
     "stage_init": (C.c_int, [_cfgp, _szp] + [_vp] * 9 + [C.POINTER(_vp)]),
     "stage_schedule": (C.c_int, [_vp, _insp, _i32]),
     "stage_begin_iteration": (C.c_int, [_vp]),
@@ -141,7 +158,7 @@ def make_cfg(sc, frc_enabled=True, tick_F=1, tick_B=2, ln_eps=1e-5, rc_mode=None
     vals = dict(arch=sc.arch, dtype=sc.dtype, hidden=sc.hidden, heads=sc.heads, ffn=sc.ffn, seq=sc.seq,
                 micro_batch=sc.micro_batch, n_own=sc.n_own, n_shadow=sc.n_shadow, P=sc.P,
                 stage_id=sc.stage_id, M=sc.M, rc_mode=int(rc_mode), tick_F=tick_F, tick_B=tick_B,
-                ln_eps=ln_eps, swap_slots=0, wrap=0)
+                ln_eps=ln_eps, swap_slots=0, wrap=0, data_parallel=0)
     vals.update(override)
     return Cfg(**vals)
 
@@ -187,6 +204,27 @@ def stage_failover_program(cfg, k_fail):
     return _instr_list(arr, n)
 
 
+def stage_merged_program(cfg):
+    n = _check(lib.stage_merged_program(C.byref(cfg), None, 0), "stage_merged_program")
+    arr = (Instr * n)()
+    _check(lib.stage_merged_program(C.byref(cfg), arr, n), "stage_merged_program")
+    return _instr_list(arr, n)
+
+
+def pointer_table(tensors):
+    """A C array of the device addresses of a list of tensors (None entries become NULL), or None."""
+    if tensors is None:
+        return None
+    return (C.c_void_p * len(tensors))(*[None if t is None else t.data_ptr() for t in tensors])
+
+
+def instr_array(program):
+    arr = (Instr * max(len(program), 1))()
+    for i, (op, lane, mb, arg) in enumerate(program):
+        arr[i].op, arr[i].lane, arr[i].mb, arr[i].arg = op, lane, mb, arg
+    return arr
+
+
 def stage_record_offset(cfg, kind, slot, layer):
     return _check(lib.stage_record_offset(C.byref(cfg), kind, slot, layer), "stage_record_offset")
 
@@ -202,6 +240,15 @@ def stage_record_fields(cfg):
 
 def _ptr(t):
     return None if t is None else C.c_void_p(t.data_ptr())
+
+
+WORKSPACE_FIELDS = ("dh", "d1", "d2", "d3", "dctx", "dqkv", "bytes")
+
+
+def stage_workspace_fields(cfg):
+    arr = (C.c_uint64 * 7)()
+    _check(lib.stage_workspace_fields(C.byref(cfg), arr), "stage_workspace_fields")
+    return dict(zip(WORKSPACE_FIELDS, [int(v) for v in arr]))
 
 
 class Stage:
@@ -266,6 +313,14 @@ class Stage:
         cols = {"qkv": 3 * H, "g": F, "dg": F}.get(field, H)
         return arena[base:base + es * T * cols].view(self.act_dtype).view(T, cols)
 
+    def workspace_tensor(self, field):
+        """View of one of lane 0's backward buffers (inspection after a backward pass has finished)."""
+        cfg = self.cfg
+        base = stage_workspace_fields(cfg)[field]
+        es = 2 if cfg.dtype == 1 else 4
+        cols = {"dh": cfg.ffn, "dqkv": 3 * cfg.hidden}.get(field, cfg.hidden)
+        return self.workspace[base:base + es * self.T * cols].view(self.act_dtype).view(self.T, cols)
+
     def new_act(self):
         return self.torch.empty(self.T, self.H, dtype=self.act_dtype, device=self.device)
 
@@ -306,6 +361,34 @@ class Stage:
         n = _check(lib.failover_merge(self._h, k_fail, arr, cap), "failover_merge")
         self.merged = True
         return _instr_list(arr, n)
+
+    def stage_run(self, program, x=None, y=None, frc_in=None, z=None, gy=None, gx=None, gz=None, gy_replay=None,
+                  us_per_tick=0.0, adam=None, comm=None):
+        """Hands an instruction list and the per-micro-batch buffer tables to the library's interpreter.
+        comm(op, lane, mb, arg) -> bool is called for every communication instruction; a true return
+        means the peer is gone.  Returns the number of instructions issued (len(program) unless comm
+        stopped the run)."""
+        keep = [pointer_table(v) for v in (x, y, frc_in, z, gy, gx, gz, gy_replay)]
+        cast = lambda a: C.cast(a, C.POINTER(C.c_void_p)) if a is not None else None
+        hp = Adam(**adam) if adam is not None else None
+        failure = []
+
+        def hook(user, ins):
+            try:
+                i = ins.contents
+                return 1 if comm(int(i.op), int(i.lane), int(i.mb), int(i.arg)) else 0
+            except BaseException as e:     # nothing may propagate through the C frames
+                failure.append(e)
+                return 1
+        cb = COMM_FN(hook) if comm is not None else C.cast(None, COMM_FN)
+        t = Tables(*[cast(a) for a in keep], us_per_tick, C.pointer(hp) if hp is not None else None, cb, None)
+        arr = instr_array(program)
+        n = lib.stage_run(self._h, arr, len(program), C.byref(t))
+        if failure:
+            raise failure[0]
+        if any(op == BRC for op, _, _, _ in program[:max(n, 0)]):
+            self._shadow_g_dirty = True
+        return _check(n, "stage_run")
 
     def stage_optimizer_init(self):
         """Allocates the optimizer state ([master | m | v] fp32 for own and replica parameters)

@@ -582,21 +582,12 @@ static bool covered(const AttnDesc& a) {
   return !(misaligned(a.qkv) || misaligned(a.ctx) || misaligned(a.dctx) || misaligned(a.dqkv));
 }
 
-template <typename K>
-static hipError_t set_smem(K kern, int bytes) {
-  return hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-}
-
 template <int D, bool CAUSAL>
 static hipError_t fwd_launch(hipStream_t s, const AttnDesc& a) {
   constexpr int BYTES = 2 * TILE * (D + 8) * 2 + 2 * TILE * (D + 16) * 2;
-  static bool ready = false;
-  auto kern = attn_fwd_mfma_kernel<D, CAUSAL>;
-  if (!ready) {
-    hipError_t e = set_smem(kern, BYTES);
-    if (e != hipSuccess) return e;
-    ready = true;
-  }
+  constexpr auto kern = attn_fwd_mfma_kernel<D, CAUSAL>;
+  const hipError_t e = ensure_lds_attribute<kern, BYTES>();
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(((a.S + 127) / 128) * a.B * a.heads), dim3(256), BYTES, s, a);
   return hipGetLastError();
 }
@@ -605,15 +596,11 @@ template <int D, bool CAUSAL>
 static hipError_t bwd_launch(hipStream_t s, const AttnDesc& a) {
   constexpr int BYTES_DQ = 4 * TILE * (D + 8) * 2;
   constexpr int BYTES_DKV = 4 * TILE * (D + 8) * 2 + 4 * TILE * 4;
-  static bool ready = false;
-  auto kq = attn_bwd_dq_mfma_kernel<D, CAUSAL>;
-  auto kkv = attn_bwd_dkv_mfma_kernel<D, CAUSAL>;
-  if (!ready) {
-    hipError_t e = set_smem(kq, BYTES_DQ);
-    if (e == hipSuccess) e = set_smem(kkv, BYTES_DKV);
-    if (e != hipSuccess) return e;
-    ready = true;
-  }
+  constexpr auto kq = attn_bwd_dq_mfma_kernel<D, CAUSAL>;
+  constexpr auto kkv = attn_bwd_dkv_mfma_kernel<D, CAUSAL>;
+  hipError_t e = ensure_lds_attribute<kq, BYTES_DQ>();
+  if (e == hipSuccess) e = ensure_lds_attribute<kkv, BYTES_DKV>();
+  if (e != hipSuccess) return e;
   dim3 grid(((a.S + 127) / 128) * a.B * a.heads);
   hipLaunchKernelGGL(kq, grid, dim3(256), BYTES_DQ, s, a);
   hipLaunchKernelGGL(kkv, grid, dim3(256), BYTES_DKV, s, a);

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 typedef __bf16 bf16_t;
 
 namespace bamboo {
@@ -34,6 +36,30 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
   return v;
+}
+
+// ---- per-process launch state ------------------------------------------------
+// Set up once per device by whichever thread gets there first (stages driven from different threads
+// share it).
+constexpr int kMaxDevices = 64;
+inline int current_device_index() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  return dev < 0 || dev >= kMaxDevices ? 0 : dev;
+}
+// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device.
+template <auto KERNEL, int BYTES>
+inline hipError_t ensure_lds_attribute() {
+  static std::once_flag once[kMaxDevices];
+  static hipError_t result[kMaxDevices];
+  const int dev = current_device_index();
+  std::call_once(once[dev], [dev]() {
+    result[dev] = hipFuncSetAttribute((const void*)KERNEL, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
+  });
+  return result[dev];
 }
 
 // ---- GEMM ------------------------------------------------------------------
@@ -74,6 +100,12 @@ struct GemmDesc {
   // column-sum launch behind them).
   float* tile_colsum;
   int* tile_colsum_parts;
+  // set by the MFMA launchers: width of the strips the tile sequence walks (see tile_walk)
+  int strip;
+  // set by the MFMA launchers for launches of many rounds of tiles with a memory-heavy epilogue: the first
+  // stagger_wgs workgroups (one round) start (blockIdx / 8) % 8 times stagger_ticks of the device wall clock
+  // late, so that the CUs do not reach their epilogues all at once (0: no stagger)
+  int stagger_ticks, stagger_wgs;
 };
 
 // Ordered final sums of partial rows (see launch_grad_reduce below): out0[c] += sum_y p0[y][c] over `parts`

@@ -5,6 +5,8 @@
 // tokens are two-stage with a fixed order (per-workgroup partial sums, then one
 // ordered sum), so results are bitwise reproducible -- needed for FRC == FNC
 // and for failover == failure-free gradients.
+#include <atomic>
+
 #include "common.h"
 #include "reduce_device.h"
 
@@ -615,11 +617,14 @@ __global__ void bubble_kernel(long long clock_ticks, int* sink) {
 }
 
 hipError_t launch_bubble(hipStream_t s, float microseconds) {
-  static int rate_khz = 0;
+  // the device clock rate, read once (racing first calls read the same value: the store is atomic)
+  static std::atomic<int> rate_cache{0};
+  int rate_khz = rate_cache.load();
   if (rate_khz == 0) {
     int dev = 0, r = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipGetLastError();
     if (hipDeviceGetAttribute(&r, hipDeviceAttributeWallClockRate, dev) != hipSuccess || r <= 0) r = 100000;
+    rate_cache.store(r);
     rate_khz = r;
   }
   if (microseconds <= 0.f) return hipSuccess;

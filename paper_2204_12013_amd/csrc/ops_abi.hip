@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include "../../include/bamboo_debug.h"
 #include "../../include/bamboo_kernels.h"
 #include "../../include/bamboo_stage.h"
 #include "common.h"

@@ -157,6 +157,45 @@ std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c, const int* tick
   return out;
 }
 
+namespace {
+// Merge rules (1)-(4) over the computations seq[from..]: members of a group are [backward] [forward]
+// or a lone forward.  first_unsent: micro-batch whose FRC output the stage after the victim still
+// has to get when the list starts (-1: none).
+void merge_rest(std::vector<bamboo_instr_t>& out, const std::vector<Step>& seq, size_t from, int slots, int s,
+                bool far, int first_unsent) {
+  std::vector<int> z_pending;   // FRC outputs the far stage still has to get
+  if (first_unsent >= 0) z_pending.push_back(first_unsent);
+  std::vector<int> gx_pending;  // input gradients not yet sent back
+  size_t j = from;
+  bool done = false;
+  while (!done) {
+    const Step* gb = nullptr;
+    const Step* gf = nullptr;
+    if (j < seq.size() && seq[j].backward) gb = &seq[j++];
+    if (j < seq.size() && !seq[j].backward) gf = &seq[j++];
+    done = !gb && !gf;
+    if (far)
+      for (int k : z_pending) out.push_back(ins(BAMBOO_SEND_ACT, 0, k, s + 2));
+    z_pending.clear();
+    if (gb && far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, gb->mb, s + 2));
+    if (s > 0)
+      for (int k : gx_pending) out.push_back(ins(BAMBOO_SEND_GRAD, 0, k, s - 1));
+    gx_pending.clear();
+    if (gf && s > 0) out.push_back(ins(BAMBOO_RECV_ACT, 0, gf->mb, s - 1));
+    if (gb) {
+      out.push_back(ins(BAMBOO_BRC, 0, gb->mb, gb->mb));
+      out.push_back(ins(BAMBOO_BWD, 0, gb->mb, gb->mb % slots));
+      gx_pending.push_back(gb->mb);
+    }
+    if (gf) {
+      out.push_back(ins(BAMBOO_FWD, 0, gf->mb, gf->mb % slots));
+      out.push_back(ins(BAMBOO_FRC, 0, gf->mb, gf->mb));
+      z_pending.push_back(gf->mb);
+    }
+  }
+}
+}  // namespace
+
 // Failover schedule (Section 5.2 "Lazy BRC and Recovery").  The failure shows
 // when the send of micro-batch k_fail's activation to the successor breaks.
 //  1. JOIN the FRC lane up to FRC(k_fail): its stash is about to be consumed.
@@ -190,36 +229,19 @@ std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_
     }
   if (c.rc_mode == BAMBOO_RC_LFLB)
     for (int k = lost; k <= k_fail; ++k) out.push_back(ins(BAMBOO_FRC, 0, k, k));
-  std::vector<int> z_pending{k_fail};  // FRC outputs the far stage still has to get
-  std::vector<int> gx_pending;          // input gradients not yet sent back
-  size_t j = at + 1;
-  bool done = false;
-  while (!done) {
-    // members of the next group: [backward] [forward] or a lone forward
-    const Step* gb = nullptr;
-    const Step* gf = nullptr;
-    if (j < seq.size() && seq[j].backward) gb = &seq[j++];
-    if (j < seq.size() && !seq[j].backward) gf = &seq[j++];
-    done = !gb && !gf;
-    if (far)
-      for (int k : z_pending) out.push_back(ins(BAMBOO_SEND_ACT, 0, k, s + 2));
-    z_pending.clear();
-    if (gb && far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, gb->mb, s + 2));
-    if (s > 0)
-      for (int k : gx_pending) out.push_back(ins(BAMBOO_SEND_GRAD, 0, k, s - 1));
-    gx_pending.clear();
-    if (gf && s > 0) out.push_back(ins(BAMBOO_RECV_ACT, 0, gf->mb, s - 1));
-    if (gb) {
-      out.push_back(ins(BAMBOO_BRC, 0, gb->mb, gb->mb));
-      out.push_back(ins(BAMBOO_BWD, 0, gb->mb, gb->mb % slots));
-      gx_pending.push_back(gb->mb);
-    }
-    if (gf) {
-      out.push_back(ins(BAMBOO_FWD, 0, gf->mb, gf->mb % slots));
-      out.push_back(ins(BAMBOO_FRC, 0, gf->mb, gf->mb));
-      z_pending.push_back(gf->mb);
-    }
-  }
+  merge_rest(out, seq, at + 1, slots, s, far, k_fail);
+  epilogue(out);
+  return out;
+}
+
+// The merged stage's whole iteration: rule-(1)-(4) groups from the first computation on, nothing to
+// join and nothing to replay (Section 5.2: until the pipeline is reconfigured the shadow node
+// executes all of the victim's instructions).  With P == 1 the two merged nodes are data-parallel
+// peers and there is no communication.
+std::vector<bamboo_instr_t> build_merged_program(const bamboo_cfg_t& c) {
+  const int P = c.P, s = c.stage_id, M = c.M;
+  std::vector<bamboo_instr_t> out;
+  merge_rest(out, one_f_one_b(P, s, M), 0, own_slot_count(P, s, M), s, s + 2 < P, -1);
   epilogue(out);
   return out;
 }
@@ -244,25 +266,28 @@ void wrap_victim_progress(const bamboo_cfg_t& c, int k_fail, int* n_fwd, int* n_
 // sequences is merged by start time on the failure-free timeline (anything a computation needs
 // started earlier there); on equal times backward work goes first, then the victim's.  Each
 // sequence is already in time order, so this is a two-way merge.
-std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, int k_fail) {
+// k_fail < 0: the whole iteration of the merged node (nothing to join, nothing to replay)
+static std::vector<bamboo_instr_t> wrap_merge(const bamboo_cfg_t& c, int k_fail) {
   const int P = c.P, s = P - 1, M = c.M;
   const int slots = own_slot_count(P, s, M);
   const bool far = P > 2;
   const std::vector<int> tf(P, c.tick_F), tb(P, c.tick_B);
   const Timeline t = play(P, M, tf.data(), tb.data());
   int n_fwd = 0, n_bwd = 0;
-  wrap_victim_progress(c, k_fail, &n_fwd, &n_bwd);
   std::vector<bamboo_instr_t> out;
-  out.push_back(ins(BAMBOO_JOIN, 0, -1, k_fail));
-  for (int k = 0; k < n_bwd; ++k) {
-    if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, 1));
-    out.push_back(ins(BAMBOO_BRC, 0, k, k));
-  }
-  // what is left: own sequence behind FWD(k_fail); victim forwards beyond k_fail, victim backwards from n_bwd
   std::vector<Step> own = one_f_one_b(P, s, M), vic;
   size_t io = 0;
-  while (!(!own[io].backward && own[io].mb == k_fail)) ++io;
-  ++io;
+  if (k_fail >= 0) {
+    wrap_victim_progress(c, k_fail, &n_fwd, &n_bwd);
+    out.push_back(ins(BAMBOO_JOIN, 0, -1, k_fail));
+    for (int k = 0; k < n_bwd; ++k) {
+      if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, 1));
+      out.push_back(ins(BAMBOO_BRC, 0, k, k));
+    }
+    // what is left: own sequence behind FWD(k_fail); victim forwards beyond k_fail, victim backwards from n_bwd
+    while (!(!own[io].backward && own[io].mb == k_fail)) ++io;
+    ++io;
+  }
   for (const Step& v : one_f_one_b(P, 0, M))
     if (v.backward ? v.mb >= n_bwd : v.mb > k_fail) vic.push_back(v);
   size_t iv = 0;
@@ -304,5 +329,8 @@ std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, i
   epilogue(out);
   return out;
 }
+
+std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, int k_fail) { return wrap_merge(c, k_fail); }
+std::vector<bamboo_instr_t> build_wrap_merged_program(const bamboo_cfg_t& c) { return wrap_merge(c, -1); }
 
 }  // namespace bamboo

@@ -26,8 +26,12 @@ std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c);
 // per-stage durations; null arrays fall back to c.tick_F / c.tick_B for every stage
 std::vector<bamboo_instr_t> build_program(const bamboo_cfg_t& c, const int* tick_F, const int* tick_B);
 std::vector<bamboo_instr_t> build_failover_program(const bamboo_cfg_t& c, int k_fail);
+// a whole iteration of the stage after it has taken over the victim's layers (adjacent stages, or the
+// two nodes of pure data parallelism when P == 1)
+std::vector<bamboo_instr_t> build_merged_program(const bamboo_cfg_t& c);
 // wrap-around: the last stage takes over the lost first stage (cfg.wrap)
 std::vector<bamboo_instr_t> build_wrap_failover_program(const bamboo_cfg_t& c, int k_fail);
+std::vector<bamboo_instr_t> build_wrap_merged_program(const bamboo_cfg_t& c);
 void wrap_victim_progress(const bamboo_cfg_t& c, int k_fail, int* n_fwd, int* n_bwd);
 
 }  // namespace bamboo

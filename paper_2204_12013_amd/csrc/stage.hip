@@ -16,6 +16,7 @@
 #include <new>
 #include <vector>
 
+#include "../../include/bamboo_debug.h"
 #include "common.h"
 #include "schedule.h"
 
@@ -137,7 +138,23 @@ int validate(const bamboo_cfg_t* c) {
   // the wrap-around failover schedule exists for the paper's own variant only (eager FRC, lazy BRC)
   if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode != BAMBOO_RC_EFLB))
     return BAMBOO_E_BADCFG;
+  if (c->data_parallel != 0 && c->data_parallel != 1) return BAMBOO_E_BADCFG;
+  // pure data parallelism: the whole model on one node, the replica is another node's model; the paper
+  // describes eager FRC (over-batching) and lazy BRC for it, nothing eager on the backward side
+  if (c->data_parallel && (c->P != 1 || c->wrap || c->n_shadow != c->n_own || c->rc_mode == BAMBOO_RC_EFEB))
+    return BAMBOO_E_BADCFG;
   return BAMBOO_OK;
+}
+
+// whether the stage has a victim to take over: a successor, the first stage (wrap), a data-parallel peer
+bool can_fail_over(const bamboo_cfg_t& c) {
+  return c.n_shadow > 0 && (c.stage_id < c.P - 1 || c.wrap || c.data_parallel);
+}
+std::vector<bamboo_instr_t> failover_list(const bamboo_cfg_t& c, int k_fail) {
+  return c.wrap ? build_wrap_failover_program(c, k_fail) : build_failover_program(c, k_fail);
+}
+std::vector<bamboo_instr_t> merged_list(const bamboo_cfg_t& c) {
+  return c.wrap ? build_wrap_merged_program(c) : build_merged_program(c);
 }
 
 int copy_out(const std::vector<bamboo_instr_t>& v, bamboo_instr_t* out, int32_t cap) {
@@ -163,7 +180,9 @@ struct bamboo_stage {
   std::vector<bamboo_instr_t> program;
   bool merged;
   std::vector<int> own_slot_mb;        // micro-batch stashed in each own slot, -1 free
-  std::vector<char> fwd_issued, frc_issued, shadow_live;
+  std::vector<char> fwd_issued, frc_issued, shadow_live, bwd_done;
+  bool merged_program_installed;       // program is the merged stage's whole iteration (not a failover list)
+  int apply_step;                      // optimizer steps taken through stage_run
   std::vector<hipEvent_t> ev_fwd, ev_frc;
   hipEvent_t ev_join;
   int last_frc_on_lane1;
@@ -236,11 +255,17 @@ uint64_t esize(const bamboo_stage* st) { return st->cfg.dtype == BAMBOO_BF16 ? 2
     if (rc_ != BAMBOO_OK) return rc_; \
   } while (0)
 
-enum KernelClass { K_GEMM_FWD = 0, K_GEMM_DGRAD, K_GEMM_WGRAD, K_ATTN_FWD, K_ATTN_BWD, K_LN_FWD, K_LN_BWD, K_COLSUM, K_COUNT };
+enum KernelClass {
+  K_GEMM_QKV = BAMBOO_K_GEMM_QKV, K_GEMM_ATTN_OUT = BAMBOO_K_GEMM_ATTN_OUT, K_GEMM_FFN1 = BAMBOO_K_GEMM_FFN1,
+  K_GEMM_FFN2 = BAMBOO_K_GEMM_FFN2, K_DGRAD_FFN2 = BAMBOO_K_DGRAD_FFN2, K_DGRAD_FFN1 = BAMBOO_K_DGRAD_FFN1,
+  K_DGRAD_ATTN_OUT = BAMBOO_K_DGRAD_ATTN_OUT, K_DGRAD_QKV = BAMBOO_K_DGRAD_QKV, K_WGRAD_GROUP = BAMBOO_K_WGRAD_GROUP,
+  K_ATTN_FWD = BAMBOO_K_ATTN_FWD, K_ATTN_BWD = BAMBOO_K_ATTN_BWD, K_LN_FWD = BAMBOO_K_LN_FWD,
+  K_LN_BWD = BAMBOO_K_LN_BWD, K_COLSUM = BAMBOO_K_COLSUM, K_COUNT = BAMBOO_K_COUNT
+};
 
-int p_gemm(bamboo_stage* st, hipStream_t s, const GemmDesc& d) {
-  const int cls = d.epi == EPI_ACC_F32 ? K_GEMM_WGRAD : (d.b_sn == 1 ? K_GEMM_FWD : K_GEMM_DGRAD);
-  ProfScope ps(st, cls, s, gemm_flops(d));
+// site: which GEMM of the layer pass this is (for the per-site timing)
+int p_gemm(bamboo_stage* st, hipStream_t s, int site, const GemmDesc& d) {
+  ProfScope ps(st, site, s, gemm_flops(d));
   HIPCHK(launch_gemm(s, st->cfg.dtype, d));
   return BAMBOO_OK;
 }
@@ -250,7 +275,7 @@ int p_gemm_group(bamboo_stage* st, hipStream_t s, const GemmDesc* d, int n, cons
                  bool* tail_done) {
   double flops = 0;
   for (int i = 0; i < n; ++i) flops += gemm_flops(d[i]);
-  ProfScope p(st, BAMBOO_K_GEMM_WGRAD, s, flops);
+  ProfScope p(st, K_WGRAD_GROUP, s, flops);
   HIPCHK(launch_gemm_group(s, st->cfg.dtype, d, n, tail, tail_done));
   return BAMBOO_OK;
 }
@@ -357,12 +382,12 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
                                   (float*)(rec + r.ln1)));
     d = gemm_nn(rec + r.ain, P(st->po.Wqkv), rec + r.qkv, T, 3 * H, H, EPI_BIAS);
     d.bias = P(st->po.bqkv);
-    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_gemm(st, s, K_GEMM_QKV, d));
     BBCHK(p_attn_fwd(st, s, a));
     d = gemm_nn(rec + r.ctx, P(st->po.Wo), rec + r.r1, T, H, H, EPI_BIAS_RES);
     d.bias = P(st->po.bo);
     d.res = rec + r.x;
-    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_gemm(st, s, K_GEMM_ATTN_OUT, d));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER)
       BBCHK(p_ln_fwd(st, s, T, H, rec + r.r1, P(st->po.g1), P(st->po.be1), rec + r.fin,
                                   (float*)(rec + r.ln1)));
@@ -372,19 +397,19 @@ int run_forward(bamboo_stage* st, int kind, int lane_id, int slot, const void* x
     d = gemm_nn(rec + r.fin, P(st->po.W1), rec + r.dg, T, F, H, EPI_BIAS_GELU);
     d.bias = P(st->po.b1);
     d.aux_out = rec + r.g;
-    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_gemm(st, s, K_GEMM_FFN1, d));
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nn(rec + r.g, P(st->po.W2), rec + r.r2, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.fin;
-      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_gemm(st, s, K_GEMM_FFN2, d));
       BBCHK(p_ln_fwd(st, s, T, H, rec + r.r2, P(st->po.g2), P(st->po.be2), out,
                                   (float*)(rec + r.ln2)));
     } else {
       d = gemm_nn(rec + r.g, P(st->po.W2), out, T, H, F, EPI_BIAS_RES);
       d.bias = P(st->po.b2);
       d.res = rec + r.r1;
-      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_gemm(st, s, K_GEMM_FFN2, d));
     }
   }
   return BAMBOO_OK;
@@ -448,7 +473,7 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
       d.tile_colsum = (float*)(ws + w.p_dh);
       d.tile_colsum_parts = &dh_parts;
     }
-    BBCHK(p_gemm(st, s, d));
+    BBCHK(p_gemm(st, s, K_DGRAD_FFN2, d));
     if (fused_sum) {
       if (!grad_reduce_add(&batch, F, dh_parts, (const float*)(ws + w.p_dh), G + st->po.b1, nullptr, nullptr))
         return BAMBOO_E_STATE;
@@ -466,19 +491,19 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dh, P(st->po.W1), d2, T, H, F, EPI_RES);   // + residual branch of r2 = y1 + f
       d.res = df;
-      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_gemm(st, s, K_DGRAD_FFN1, d));
       BBCHK(p_ln_bwd(st, s, ws, T, H, d2, rec + r.r1, (const float*)(rec + r.ln1), P(st->po.g1), nullptr, d1,
                      G + st->po.g1, G + st->po.be1, G + st->po.bo, w.p_ln[0], &batch));
       da = d1;
     } else {
-      BBCHK(p_gemm(st, s, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
+      BBCHK(p_gemm(st, s, K_DGRAD_FFN1, gemm_nt(dh, P(st->po.W1), d1, T, H, F, EPI_STORE)));
       BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.r1, (const float*)(rec + r.ln2), P(st->po.g2), dy, d2,
                      G + st->po.g2, G + st->po.be2, G + st->po.bo, w.p_ln[1], &batch));   // + residual branch of y = x1 + f
       da = d2;
     }
     // a = ctx Wo + bo
     wgrad[2] = gemm_tn(rec + r.ctx, da, G + st->po.Wo, T, H, H);
-    BBCHK(p_gemm(st, s, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
+    BBCHK(p_gemm(st, s, K_DGRAD_ATTN_OUT, gemm_nt(da, P(st->po.Wo), dctx, T, H, H, EPI_STORE)));
     // the MFMA kernels also leave the column sums of dqkv (the gradient of bqkv), one partial row per sample
     // and block of 128 tokens; any other kernel leaves dqkv_parts at 0 and a column-sum launch follows
     int dqkv_parts = 0;
@@ -498,9 +523,9 @@ int run_backward(bamboo_stage* st, int kind, int lane_id, int slot, const void* 
     if (c.arch == BAMBOO_ARCH_POST_LN_ENCODER) {
       d = gemm_nt(dqkv, P(st->po.Wqkv), dx, T, H, 3 * H, EPI_RES);   // + residual branch of r1 = x + a
       d.res = da;
-      BBCHK(p_gemm(st, s, d));
+      BBCHK(p_gemm(st, s, K_DGRAD_QKV, d));
     } else {
-      BBCHK(p_gemm(st, s, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
+      BBCHK(p_gemm(st, s, K_DGRAD_QKV, gemm_nt(dqkv, P(st->po.Wqkv), d1, T, H, 3 * H, EPI_STORE)));
       BBCHK(p_ln_bwd(st, s, ws, T, H, d1, rec + r.x, (const float*)(rec + r.ln1), P(st->po.g1), da, dx,
                      G + st->po.g1, G + st->po.be1, nullptr, w.p_ln[0], &batch));   // + residual branch of x1 = x + a
     }
@@ -615,11 +640,21 @@ int stage_program_uneven(const bamboo_cfg_t* cfg, const int32_t* tick_F, const i
 int stage_failover_program(const bamboo_cfg_t* cfg, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
   const int v = validate(cfg);
   if (v != BAMBOO_OK) return v;
-  if (cfg->n_shadow <= 0 || (cfg->stage_id >= cfg->P - 1 && !cfg->wrap)) return BAMBOO_E_STATE;
+  if (!can_fail_over(*cfg)) return BAMBOO_E_STATE;
   if (k_fail < 0 || k_fail >= cfg->M) return BAMBOO_E_BADMB;
   try {
-    return copy_out(cfg->wrap ? build_wrap_failover_program(*cfg, k_fail) : build_failover_program(*cfg, k_fail), out,
-                    cap);
+    return copy_out(failover_list(*cfg, k_fail), out, cap);
+  } catch (const std::bad_alloc&) {
+    return BAMBOO_E_NOMEM;
+  }
+}
+
+int stage_merged_program(const bamboo_cfg_t* cfg, bamboo_instr_t* out, int32_t cap) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (!can_fail_over(*cfg)) return BAMBOO_E_STATE;
+  try {
+    return copy_out(merged_list(*cfg), out, cap);
   } catch (const std::bad_alloc&) {
     return BAMBOO_E_NOMEM;
   }
@@ -658,6 +693,16 @@ int stage_record_fields(const bamboo_cfg_t* cfg, uint64_t out[13]) {
   if (!out) return BAMBOO_E_ARG;
   const RecordLayout r = record_layout(*cfg);
   const uint64_t f[13] = {r.x, r.ain, r.qkv, r.ctx, r.r1, r.fin, r.g, r.dg, r.r2, r.lse, r.ln1, r.ln2, r.bytes};
+  memcpy(out, f, sizeof(f));
+  return BAMBOO_OK;
+}
+
+int stage_workspace_fields(const bamboo_cfg_t* cfg, uint64_t out[7]) {
+  const int v = validate(cfg);
+  if (v != BAMBOO_OK) return v;
+  if (!out) return BAMBOO_E_ARG;
+  const LaneScratch w = lane_scratch(*cfg, true);
+  const uint64_t f[7] = {w.dh, w.d1, w.d2, w.d3, w.dctx, w.dqkv, w.bytes};
   memcpy(out, f, sizeof(f));
   return BAMBOO_OK;
 }
@@ -701,6 +746,9 @@ int stage_init(const bamboo_cfg_t* cfg, const bamboo_sizes_t* sizes, const void*
     st->fwd_issued.assign(cfg->M, 0);
     st->frc_issued.assign(cfg->M, 0);
     st->shadow_live.assign(cfg->M, 0);
+    st->bwd_done.assign(cfg->M, 0);
+    st->merged_program_installed = false;
+    st->apply_step = 0;
     st->ev_fwd.assign(cfg->M, nullptr);
     st->ev_frc.assign(cfg->M, nullptr);
     st->ev_join = nullptr;
@@ -740,6 +788,17 @@ int stage_begin_iteration(bamboo_stage_t* st) {
   std::fill(st->fwd_issued.begin(), st->fwd_issued.end(), 0);
   std::fill(st->frc_issued.begin(), st->frc_issued.end(), 0);
   std::fill(st->shadow_live.begin(), st->shadow_live.end(), 0);
+  std::fill(st->bwd_done.begin(), st->bwd_done.end(), 0);
+  // the first iteration after a merge: the failover list (which starts in mid-iteration) gives way to
+  // the merged stage's whole-iteration program
+  if (st->merged && !st->merged_program_installed) {
+    try {
+      st->program = merged_list(st->cfg);
+    } catch (const std::bad_alloc&) {
+      return BAMBOO_E_NOMEM;
+    }
+    st->merged_program_installed = true;
+  }
   std::fill(st->ring_mb.begin(), st->ring_mb.end(), -1);
   std::fill(st->on_host.begin(), st->on_host.end(), 0);
   st->last_frc_on_lane1 = -1;
@@ -766,11 +825,13 @@ int shadow_fwd_frc(bamboo_stage_t* st, int32_t k, const void* y, void* z) {
   // lazy FRC: only the failover schedule runs it
   if (st->cfg.n_shadow <= 0 || (st->cfg.rc_mode == BAMBOO_RC_LFLB && !st->merged)) return BAMBOO_E_STATE;
   if (k < 0 || k >= st->cfg.M) return BAMBOO_E_BADMB;
-  // the replica of the first stage works on the samples, not on this stage's output
-  if ((!st->fwd_issued[k] && !st->cfg.wrap) || st->frc_issued[k]) return BAMBOO_E_BADMB;
+  // the replica of the first stage works on the samples, the replica of a data-parallel peer on that
+  // peer's minibatch: not on this stage's output
+  const bool input_is_own_output = !st->cfg.wrap && !st->cfg.data_parallel;
+  if ((!st->fwd_issued[k] && input_is_own_output) || st->frc_issued[k]) return BAMBOO_E_BADMB;
   const int lane_id = st->merged ? 0 : 1;
   hipEvent_t ev;
-  if (lane_id == 1 && !st->cfg.wrap) {
+  if (lane_id == 1 && input_is_own_output) {
     if (get_event(st->ev_fwd, k, &ev) != BAMBOO_OK) return BAMBOO_E_HIP;
     HIPCHK(hipStreamWaitEvent(st->lane[1], ev, 0));
   }
@@ -816,6 +877,7 @@ int stage_bwd(bamboo_stage_t* st, int32_t k, const void* gy, void* gx) {
   const int rc = run_backward(st, 0, 0, slot, gy, gx);
   if (rc != BAMBOO_OK) return rc;
   st->own_slot_mb[slot] = -1;
+  st->bwd_done[k] = 1;
   return BAMBOO_OK;
 }
 
@@ -860,14 +922,16 @@ int shadow_bwd_brc(bamboo_stage_t* st, int32_t k, const void* gz, void* gy) {
 
 int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int32_t cap) {
   if (!st) return BAMBOO_E_ARG;
-  if (st->merged || st->cfg.n_shadow <= 0 || (st->cfg.stage_id >= st->cfg.P - 1 && !st->cfg.wrap)) return BAMBOO_E_STATE;
+  if (st->merged || !can_fail_over(st->cfg)) return BAMBOO_E_STATE;
   if (k_fail < 0 || k_fail >= st->cfg.M) return BAMBOO_E_BADMB;
   std::vector<bamboo_instr_t> prog;
   try {
-    prog = st->cfg.wrap ? build_wrap_failover_program(st->cfg, k_fail) : build_failover_program(st->cfg, k_fail);
+    prog = failover_list(st->cfg, k_fail);
   } catch (const std::bad_alloc&) {
     return BAMBOO_E_NOMEM;
   }
+  // the size-query form (NULL, 0) of the other schedule calls would merge the stage for good: rejected
+  if (out == nullptr) return BAMBOO_E_ARG;
   const int n = copy_out(prog, out, cap);
   if (n < 0) return n;
   // JOIN: everything issued on the FRC lane must be visible to lane 0
@@ -875,6 +939,69 @@ int failover_merge(bamboo_stage_t* st, int32_t k_fail, bamboo_instr_t* out, int3
   HIPCHK(hipStreamWaitEvent(st->lane[0], st->ev_join, 0));
   st->merged = true;
   st->program.swap(prog);
+  return n;
+}
+
+int stage_run(bamboo_stage_t* st, const bamboo_instr_t* program, int32_t n, const bamboo_tables_t* t) {
+  if (!st || !t || n < 0 || (n > 0 && !program)) return BAMBOO_E_ARG;
+  // an instruction of the wrap-around stage is a pair of calls into two objects (the stage and the
+  // model's ends): the caller composes them
+  if (st->cfg.wrap) return BAMBOO_E_STATE;
+  const int M = st->cfg.M;
+  for (int32_t i = 0; i < n; ++i) {
+    const bamboo_instr_t& in = program[i];
+    const int k = in.mb;
+    const bool needs_mb = in.op == BAMBOO_FWD || in.op == BAMBOO_BWD || in.op == BAMBOO_FRC || in.op == BAMBOO_BRC;
+    if (needs_mb && (k < 0 || k >= M)) return BAMBOO_E_BADMB;
+    int rc = BAMBOO_OK;
+    switch (in.op) {
+      case BAMBOO_FWD:
+        if (!t->x || !t->y) return BAMBOO_E_ARG;
+        rc = stage_fwd(st, k, t->x[k], t->y[k]);
+        break;
+      case BAMBOO_FRC: {
+        const void* src = t->frc_in ? t->frc_in[k] : (t->y ? t->y[k] : nullptr);
+        if (!src) return BAMBOO_E_ARG;
+        rc = shadow_fwd_frc(st, k, src, t->z ? t->z[k] : nullptr);
+        break;
+      }
+      case BAMBOO_BWD:
+        if (!t->gy || !t->gx) return BAMBOO_E_ARG;
+        rc = stage_bwd(st, k, t->gy[k], t->gx[k]);
+        break;
+      case BAMBOO_BRC:
+        if (!t->gz) return BAMBOO_E_ARG;
+        if (!st->merged) {
+          rc = shadow_bwd_brc(st, k, t->gz[k], nullptr);     // beside a live successor: its g_y is the successor's to deliver
+        } else if (st->bwd_done[k] || st->cfg.data_parallel) {
+          // replayed, or a data-parallel peer's input gradient: it feeds nothing on this node
+          rc = shadow_bwd_brc(st, k, t->gz[k], t->gy_replay ? t->gy_replay[k] : nullptr);
+        } else {
+          if (!t->gy) return BAMBOO_E_ARG;
+          rc = shadow_bwd_brc(st, k, t->gz[k], t->gy[k]);   // the gradient the victim would have sent: feeds BWD(k)
+        }
+        break;
+      case BAMBOO_BUBBLE:
+        if (t->us_per_tick > 0.f) rc = stage_bubble(st, in.arg, t->us_per_tick);
+        break;
+      case BAMBOO_JOIN:
+        rc = stage_join(st);
+        break;
+      case BAMBOO_APPLY:
+        if (t->adam && st->opt[0]) rc = stage_apply(st, t->adam, ++st->apply_step);
+        break;
+      case BAMBOO_RECV_ACT:
+      case BAMBOO_SEND_ACT:
+      case BAMBOO_RECV_GRAD:
+      case BAMBOO_SEND_GRAD:
+      case BAMBOO_ALLREDUCE:
+        if (t->comm && t->comm(t->user, &in) != 0) return i;   // the peer is gone: the caller fails over
+        break;
+      default:
+        return BAMBOO_E_ARG;
+    }
+    if (rc != BAMBOO_OK) return rc;
+  }
   return n;
 }
 

@@ -1,20 +1,23 @@
-"""Instruction-list interpreter around one Stage: stands in for the neighbours.
+"""The neighbours of one Stage: buffer tables and the communication hook for the library's
+instruction-list interpreter (stage_run).
 
 The stage before (s-1) is a table of inputs x_k, the stage after the successor
 (s+2) a table of upstream gradients g_z_k, both pre-staged in device memory
 (they replace RECV_ACT / RECV_GRAD).  The successor (s+1) is either absent
 (benchmark: g_y_k comes from a table) or simulated by a second Stage object
 running the replica's parameter values as its own layers, with its own stash
-and gradient buffer, until it is "preempted".  No arithmetic happens here: every
-compute instruction is one call into the C ABI.
+and gradient buffer, until it is "preempted".  No arithmetic happens here and no
+instruction is interpreted here: the list goes to stage_run, which issues every
+computation; this side answers the communication instructions.
 """
 from . import binding as B
 
 
 class StageHarness:
-    def __init__(self, stage, x, gz, successor=None, gy_table=None, us_per_tick=0.0, adam=None):
+    def __init__(self, stage, x, gz, successor=None, gy_table=None, us_per_tick=0.0, adam=None, frc_in=None):
         self.st = stage
         self.x, self.gz = x, gz
+        self.frc_in = frc_in      # inputs of FRC where they are not the stage's own outputs (data-parallel peer)
         self.succ = successor
         self.gy_table = gy_table
         self.us_per_tick = us_per_tick
@@ -54,42 +57,40 @@ class StageHarness:
         succ.stage_bwd(k, self.gz[k], self.gy[k])
         self.st.stream_main.wait_stream(succ.stream_main)
 
+    def _comm(self, op, lane, k, arg):
+        """Hook for the communication instructions: the live successor's work happens where its
+        gradient is received.  Nothing here ever reports a lost peer (the tests and the benchmark
+        decide themselves when the successor is gone)."""
+        if op == B.RECV_GRAD and arg == self.st.cfg.stage_id + 1 and self.succ is not None and not self.st.merged:
+            self._successor_backward(k)
+        return False
+
     def run(self, program):
+        """The library interprets the list (stage_run); this side only supplies the buffer tables and,
+        through the hook, the neighbours."""
         st = self.st
+        # replayed BRCs (their own backward already ran) write their input gradient to buffers of their own
+        done = set(self.bwd_done)
+        replay = [None] * st.cfg.M
         for op, lane, k, arg in program:
-            if op == B.FWD:
-                st.stage_fwd(k, self.x[k], self.y[k])
-            elif op == B.FRC:
-                st.shadow_fwd_frc(k, self.y[k], self.z_frc[k])
-            elif op == B.RECV_GRAD:
-                if arg == st.cfg.stage_id + 1 and self.succ is not None:
-                    self._successor_backward(k)
-            elif op == B.BWD:
-                st.stage_bwd(k, self.gy[k], self.gx[k])
-                self.bwd_done.add(k)
-            elif op == B.BRC:
-                if not st.merged:                 # eager BRC beside a live successor: its g_y is the
-                    st.shadow_bwd_brc(k, self.gz[k], None)      # successor's to deliver, ours is dropped
-                elif k in self.bwd_done:          # replayed: own backward already ran
-                    self.gy_replay[k] = st.new_act()
-                    st.shadow_bwd_brc(k, self.gz[k], self.gy_replay[k])
-                else:
-                    st.shadow_bwd_brc(k, self.gz[k], self.gy[k])
-            elif op == B.BUBBLE:
-                if self.us_per_tick > 0:
-                    st.stage_bubble(arg, self.us_per_tick)
-            elif op == B.JOIN:
-                st.stage_join()
-            elif op == B.APPLY and self.adam is not None:
-                # the stage and its (live) successor both update; the replica then takes the
-                # successor's new parameters and optimizer state
-                self.step += 1
-                st.stage_apply(self.step, **self.adam)
-                if self.succ is not None and not st.merged:
-                    self.succ.stage_apply(self.step, **self.adam)
-                    st.stream_main.wait_stream(self.succ.stream_main)
-                    st.stage_sync_replica(self.succ.own_w, self.succ.own_opt)
-            # SEND_*, RECV_ACT, ALLREDUCE, APPLY: placeholders on one GPU
+            if op == B.BWD:
+                done.add(k)
+            elif op == B.BRC and st.merged and (k in done or st.cfg.data_parallel):
+                self.gy_replay[k] = replay[k] = st.new_act()
+        n = st.stage_run(program, x=self.x, y=self.y, frc_in=self.frc_in, z=self.z_frc, gy=self.gy, gx=self.gx,
+                         gz=self.gz, gy_replay=replay if any(r is not None for r in replay) else None,
+                         us_per_tick=self.us_per_tick, adam=self.adam,
+                         comm=self._comm if self.succ is not None else None)
+        assert n == len(program)
+        self.bwd_done = done
+        if self.adam is not None and any(op == B.APPLY for op, _, _, _ in program):
+            # the stage has updated itself (APPLY inside stage_run); its live successor updates too, and the
+            # replica then takes the successor's new parameters and optimizer state
+            self.step += 1
+            if self.succ is not None and not st.merged:
+                self.succ.stage_apply(self.step, **self.adam)
+                st.stream_main.wait_stream(self.succ.stream_main)
+                st.stage_sync_replica(self.succ.own_w, self.succ.own_opt)
         return self
 
     def sync(self):

@@ -1,7 +1,7 @@
 """Condense rocprofv3 CSV output into the short text summaries kept under profiles/.
 
-  python -m paper_2204_12013_amd.profile_summary stats  <kernel_stats.csv>
-  python -m paper_2204_12013_amd.profile_summary pmc    <counter_collection.csv> [...]
+  python profile_summary.py stats  <kernel_stats.csv>
+  python profile_summary.py pmc    <counter_collection.csv> [...]
 
 `stats` prints calls / average / total per kernel.  `pmc` prints, per kernel, the
 mean counter value per dispatch, and scales FETCH_SIZE / WRITE_SIZE (KiB) by what

@@ -24,3 +24,17 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """How close the GPU-vs-oracle comparisons came to their three bounds (tensor, row, element)."""
+    try:
+        import util
+    except Exception:
+        return
+    if not util.WORST:
+        return
+    terminalreporter.write_line("worst fraction of the parity bounds (tensor / row / element):")
+    for key in sorted(util.WORST):
+        t, r, e = util.WORST[key]
+        terminalreporter.write_line("  %-70s %.3f %.3f %.3f" % (key[:70], t, r, e))

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def _declared():
     names = []
-    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h"):
+    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h", "bamboo_debug.h"):
         text = open(os.path.join(ROOT, "include", h)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names += re.findall(r"\b(?:int|int64_t|uint64_t|const char\s*\*)\s+(\w+)\s*\(", text)
@@ -227,9 +227,59 @@ def test_headers_are_plain_c(tmp_path):
     gcc = shutil.which("gcc")
     if gcc is None:
         pytest.skip("no C compiler")
-    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h"):
+    for h in ("bamboo_stage.h", "bamboo_kernels.h", "bamboo_ends.h", "bamboo_debug.h"):
         src = tmp_path / (h + ".c")
         src.write_text('#include "%s"\nint main(void) { return 0; }\n' % h)
         r = subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"),
                             "-c", str(src), "-o", str(tmp_path / (h + ".o"))], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_merged_program_equals_oracle_bit_exact():
+    """The whole-iteration program of a stage that has taken over its victim (adjacent stages, wrap-around,
+    data-parallel peers)."""
+    n = 0
+    for P, M in itertools.product(range(2, 7), [1, 2, 3, 5, 8, 16]):
+        for s in range(P - 1):
+            assert B.stage_merged_program(_cfg(P, s, M)) == S.merged_program(P, s, M), (P, s, M)
+            n += 1
+        for tf, tb in ((1, 2), (2, 3)):
+            cfg = _cfg(P, P - 1, M, tick_F=tf, tick_B=tb)
+            cfg.wrap = 1
+            assert B.stage_merged_program(cfg) == S.wrap_merged_program(P, M, tf, tb), (P, M, tf, tb)
+    assert n > 80
+    with pytest.raises(B.BambooError) as e:          # the last stage of a plain pipeline has nothing to take over
+        B.stage_merged_program(_cfg(3, 2, 4))
+    assert e.value.status == B.E_STATE
+    with pytest.raises(B.BambooError) as e:
+        B.stage_merged_program(_cfg(3, 0, 4, n_shadow=0))
+    assert e.value.status == B.E_STATE
+
+
+def test_data_parallel_programs_equal_oracle_bit_exact():
+    """Pure data parallelism (Section 5.2): one node, the replica is a peer's model."""
+    for M in (1, 2, 3, 5, 8, 16):
+        for rc in (S.LFLB, S.EFLB):
+            cfg = _cfg(1, 0, M, rc)
+            cfg.data_parallel = 1
+            assert B.stage_program(cfg) == S.stage_program(1, 0, M, rc=rc)
+            assert B.stage_merged_program(cfg) == S.merged_program(1, 0, M)
+            for k_fail in range(M):
+                assert B.stage_failover_program(cfg, k_fail) == \
+                    S.failover_program(1, 0, M, k_fail, rc=rc, data_parallel=True), (M, rc, k_fail)
+    for bad in (dict(P=2), dict(rc_mode=2), dict(n_shadow=0), dict(n_shadow=2), dict(wrap=1), dict(data_parallel=2)):
+        cfg = _cfg(1, 0, 4)
+        cfg.data_parallel = 1
+        for k, v in bad.items():
+            setattr(cfg, k, v)
+        with pytest.raises(B.BambooError) as e:
+            B.stage_query_sizes(cfg)
+        assert e.value.status == B.E_BADCFG, bad
+    # without the flag a one-stage pipeline has no victim
+    with pytest.raises(B.BambooError) as e:
+        B.stage_failover_program(_cfg(1, 0, 4), 0)
+    assert e.value.status == B.E_STATE
+
+
+def test_stage_run_rejects_bad_arguments_without_a_gpu():
+    assert B.lib.stage_run(None, None, 0, None) == B.E_ARG

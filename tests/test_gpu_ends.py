@@ -6,7 +6,7 @@ import torch
 
 from oracle import ends as E
 from paper_2204_12013_amd import synth
-from util import TOL, rel_l2
+from util import TOL, assert_close, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -38,7 +38,7 @@ def test_embedding_forward_and_gradient(B, dtype, V, S, Bsz, H):
     out = torch.empty(T, H, dtype=d_tok.dtype, device=DEV)
     B.bk_embedding_fwd(d_ids, d_tok, d_pos, out)
     tol = TOL[dtype]
-    assert rel_l2(B.to_host(out), want) <= (1e-7 if dtype == 0 else tol)
+    assert_close(B.to_host(out), want, (1e-7 if dtype == 0 else tol), "ends B.to_host(out)")
     # gradients accumulate onto what is there
     init_t = rng.normal(0, 1, (V, H)).astype(np.float32)
     init_p = rng.normal(0, 1, (S, H)).astype(np.float32)
@@ -51,8 +51,8 @@ def test_embedding_forward_and_gradient(B, dtype, V, S, Bsz, H):
     assert torch.equal(runs[0][0], runs[1][0]) and torch.equal(runs[0][1], runs[1][1])     # no atomics
     got_t = runs[0][0].cpu().numpy().astype(np.float64) - init_t
     got_p = runs[0][1].cpu().numpy().astype(np.float64) - init_p
-    assert rel_l2(got_t, wg["E_tok"]) <= 1e-5
-    assert rel_l2(got_p, wg["E_pos"]) <= 1e-5
+    assert_close(got_t, wg["E_tok"], 1e-5, "ends got_t")
+    assert_close(got_p, wg["E_pos"], 1e-5, "ends got_p")
     untouched = np.setdiff1d(np.arange(V), ids)
     assert np.array_equal(runs[0][0].cpu().numpy()[untouched], init_t[untouched])
 
@@ -104,7 +104,7 @@ def test_softmax_cross_entropy(B, dtype, T, V):
     assert abs(d_loss.item() - loss) <= 1e-5 * max(1.0, abs(loss))
     d_dl = torch.empty_like(d_logits)
     B.bk_softmax_xent_bwd(d_logits, d_labels, d_lse, 1.0 / T, d_dl)
-    assert rel_l2(B.to_host(d_dl), dl) <= (1e-5 if dtype == 0 else TOL[dtype])
+    assert_close(B.to_host(d_dl), dl, (1e-5 if dtype == 0 else TOL[dtype]), "ends B.to_host(d_dl)")
     B.bk_softmax_xent_bwd(d_logits, d_labels, d_lse, 1.0 / T, d_logits)      # in place
     assert torch.equal(d_logits, d_dl)
 

@@ -11,7 +11,7 @@ from oracle import optim as O
 from oracle import schedule as S
 from oracle import stage as St
 from paper_2204_12013_amd import synth
-from util import oracle_layers, rel_l2
+from util import assert_close, oracle_layers, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -44,7 +44,8 @@ def test_adam_kernel_matches_oracle(B, dtype, n):
         B.bk_adam(torch.from_numpy(g).to(DEV), master, m, v, w, step, **HP)
         wr, mr, vr = O.adam_step(wr, g.astype(np.float64), mr, vr, step, **HP)
         torch.cuda.synchronize()
-        assert rel_l2(m.cpu().numpy(), mr) <= 1e-6 and rel_l2(v.cpu().numpy(), vr) <= 1e-6
+        assert_close(m.cpu().numpy(), mr, 1e-6, "optimizer first moment")
+        assert_close(v.cpu().numpy(), vr, 1e-6, "optimizer second moment")
         assert np.abs(master.cpu().numpy() - wr).max() <= 1e-6 * HP["lr"] * 50 + 1e-7 * np.abs(wr).max()
         assert torch.equal(w, master.to(act))
 
@@ -96,14 +97,14 @@ def test_training_iterations_match_oracle_fp32():
         O.sync_replica(shadow, successor)
         for k in range(sc.M):
             assert torch.equal(hz.z_frc[k], hz.z_succ[k]), (it, k)        # FRC == successor's forward, bitwise
-            assert rel_l2(B.to_host(hz.z_frc[k]), sim.z_frc[k]) <= 1e-3, (it, k)
+            assert_close(B.to_host(hz.z_frc[k]), sim.z_frc[k], 1e-3, "optimizer B.to_host(hz.z_frc[k]) %s" % ((it, k),))
         assert torch.equal(st.shadow_w, succ.own_w) and torch.equal(st.shadow_opt, succ.own_opt)
         got = st.own_w.cpu().numpy().astype(np.float64).reshape(sc.n_own, -1)
         for l in range(sc.n_own):
             ref = L.pack_layer(own[l], sc.hidden, sc.ffn)
             # Adam divides by the gradient's own magnitude: elements whose gradient is at the level of
             # the fp32 rounding noise may step the other way, so the bar is looser than for gradients
-            assert rel_l2(got[l], ref) <= 1e-3, (it, l)
+            assert_close(got[l], ref, 1e-3, "optimizer got[l] %s" % ((it, l),))
     assert hz.step == 3
     st.stage_destroy()
     succ.stage_destroy()

@@ -8,7 +8,7 @@ import torch
 from oracle import schedule as S
 from oracle import stage as St
 from paper_2204_12013_amd import synth
-from util import TOL, check_grads, oracle_layers, rel_l2
+from util import TOL, assert_close, check_grads, oracle_layers, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -69,10 +69,10 @@ def test_iteration_matches_oracle(B, name):
     hz.sync()
     ref = _oracle(sc, inp)
     for k in range(sc.M):
-        assert rel_l2(B.to_host(hz.y[k]), ref.y[k]) <= tol, ("y", k)
-        assert rel_l2(B.to_host(hz.z_frc[k]), ref.z_frc[k]) <= tol, ("z", k)
-        assert rel_l2(B.to_host(hz.gy[k]), ref.gy[k]) <= tol, ("gy", k)
-        assert rel_l2(B.to_host(hz.gx[k]), ref.gx[k]) <= tol, ("gx", k)
+        assert_close(B.to_host(hz.y[k]), ref.y[k], tol, "stage B.to_host(hz.y[k]) %s" % (("y", k),))
+        assert_close(B.to_host(hz.z_frc[k]), ref.z_frc[k], tol, "stage B.to_host(hz.z_frc[k]) %s" % (("z", k),))
+        assert_close(B.to_host(hz.gy[k]), ref.gy[k], tol, "stage B.to_host(hz.gy[k]) %s" % (("gy", k),))
+        assert_close(B.to_host(hz.gx[k]), ref.gx[k], tol, "stage B.to_host(hz.gx[k]) %s" % (("gx", k),))
         # Section 5.1: FRC is exactly the successor's forward -- bitwise on the GPU
         assert torch.equal(hz.z_frc[k], hz.z_succ[k])
     check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, tol, "own")
@@ -109,8 +109,8 @@ def test_failover_matches_oracle_and_failure_free_run(B, name, k_fail):
     check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, tol, "own")
     check_grads(st.shadow_g.cpu().numpy(), ref.G_shadow, sc.hidden, sc.ffn, tol, "shadow")
     for k in range(sc.M):
-        assert rel_l2(B.to_host(hz.gx[k]), ref.gx[k]) <= tol
-        assert rel_l2(B.to_host(hz.z_frc[k]), ref.z_frc[k]) <= tol
+        assert_close(B.to_host(hz.gx[k]), ref.gx[k], tol, "stage B.to_host(hz.gx[k])")
+        assert_close(B.to_host(hz.z_frc[k]), ref.z_frc[k], tol, "stage B.to_host(hz.z_frc[k])")
     # Sections 1 and 5.2: nothing is lost -- gradients equal the failure-free run's, bitwise
     assert torch.equal(st.own_g, st0.own_g)
     assert torch.equal(st.shadow_g, hz0.succ.own_g)
@@ -149,6 +149,15 @@ def test_misuse_is_rejected_not_undefined(B):
     with pytest.raises(E) as e:
         st.shadow_fwd_frc(0, hz.y[0], None)
     assert e.value.status == B.E_BADMB
+    # the size-query form of the schedule calls must not merge the stage: refused, the stage stays as it was
+    before = st.stage_schedule()
+    assert B.lib.failover_merge(st._h, 1, None, 0) == B.E_ARG
+    small = (B.Instr * 2)()
+    assert B.lib.failover_merge(st._h, 1, small, 2) == B.E_ARG
+    assert st.stage_schedule() == before
+    with pytest.raises(E) as e:
+        st.shadow_bwd_brc(0, hz.gz[0], None)                 # still not merged
+    assert e.value.status == B.E_STATE
     st.failover_merge(1)
     with pytest.raises(E) as e:
         st.failover_merge(1)
@@ -266,8 +275,8 @@ def test_degenerate_configurations_match_oracle_with_and_without_failure(B, name
     hz.sync()
     ref = _oracle(sc, inp)
     for k in range(sc.M):
-        assert rel_l2(B.to_host(hz.y[k]), ref.y[k]) <= tol
-        assert rel_l2(B.to_host(hz.gx[k]), ref.gx[k]) <= tol
+        assert_close(B.to_host(hz.y[k]), ref.y[k], tol, "stage B.to_host(hz.y[k])")
+        assert_close(B.to_host(hz.gx[k]), ref.gx[k], tol, "stage B.to_host(hz.gx[k])")
         assert torch.equal(hz.z_frc[k], hz.z_succ[k])
     check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, tol, "own")
     check_grads(hz.succ.own_g.cpu().numpy(), ref.G_succ, sc.hidden, sc.ffn, tol, "successor")
@@ -309,8 +318,8 @@ def test_single_stage_pipeline_without_replica(B):
     for k in range(sc.M):
         y, caches = L.stack_fwd(sc.arch, own, inp["x"][k].astype(np.float64), sc.micro_batch, sc.seq, sc.heads)
         gx, grads = L.stack_bwd(sc.arch, own, caches, inp["gz"][k].astype(np.float64))
-        assert rel_l2(B.to_host(hz.y[k]), y) <= TOL[sc.dtype]
-        assert rel_l2(B.to_host(hz.gx[k]), gx) <= TOL[sc.dtype]
+        assert_close(B.to_host(hz.y[k]), y, TOL[sc.dtype], "stage B.to_host(hz.y[k])")
+        assert_close(B.to_host(hz.gx[k]), gx, TOL[sc.dtype], "stage B.to_host(hz.gx[k])")
         G = grads if G is None else [{n: a[n] + b[n] for n in a} for a, b in zip(G, grads)]
     check_grads(st.own_g.cpu().numpy(), G, sc.hidden, sc.ffn, TOL[sc.dtype], "own")
     with pytest.raises(B.BambooError) as e:
@@ -349,3 +358,171 @@ def test_gradients_do_not_depend_on_how_the_weight_gradients_are_launched(B, nam
     assert torch.equal(grads[0][1], grads[1][1])
     for a, b in zip(grads[0][2], grads[1][2]):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name,k_fail", [("tiny", 2), ("bf16_post_ln", 3), ("bf16_causal_d128", 0)])
+def test_iteration_after_the_failover_runs_the_merged_program(B, name, k_fail):
+    """Section 5.2: in the iterations after a preemption the shadow node executes all of the victim's
+    instructions.  After failover_merge the next stage_begin_iteration installs the merged stage's
+    whole-iteration program: it equals the oracle's list, the stage behaves as one stage of own + replica
+    layers (against the oracle), and with the same parameters and inputs it ends with bitwise the
+    gradients of the failure-free iteration (own, and the successor's in the replica buffer)."""
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc = SMALL[name]
+    tol = TOL[sc.dtype]
+    inp, st0, hz0 = _build(B, sc)
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+    _, st, hz = _build(B, sc)
+    hz.begin_iteration()
+    hz.run(split_at_failure(st.stage_schedule(), k_fail))
+    hz.succ.stage_sync()
+    hz.run(st.failover_merge(k_fail))
+    hz.sync()
+    # second iteration: merged from the start
+    hz.begin_iteration()
+    prog = st.stage_schedule()
+    assert prog == S.merged_program(sc.P, sc.stage_id, sc.M) == B.stage_merged_program(st.cfg)
+    hz.run(prog)
+    hz.sync()
+    assert torch.equal(st.own_g, st0.own_g)
+    assert torch.equal(st.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz.gx[k], hz0.gx[k])
+        assert torch.equal(hz.z_frc[k], hz0.z_succ[k])
+        assert torch.equal(hz.gy[k], hz0.gy[k])            # BRC's input gradient is what the victim used to send
+    own = oracle_layers(inp["own_w"], sc.hidden, sc.ffn)
+    shadow = oracle_layers(inp["shadow_w"], sc.hidden, sc.ffn)
+    x = {k: inp["x"][k].astype(np.float64) for k in range(sc.M)}
+    gz = {k: inp["gz"][k].astype(np.float64) for k in range(sc.M)}
+    sim = St.StageSim(sc.arch, own, shadow, sc.micro_batch, sc.seq, sc.heads, sc.P, sc.stage_id, sc.M, x, gz)
+    sim.preempt_successor()
+    sim.run(S.merged_program(sc.P, sc.stage_id, sc.M))
+    check_grads(st.own_g.cpu().numpy(), sim.G_own, sc.hidden, sc.ffn, tol, "merged own")
+    check_grads(st.shadow_g.cpu().numpy(), sim.G_shadow, sc.hidden, sc.ffn, tol, "merged replica")
+    for k in range(sc.M):
+        assert_close(B.to_host(hz.z_frc[k]), sim.z_frc[k], tol, "stage merged z")
+        assert_close(B.to_host(hz.gx[k]), sim.gx[k], tol, "stage merged gx")
+    for s_ in (st0, st, hz0.succ, hz.succ):
+        s_.stage_destroy()
+
+
+def test_stage_run_stops_where_the_hook_reports_a_lost_peer(B):
+    """Section 4: a lost neighbour shows at a communication instruction.  stage_run hands every such
+    instruction to the caller's hook and, when the hook says the peer is gone, stops before it and
+    returns its index; the caller then merges and runs the failover schedule -- same gradients as a
+    failure-free iteration, bitwise."""
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc = SMALL["bf16_post_ln"]
+    k_fail = 2
+    inp, st0, hz0 = _build(B, sc)
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+    _, st, hz = _build(B, sc)
+    hz.begin_iteration()
+    prog = st.stage_schedule()
+    seen = []
+
+    def comm(op, lane, k, arg):
+        seen.append((op, k))
+        if op == B.SEND_ACT and k == k_fail and arg == sc.stage_id + 1:
+            return True                                 # handing over micro-batch k_fail fails
+        return hz._comm(op, lane, k, arg)
+    n = st.stage_run(prog, x=hz.x, y=hz.y, z=hz.z_frc, gy=hz.gy, gx=hz.gx, gz=hz.gz, comm=comm)
+    assert prog[n][0] == B.SEND_ACT and prog[n][2] == k_fail and 0 < n < len(prog)
+    ran = prog[:n]
+    assert ran[:len(split_at_failure(prog, k_fail))] == split_at_failure(prog, k_fail)      # FWD(k_fail) and its FRC ran
+    assert all(i[0] in (B.BUBBLE, B.SEND_GRAD) for i in ran[len(split_at_failure(prog, k_fail)):])
+    hz.bwd_done = {i[2] for i in prog[:n] if i[0] == B.BWD}
+    hz.succ.stage_sync()
+    hz.run(st.failover_merge(k_fail))
+    hz.sync()
+    assert torch.equal(st.own_g, st0.own_g) and torch.equal(st.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz.gx[k], hz0.gx[k])
+    # misuse: tables that an instruction needs are missing
+    with pytest.raises(B.BambooError) as e:
+        st.stage_begin_iteration()
+        st.stage_run([(B.FWD, 0, 0, 0)], x=None, y=hz.y)
+    assert e.value.status == B.E_ARG
+    with pytest.raises(B.BambooError) as e:
+        st.stage_run([(B.FWD, 0, sc.M, 0)], x=hz.x, y=hz.y)
+    assert e.value.status == B.E_BADMB
+    for s_ in (st0, st, hz0.succ, hz.succ):
+        s_.stage_destroy()
+
+
+@pytest.mark.parametrize("dtype,rc", [(0, 1), (1, 1), (1, 0)])
+def test_pure_data_parallel_node_matches_oracle_and_recovers_the_peers_gradient(B, dtype, rc):
+    """Section 5.2, "Support for Pure Data Parallelism": the node holds the whole model and the replica of a
+    peer's model; eager FRC is the forward of the peer's minibatch beside its own (over-batching), lazy
+    BRC rebuilds the peer's gradient when the peer is lost.  Against the oracle, and bitwise against a
+    second stage object playing the peer."""
+    from paper_2204_12013_amd.harness import StageHarness, split_at_failure
+    sc = synth.StageConfig("dp", 1, dtype, 256 if dtype else 72, 4 if dtype else 3, 1024 if dtype else 200,
+                           160 if dtype else 21, 2, 2, 2, 1, 0, 4, 31)
+    tol = TOL[sc.dtype]
+    inp = synth.make_stage_inputs(sc)
+    peer_in = synth.make_stage_inputs(sc.replace(seed=sc.seed + 1))      # the peer's minibatch and upstream gradients
+    dev = lambda a: B.to_device(a, sc.dtype)
+    cfg = B.make_cfg(sc, rc_mode=rc, data_parallel=1)
+    x, g = [dev(inp["x"][k]) for k in range(sc.M)], [dev(inp["gz"][k]) for k in range(sc.M)]
+    xn, gn = [dev(peer_in["x"][k]) for k in range(sc.M)], [dev(peer_in["gz"][k]) for k in range(sc.M)]
+
+    def node():
+        st = B.Stage(cfg, dev(inp["own_w"].reshape(-1)), dev(inp["shadow_w"].reshape(-1)))
+        return st, StageHarness(st, x, gn, gy_table=g, frc_in=xn)
+    # the peer itself: its own model (= the replica's values) on its own minibatch
+    peer = B.Stage(B.make_cfg(sc.replace(n_shadow=0), frc_enabled=False), dev(inp["shadow_w"].reshape(-1)), None)
+    hp = StageHarness(peer, xn, gn, gy_table=gn)
+    torch.cuda.synchronize()
+    hp.begin_iteration()
+    hp.run(peer.stage_schedule())
+    hp.sync()
+    st0, hz0 = node()
+    prog = st0.stage_schedule()
+    assert prog == S.stage_program(1, 0, sc.M, rc=rc)
+    hz0.begin_iteration()
+    hz0.run(prog)
+    hz0.sync()
+    if rc == 1:
+        for k in range(sc.M):
+            assert torch.equal(hz0.z_frc[k], hp.y[k])           # FRC == the peer's own forward, bitwise
+    args = (sc.arch, oracle_layers(inp["own_w"], sc.hidden, sc.ffn), oracle_layers(inp["shadow_w"], sc.hidden, sc.ffn),
+            sc.micro_batch, sc.seq, sc.heads, sc.M,
+            {k: inp["x"][k].astype(np.float64) for k in range(sc.M)}, {k: inp["gz"][k].astype(np.float64) for k in range(sc.M)},
+            {k: peer_in["x"][k].astype(np.float64) for k in range(sc.M)},
+            {k: peer_in["gz"][k].astype(np.float64) for k in range(sc.M)})
+    for k_fail in (0, 2, sc.M - 1):
+        st, hz = node()
+        hz.begin_iteration()
+        hz.run(split_at_failure(prog, k_fail))
+        merged = st.failover_merge(k_fail)
+        assert merged == S.failover_program(1, 0, sc.M, k_fail, rc=rc, data_parallel=True)
+        hz.run(merged)
+        hz.sync()
+        assert torch.equal(st.own_g, st0.own_g)
+        assert torch.equal(st.shadow_g, peer.own_g)              # exactly what the peer would have contributed
+        for k in range(sc.M):
+            assert torch.equal(hz.gx[k], hz0.gx[k])
+            assert torch.equal(hz.gy_replay[k], hp.gx[k])        # BRC's input gradient == the peer's own
+        sim = St.DataParallelSim(*args)
+        sim.run(S.prefix_until_failure(1, 0, sc.M, k_fail, rc=rc))
+        sim.preempt_neighbour()
+        sim.run(S.failover_program(1, 0, sc.M, k_fail, rc=rc, data_parallel=True))
+        check_grads(st.own_g.cpu().numpy(), sim.G_own, sc.hidden, sc.ffn, tol, "data-parallel own")
+        check_grads(st.shadow_g.cpu().numpy(), sim.G_shadow, sc.hidden, sc.ffn, tol, "data-parallel replica")
+        for k in range(sc.M):
+            assert_close(B.to_host(hz.z_frc[k]), sim.z_frc[k], tol, "stage data-parallel z")
+            assert_close(B.to_host(hz.gx[k]), sim.gx[k], tol, "stage data-parallel gx")
+        # the next iteration: both minibatches from the start
+        hz.begin_iteration()
+        assert st.stage_schedule() == S.merged_program(1, 0, sc.M)
+        hz.run(st.stage_schedule())
+        hz.sync()
+        assert torch.equal(st.own_g, st0.own_g) and torch.equal(st.shadow_g, peer.own_g)
+        st.stage_destroy()
+    for s_ in (st0, peer):
+        s_.stage_destroy()

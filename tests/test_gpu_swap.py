@@ -10,7 +10,7 @@ import torch
 from oracle import schedule as S
 from paper_2204_12013_amd import synth
 from test_gpu_stage import SMALL, _oracle
-from util import TOL, check_grads
+from util import TOL, assert_close, check_grads
 
 pytestmark = pytest.mark.gpu
 

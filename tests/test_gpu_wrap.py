@@ -10,7 +10,7 @@ from oracle import ends as E
 from oracle import schedule as S
 from oracle import stage as St
 from paper_2204_12013_amd import synth
-from util import TOL, check_grads, oracle_layers, rel_l2
+from util import TOL, assert_close, check_grads, oracle_layers, rel_l2
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -98,8 +98,7 @@ def _oracle(sc, V, inp, ein, k_fail=None):
 def _check_named(got_flat, want, unpack, tol, label):
     got = unpack(got_flat.cpu().numpy())
     for n, w in want.items():
-        e = rel_l2(got[n], w)
-        assert e <= tol, "%s %s: rel L2 %.3e > %.1e" % (label, n, e, tol)
+        assert_close(got[n], w, tol, "wrap %s gradient: %s" % (label, n))
 
 
 def _check_against_oracle(B, sc, V, st, en, hz, ref):
@@ -109,8 +108,8 @@ def _check_against_oracle(B, sc, V, st, en, hz, ref):
     loss = hz.loss.cpu().numpy()
     for k in range(sc.M):
         assert abs(loss[k] - ref.loss[k]) <= tol * abs(ref.loss[k]), (k, loss[k], ref.loss[k])
-        assert rel_l2(B.to_host(hz.gx[k]), ref.gx[k]) <= tol
-        assert rel_l2(B.to_host(hz.z_frc[k]), ref.z_frc[k]) <= tol
+        assert_close(B.to_host(hz.gx[k]), ref.gx[k], tol, "wrap B.to_host(hz.gx[k])")
+        assert_close(B.to_host(hz.z_frc[k]), ref.z_frc[k], tol, "wrap B.to_host(hz.z_frc[k])")
 
 
 @pytest.mark.parametrize("name", list(WRAP))
@@ -248,12 +247,12 @@ def test_ends_at_the_bert_large_size(B):
     want_loss, _, cache = E.back_fwd(sc.arch, back, y.astype(np.float64), ein["labels"][0].astype(np.int64))
     want_gy, want_gb = E.back_bwd(sc.arch, back, cache)
     assert abs(loss.item() - want_loss) <= tol * want_loss
-    assert rel_l2(B.to_host(gy), want_gy) <= tol
+    assert_close(B.to_host(gy), want_gy, tol, "wrap B.to_host(gy)")
     _check_named(en.back_g, want_gb, lambda a: E.unpack_back(a, sc.arch, V, sc.hidden), tol, "back")
     del cache, want_gb
     front = E.unpack_front(ein["front_w"], sc.arch, V, sc.seq, sc.hidden)
     want_x0, cf = E.front_fwd(sc.arch, front, ein["ids"][0].astype(np.int64), sc.seq)
-    assert rel_l2(B.to_host(x0), want_x0) <= tol
+    assert_close(B.to_host(x0), want_x0, tol, "wrap B.to_host(x0)")
     want_gf = E.front_bwd(sc.arch, front, cf, dx0.astype(np.float64))
     _check_named(en.front_g, want_gf, lambda a: E.unpack_front(a, sc.arch, V, sc.seq, sc.hidden), tol, "front")
     en.ends_destroy()

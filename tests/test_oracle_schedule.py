@@ -288,3 +288,92 @@ def test_wrap_around_failover_program_invariants():
                         live.add(k)
                     elif op == S.BWD:
                         live.remove(k)
+
+
+def test_merged_program_structure():
+    """Rules 1-4 of Section 5.2 on the merged stage's whole iteration: no traffic between victim and
+    shadow is left, every group leads with its communication (the victim's external traffic before the
+    shadow's own), backward work precedes forward work, every micro-batch has exactly one FWD, FRC,
+    BRC and BWD, and the order of the own computations is the stage's 1F1B order."""
+    for P in range(2, 7):
+        for s in range(P - 1):
+            for M in (1, 2, 3, 5, 8):
+                prog = S.merged_program(P, s, M)
+                assert prog[-3:] == [(S.JOIN, 0, -1, -1), (S.ALLREDUCE, 0, -1, 0), (S.APPLY, 0, -1, 0)]
+                assert all(lane == 0 for _, lane, _, _ in prog)
+                assert not any(op in (S.SEND_ACT, S.RECV_GRAD) and arg == s + 1 for op, _, _, arg in prog)
+                for op in (S.FWD, S.FRC, S.BRC, S.BWD):
+                    assert sorted(k for o, _, k, _ in prog if o == op) == list(range(M))
+                own = [("F" if op == S.FWD else "B", k) for op, _, k, _ in prog if op in (S.FWD, S.BWD)]
+                assert own == S.compute_order(P, s, M)
+                pos = {(op, k): i for i, (op, _, k, _) in enumerate(prog)}
+                for k in range(M):
+                    assert pos[(S.FWD, k)] < pos[(S.FRC, k)] < pos[(S.BRC, k)] < pos[(S.BWD, k)]
+                    if s + 2 < P:      # the victim's external traffic exists and brackets its work
+                        assert pos[(S.FRC, k)] < pos[(S.SEND_ACT, k)] < pos[(S.RECV_GRAD, k)] < pos[(S.BRC, k)]
+                    else:
+                        assert (S.SEND_ACT, k) not in pos and (S.RECV_GRAD, k) not in pos
+                    if s > 0:
+                        assert pos[(S.RECV_ACT, k)] < pos[(S.FWD, k)] and pos[(S.BWD, k)] < pos[(S.SEND_GRAD, k)]
+                # inside a run of instructions between computations, communication never follows computation
+                comm = (S.SEND_ACT, S.RECV_ACT, S.SEND_GRAD, S.RECV_GRAD)
+                groups, cur = [], []
+                for ins in prog[:-3]:
+                    if ins[0] in comm and cur and cur[-1][0] not in comm:
+                        groups.append(cur)
+                        cur = []
+                    cur.append(ins)
+                groups.append(cur)
+                for grp in groups if s + 2 < P else []:     # (groups show only where every one of them has traffic)
+                    ops = [i[0] for i in grp if i[0] not in comm]
+                    if S.BWD in ops and S.FWD in ops:
+                        assert ops.index(S.BWD) < ops.index(S.FWD)          # rule 4
+                    far = [i for i, ins in enumerate(grp) if ins[0] in comm and ins[3] == s + 2]
+                    near = [i for i, ins in enumerate(grp) if ins[0] in comm and ins[3] == s - 1]
+                    if far and near:
+                        assert max(far) < min(near)                            # rule 3
+    # the failover schedule's last part, started at the first computation, is the same list
+    full = S.merged_program(4, 1, 8)
+    tail = S.failover_program(4, 1, 8, 0)
+    i = next(i for i, ins in enumerate(tail) if ins[0] == S.BRC and ins[2] == 0)
+    j = next(i for i, ins in enumerate(full) if ins[0] == S.BRC and ins[2] == 0)
+    assert [ins for ins in tail[i:] if ins[0] not in (S.SEND_ACT,)] == [ins for ins in full[j:] if ins[0] not in (S.SEND_ACT,)]
+
+
+def test_data_parallel_programs():
+    """Pure data parallelism (Section 5.2): one node, no bubbles, no communication before the
+    all-reduce; eager FRC sits beside every forward."""
+    M = 5
+    prog = S.stage_program(1, 0, M)
+    assert [(op, lane, k) for op, lane, k, _ in prog[:-3]] == [
+        t for k in range(M) for t in ((S.FWD, 0, k), (S.FRC, 1, k), (S.BWD, 0, k))]
+    assert not any(op == S.BUBBLE for op, _, _, _ in prog)
+    assert S.own_slots(1, 0, M) == 1
+    merged = S.merged_program(1, 0, M)
+    assert [(op, k) for op, _, k, _ in merged[:-3]] == [
+        (S.FWD, 0), (S.FRC, 0)] + [t for k in range(M - 1) for t in ((S.BRC, k), (S.BWD, k), (S.FWD, k + 1), (S.FRC, k + 1))
+                                   ] + [(S.BRC, M - 1), (S.BWD, M - 1)]
+    for k_fail in range(M):
+        f = S.failover_program(1, 0, M, k_fail, data_parallel=True)
+        assert f[0] == (S.JOIN, 0, -1, k_fail)
+        assert [k for op, _, k, _ in f if op == S.BRC] == list(range(M))
+        assert [k for op, _, k, _ in f if op == S.FRC] == list(range(k_fail + 1, M))
+
+
+def test_wrap_merged_program_structure():
+    for P in (2, 3, 4, 6):
+        for M in (1, 3, 4, 8):
+            prog = S.wrap_merged_program(P, M)
+            for op in (S.FWD, S.FRC, S.BRC, S.BWD):
+                assert sorted(k for o, _, k, _ in prog if o == op) == list(range(M))
+            pos = {(op, k): i for i, (op, _, k, _) in enumerate(prog)}
+            for k in range(M):
+                # the first stage's forward of a micro-batch precedes the last stage's, its backward follows it
+                assert pos[(S.FRC, k)] < pos[(S.FWD, k)] < pos[(S.BWD, k)] < pos[(S.BRC, k)]
+            own = [("F" if op == S.FWD else "B", k) for op, _, k, _ in prog if op in (S.FWD, S.BWD)]
+            vic = [("F" if op == S.FRC else "B", k) for op, _, k, _ in prog if op in (S.FRC, S.BRC)]
+            assert own == S.compute_order(P, P - 1, M) and vic == S.compute_order(P, 0, M)
+            # the failover schedule for a loss at the very first micro-batch ends the same way
+            f = S.wrap_failover_program(P, M, 0)
+            last = lambda p: [i for i in p if i[0] in (S.FWD, S.BWD, S.FRC, S.BRC)][-2 * M:]
+            assert last(f) == last(prog)

@@ -175,3 +175,94 @@ def test_wrap_around_failover_rebuilds_the_first_stage_gradients():
         for n in Gfv:
             np.testing.assert_allclose(sim.G_front[n], Gfv[n], rtol=0, atol=1e-12)
         assert sim.loss == ref.loss
+
+
+def test_merged_iteration_is_one_deep_stage():
+    """Section 5.2: until the pipeline is reconfigured the shadow node executes all of the victim's
+    instructions.  A whole iteration of the merged program must therefore be an ordinary stage of
+    own + replica layers: outputs, input gradients and both gradient sets equal one deep stack's."""
+    for arch, P, s, M in [(0, 4, 1, 5), (1, 3, 0, 4), (0, 2, 0, 3), (1, 5, 3, 6)]:
+        arch, own, shadow, B, S_len, n_h, P, s, M, x, gz = _setup(arch, P, s, M, n_own=2, n_shadow=2, seed=P + M)
+        sim = St.StageSim(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz)
+        sim.preempt_successor()
+        sim.run(S.merged_program(P, s, M))
+        assert not sim.own_stash and not sim.shadow_stash
+        G = None
+        for k in range(M):
+            z, caches = L.stack_fwd(arch, own + shadow, x[k], B, S_len, n_h)
+            gx, grads = L.stack_bwd(arch, own + shadow, caches, gz[k])
+            np.testing.assert_allclose(sim.z_frc[k], z, rtol=0, atol=1e-13)
+            np.testing.assert_allclose(sim.gx[k], gx, rtol=0, atol=1e-13)
+            G = grads if G is None else [{n: a[n] + b[n] for n in L.PARAM_NAMES} for a, b in zip(G, grads)]
+        for got, want in zip(sim.G_own + sim.G_shadow, G):
+            for n in L.PARAM_NAMES:
+                np.testing.assert_allclose(got[n], want[n], rtol=0, atol=1e-12)
+        # and it is what the failure-free pair of stages accumulates (same order of additions: bitwise)
+        ref = St.run_no_failure(arch, own, shadow, B, S_len, n_h, P, s, M, x, gz)
+        for a, b in zip(sim.G_shadow, ref.G_succ):
+            for n in L.PARAM_NAMES:
+                assert np.array_equal(a[n], b[n])
+        for a, b in zip(sim.G_own, ref.G_own):
+            for n in L.PARAM_NAMES:
+                assert np.array_equal(a[n], b[n])
+
+
+def _dp_setup(arch, M, seed=0, same_weights=False):
+    H, n_h, F, S_len, B = 8, 2, 16, 4, 1
+    rng = np.random.default_rng(seed)
+    own = _layers(rng, 2, H, F)
+    replica = [dict(p) for p in own] if same_weights else _layers(rng, 2, H, F)
+    mk = lambda: {k: rng.standard_normal((B * S_len, H)) for k in range(M)}
+    return (arch, own, replica, B, S_len, n_h, M, mk(), mk(), mk(), mk())
+
+
+def test_data_parallel_eager_frc_is_over_batching():
+    """Section 5.2, pure data parallelism: eager FRC amounts to the node processing its own minibatch
+    plus a redundant one.  With equal parameters (a synchronous job) the node's own gradient plus the
+    replica's, after BRC, must be the gradient of ONE pass over the two minibatches put together."""
+    for arch in (0, 1):
+        M = 3
+        args = _dp_setup(arch, M, seed=5 + arch, same_weights=True)
+        arch, own, replica, B, S_len, n_h, M, x, g, xn, gn = args
+        sim = St.DataParallelSim(*args).run(S.merged_program(1, 0, M))
+        G = None
+        for k in range(M):
+            both_x, both_g = np.concatenate([x[k], xn[k]]), np.concatenate([g[k], gn[k]])
+            _, caches = L.stack_fwd(arch, own, both_x, 2 * B, S_len, n_h)
+            _, grads = L.stack_bwd(arch, own, caches, both_g)
+            G = grads if G is None else [{n: a[n] + b[n] for n in L.PARAM_NAMES} for a, b in zip(G, grads)]
+        for l in range(len(own)):
+            for n in L.PARAM_NAMES:
+                np.testing.assert_allclose(sim.G_own[l][n] + sim.G_shadow[l][n], G[l][n], rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("rc", [S.LFLB, S.EFLB])
+def test_data_parallel_failover_rebuilds_the_lost_nodes_gradient(rc):
+    """Whatever micro-batch the loss of the other node falls on, the iteration ends with this node's own
+    gradient and, in the replica, exactly the gradient the lost node would have contributed to the
+    all-reduce (brute force, every k_fail; different parameter values in the replica so that a mix-up
+    of the two parameter sets cannot cancel)."""
+    M = 4
+    args = _dp_setup(1, M, seed=9)
+    arch, own, replica, B, S_len, n_h, M, x, g, xn, gn = args
+    ref = St.DataParallelSim(*args)
+    ref.run(S.stage_program(1, 0, M, rc=rc))
+    z_neigh = [ref._neighbour_step(k) for k in range(M)]        # what the other node computes itself
+    assert not any(op in (S.SEND_ACT, S.RECV_ACT, S.SEND_GRAD, S.RECV_GRAD)
+                   for op, _, _, _ in S.stage_program(1, 0, M, rc=rc))
+    for k_fail in range(M):
+        sim = St.DataParallelSim(*args)
+        sim.run(S.prefix_until_failure(1, 0, M, k_fail, rc=rc))
+        sim.preempt_neighbour()
+        prog = S.failover_program(1, 0, M, k_fail, rc=rc, data_parallel=True)
+        sim.run(prog)
+        assert not any(op in (S.SEND_ACT, S.RECV_ACT, S.SEND_GRAD, S.RECV_GRAD) for op, _, _, _ in prog)
+        assert sorted(k for op, _, k, _ in prog if op == S.BRC) == list(range(M))      # every micro-batch once
+        assert not sim.own_stash and not sim.shadow_stash
+        for l in range(len(own)):
+            for n in L.PARAM_NAMES:
+                assert np.array_equal(sim.G_own[l][n], ref.G_own[l][n])
+                assert np.array_equal(sim.G_shadow[l][n], ref.G_neigh[l][n]), (k_fail, l, n)
+        for k in range(M):
+            assert np.array_equal(sim.z_frc[k], z_neigh[k])
+            assert np.array_equal(sim.gx[k], ref.gx[k])
