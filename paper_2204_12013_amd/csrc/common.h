@@ -100,12 +100,6 @@ struct GemmDesc {
   // column-sum launch behind them).
   float* tile_colsum;
   int* tile_colsum_parts;
-  // set by the MFMA launchers: width of the strips the tile sequence walks (see tile_walk)
-  int strip;
-  // set by the MFMA launchers for launches of many rounds of tiles with a memory-heavy epilogue: the first
-  // stagger_wgs workgroups (one round) start (blockIdx / 8) % 8 times stagger_ticks of the device wall clock
-  // late, so that the CUs do not reach their epilogues all at once (0: no stagger)
-  int stagger_ticks, stagger_wgs;
 };
 
 // Ordered final sums of partial rows (see launch_grad_reduce below): out0[c] += sum_y p0[y][c] over `parts`

@@ -381,35 +381,21 @@ __device__ __forceinline__ void write_tile(const GemmDesc& d, f32x16 (&acc)[WM][
   }
 }
 
-// Tile order.  Consecutive workgroup ids are spread round-robin over the 8 XCDs, each with its own L2, and
-// an operand panel (the rows of A of one tile row, the columns of B of one tile column) is fetched into
-// every L2 whose XCD works on a tile that needs it.  So (1) every XCD gets a contiguous range of the
-// launch's tile sequence (xcd_chunk), and (2) the sequence walks strips laid across the SHORT side of the
-// tile grid, `strip` tiles wide, fast index across the strip: a range of n tiles then covers about
-// strip + n / strip panels, least for strip ~ sqrt(n), and the tiles an XCD works on at one time share
-// their panels in its L2.  The host picks strip from the tiles per XCD (tile_strip below).
-__device__ __forceinline__ int xcd_chunk(int pid, int total) {
-  const int per = total / 8;
-  return pid < per * 8 ? (pid % 8) * per + pid / 8 : pid;
-}
-__device__ __forceinline__ void tile_walk(int pid, int tiles_m, int tiles_n, int strip, int* tm, int* tn) {
-  if (tiles_n <= tiles_m) {      // strips of columns, walked row by row
-    const int width = strip * tiles_m;
-    const int first_n = (pid / width) * strip;
-    const int cols = min(tiles_n - first_n, strip);
-    *tn = first_n + (pid % width) % cols;
-    *tm = (pid % width) / cols;
-  } else {                        // strips of rows, walked column by column
-    const int width = strip * tiles_n;
-    const int first_m = (pid / width) * strip;
-    const int rows = min(tiles_m - first_m, strip);
-    *tm = first_m + (pid % width) % rows;
-    *tn = (pid % width) / rows;
-  }
-}
-// a single problem's launch: XCD ranges, then the walk
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int strip, int* tm, int* tn) {
-  tile_walk(xcd_chunk(pid, tiles_m * tiles_n), tiles_m, tiles_n, strip, tm, tn);
+// Tile order: consecutive workgroup ids are spread round-robin over the 8 XCDs,
+// each with its own L2.  Give every XCD a contiguous range of tiles, and inside
+// the range walk down GROUP rows of tiles before moving to the next column, so
+// that the tiles an XCD works on at one time share operand slices in its L2.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int* tm, int* tn) {
+  const int nb = tiles_m * tiles_n;
+  const int per = nb / 8;
+  if (pid < per * 8) pid = (pid % 8) * per + pid / 8;
+  constexpr int GROUP = 8;
+  const int width = GROUP * tiles_n;
+  const int group = pid / width;
+  const int first_m = group * GROUP;
+  const int rows = min(tiles_m - first_m, GROUP);
+  *tm = first_m + (pid % width) % rows;
+  *tn = (pid % width) / rows;
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI>
@@ -421,7 +407,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDesc d) {
   const int wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;       // 2 x 2 wavefronts
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, max(d.strip, 1), &tile_m, &tile_n);
+  tile_of_block(blockIdx.x, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const bf16_t* A = (const bf16_t*)d.A;
   const bf16_t* B = (const bf16_t*)d.B;
@@ -703,9 +689,7 @@ __device__ __forceinline__ void wait_loads_and_lds() {
 // Slices are kept in NS LDS buffers used round-robin; the global -> LDS loads of slice kt + NS - 1 ... are
 // in flight while slice kt feeds the MFMAs, i.e. a load has NS - 1 slices of MFMA time to land.
 // pid: index of this workgroup's tile among the tiles of problem d
-// GROUPED: pid is already a position in the problem's tile sequence (the launch has dealt the XCD ranges
-// over all of its problems)
-template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS, bool GROUPED = false>
+template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
 __device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
   typedef SmemPl<WM, WN, NS, EPI == EPI_BIAS_GELU> SM;
   typedef PlLoop<WM, WN, A_K, B_K> Loop;
@@ -717,23 +701,10 @@ __device__ __forceinline__ void gemm_pl_body(const GemmDesc& d, int pid) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  if (GROUPED) tile_walk(pid, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, max(d.strip, 1), &tile_m, &tile_n);
-  else tile_of_block(pid, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, max(d.strip, 1), &tile_m, &tile_n);
+  tile_of_block(pid, (d.M + BM - 1) / BM, (d.N + BN - 1) / BN, &tile_m, &tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const long lda = A_K ? d.a_sm : d.a_sk;
   const long ldb = B_K ? d.b_sn : d.b_sk;
-
-  // Phase stagger (fp32 read-modify-write form over many rounds): all tiles of a launch take the same time,
-  // so without it every CU reaches its epilogue at the same moment, the memory system serves 256 epilogues
-  // at once while no MFMA runs, and then idles while all of them run their main loops.  Delaying the first
-  // round's workgroups by eighths of a tile time spreads the epilogues over the tile period; the order
-  // holds for the rest of the launch because a CU's next workgroup starts when its last one ends.  The
-  // wait is bounded by the free-running device clock and by an iteration cap.
-  if (EPI == EPI_ACC_F32 && d.stagger_ticks > 0 && (int)blockIdx.x < d.stagger_wgs) {
-    const long long wait = (long long)((blockIdx.x >> 3) & 7) * d.stagger_ticks;
-    const long long t0 = wall_clock64();
-    for (int it = 0; it < 8192 && wall_clock64() - t0 < wait; ++it) __builtin_amdgcn_s_sleep(32);
-  }
 
   Loop L;
   Loop::OpA::load_offsets(L.offA, lda, m0, d.M);
@@ -850,35 +821,21 @@ __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_kernel(GemmDesc d) {
 // tile to the next one's without the chip draining in between.
 template <int WM, int WN, int NS, int MINB>
 __global__ __launch_bounds__(256, MINB) void gemm_mfma_pl_group_kernel(GemmGroup g) {
-  const int total = g.first[GemmGroup::MAX];
-  if ((int)blockIdx.x >= total) {                  // behind the GEMM tiles: the reductions riding along
+  const int b = blockIdx.x;
+  if (b >= g.first[GemmGroup::MAX]) {              // behind the GEMM tiles: the reductions riding along
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    colreduce_batch_block(g.tail, (int)blockIdx.x - total, (float*)smem_raw);
+    colreduce_batch_block(g.tail, b - g.first[GemmGroup::MAX], (float*)smem_raw);
     return;
   }
-  // Every XCD takes one contiguous range of the concatenated tile sequences, so a problem's operands go
-  // to the L2s of the few XCDs its range spans instead of to all eight.
-  const int b = xcd_chunk(blockIdx.x, total);
   int p = 0;
 #pragma unroll
   for (int q = 1; q < GemmGroup::MAX; ++q)
     if (q < g.n && b >= g.first[q]) p = q;
-  gemm_pl_body<WM, WN, false, false, EPI_ACC_F32, NS, true>(g.d[p], b - g.first[p]);
-}
-
-// Strip width of the tile walk for a launch of `total` tiles: about the square root of the tiles per XCD
-// (see tile_walk), at least 8, at most the short side of the problem's tile grid.
-static int tile_strip(long total, int tiles_m, int tiles_n) {
-  int g = 8;
-  while ((long)(g + 1) * (g + 1) * 8 <= total) ++g;
-  const int shorter = tiles_m < tiles_n ? tiles_m : tiles_n;
-  return g < shorter ? g : shorter;
+  gemm_pl_body<WM, WN, false, false, EPI_ACC_F32, NS>(g.d[p], b - g.first[p]);
 }
 
 template <int WM, int WN, bool A_K, bool B_K, int EPI, int NS>
-static hipError_t launch_pl(hipStream_t s, const GemmDesc& d_in, int tiles) {
-  GemmDesc d = d_in;
-  d.strip = tile_strip(tiles, (d.M + 64 * WM - 1) / (64 * WM), (d.N + 64 * WN - 1) / (64 * WN));
+static hipError_t launch_pl(hipStream_t s, const GemmDesc& d, int tiles) {
   typedef SmemPl<WM, WN, NS, EPI == EPI_BIAS_GELU> SM;
   constexpr auto kern = gemm_mfma_pl_kernel<WM, WN, A_K, B_K, EPI, NS, (2 * SM::BYTES <= 160 * 1024 ? 2 : 1)>;
   const hipError_t e = ensure_lds_attribute<kern, SM::BYTES>();
@@ -911,9 +868,7 @@ static hipError_t launch_cfg(hipStream_t s, const GemmDesc& d, int ns) {
   constexpr auto kern = gemm_mfma_kernel<WM, WN, A_K, B_K, EPI>;
   const hipError_t e = ensure_lds_attribute<kern, SM::BYTES>();
   if (e != hipSuccess) return e;
-  GemmDesc dd = d;
-  dd.strip = tile_strip(tiles, (d.M + 64 * WM - 1) / (64 * WM), (d.N + 64 * WN - 1) / (64 * WN));
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, dd);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), SM::BYTES, s, d);
   return hipGetLastError();
 }
 
@@ -937,8 +892,8 @@ static const TileCost kCostStore[] = {     // bf16 output (forward and input-gra
     {11, 2, 1.96f, 0.377f, 3.94f}, {11, 4, 1.48f, 0.396f, 5.05f}, {22, 2, 5.04f, 0.949f, 0.35f},
     {22, 3, 4.52f, 0.545f, 1.60f}, {24, 2, 4.93f, 1.068f, 5.59f}, {24, 3, 7.76f, 0.816f, 1.45f},
     {42, 2, 1.85f, 1.107f, 8.18f}, {42, 3, 5.44f, 0.874f, 2.50f}, {44, 2, 14.98f, 1.281f, 0.58f},
-    // 256 x 192 (N = 3 H of the QKV projection is 16 x 192 when H = 1024, i.e. with 4096 tokens exactly 256
-    // tiles; N = 12288 is 64 x 192); coefficients scaled from the 256 x 256 tile's
+    // 256 x 192 (offered for the bias-only forward form: N = 3 H of the QKV projection is 16 x 192 when
+    // H = 1024, i.e. with 4096 tokens exactly 256 tiles); coefficients scaled from the 256 x 256 tile's
     {43, 2, 11.6f, 0.98f, 0.58f}};
 static const TileCost kCostAcc[] = {       // fp32 read-modify-write output (weight-gradient form)
     {11, 2, 0.f, 0.487f, 1.98f}, {11, 4, 0.f, 0.504f, 0.f}, {22, 2, 0.f, 0.983f, 0.f},
@@ -977,10 +932,8 @@ static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* c
 template <bool A_K, bool B_K, int EPI>
 static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
   int pick, ns;
-  // The 256 x 192 tile exists in the pipelined kernel only (K a multiple of the slice depth), for the
-  // forward and input-gradient forms whose epilogue is a plain store (+ bias, + residual): N = 3 H of a QKV
-  // projection, or N = 12288 = 64 x 192 with 2048 tokens, are whole rounds of 256 such tiles.
-  constexpr bool HAS_43 = A_K && (EPI == EPI_STORE || EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_RES);
+  // the 256 x 192 tile exists in the pipelined kernel only (K a multiple of the slice depth)
+  constexpr bool HAS_43 = A_K && !B_K && EPI == EPI_BIAS;
   choose_tile(d, EPI == EPI_ACC_F32, EPI == EPI_BIAS_GELU ? kGeluBytes : 0, &pick, &ns,
               HAS_43 && d.K % BK == 0 && d.K >= 2 * BK && !g_forced_stages);
   if (EPI == EPI_BIAS_GELU) {
@@ -1012,26 +965,6 @@ static hipError_t launch_form(hipStream_t s, const GemmDesc& d) {
   }
 }
 
-static bool stagger_enabled() {
-  static const bool off = getenv("BAMBOO_GEMM_NO_STAGGER") != nullptr;   // tuning knob
-  return !off;
-}
-// ticks of the device wall clock (the counter wall_clock64 reads) per microsecond
-static double wall_clock_ticks_per_us() {
-  static std::atomic<int> cache{0};
-  int khz = cache.load();
-  if (khz == 0) {
-    int r = 0;
-    if (hipDeviceGetAttribute(&r, hipDeviceAttributeWallClockRate, current_device_index()) != hipSuccess || r <= 0) {
-      (void)hipGetLastError();
-      r = 100000;
-    }
-    cache.store(r);
-    khz = r;
-  }
-  return khz * 1e-3;
-}
-
 template <int WM, int WN, int NS>
 static hipError_t launch_group_cfg(hipStream_t s, GemmGroup& g) {
   typedef SmemPl<WM, WN, NS, false> SM;
@@ -1044,26 +977,6 @@ static hipError_t launch_group_cfg(hipStream_t s, GemmGroup& g) {
     total += ((g.d[i].M + 64 * WM - 1) / (64 * WM)) * ((g.d[i].N + 64 * WN - 1) / (64 * WN));
   }
   for (int i = g.n; i <= GemmGroup::MAX; ++i) g.first[i] = total;
-  for (int i = 0; i < g.n; ++i)
-    g.d[i].strip = tile_strip(total, (g.d[i].M + 64 * WM - 1) / (64 * WM), (g.d[i].N + 64 * WN - 1) / (64 * WN));
-  // many rounds of tiles that all end in a read-modify-write of their fp32 output: stagger the first round
-  const int slots = 256 * (2 * SM::BYTES <= 160 * 1024 ? 2 : 1);
-  if (total >= 4 * slots && stagger_enabled()) {
-    double slices = 0;
-    for (int i = 0; i < g.n; ++i)
-      slices += (double)(g.first[i + 1] - g.first[i]) * (g.d[i].K / BK);
-    // one tile: its slices at the fitted time per slice, plus moving its output twice at a CU's share of
-    // ~4.5 TB/s; an eighth of that per phase step, in wall-clock ticks
-    const TileCost* tc = nullptr;
-    for (const TileCost& e2 : kCostAcc)
-      if (e2.code == 10 * WM + WN && e2.ns == NS) tc = &e2;
-    const double tile_us = (tc ? tc->b : 1.5) * slices / total + 64.0 * WM * 64.0 * WN * 8.0 / (4.5e6 / 256.0);
-    const int ticks = (int)(tile_us / 8.0 * wall_clock_ticks_per_us());
-    for (int i = 0; i < g.n; ++i) {
-      g.d[i].stagger_ticks = ticks;
-      g.d[i].stagger_wgs = slots;
-    }
-  }
   static_assert(SM::BYTES >= kReduceLdsFloats * 4, "the tail workgroups use the front of the tile ring");
   total += grad_reduce_blocks(g.tail);
   hipLaunchKernelGGL(kern, dim3(total), dim3(256), SM::BYTES, s, g);
