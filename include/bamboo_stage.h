@@ -94,7 +94,7 @@ typedef struct {
   int32_t wrap;        /* 1: this is the last stage (stage_id == P-1) and its replica layers are the FIRST
                           stage's (Section 5.1: the last node is the first node's predecessor and fetches
                           the input samples itself).  FRC(k) then does not depend on FWD(k), and the
-                          failover schedule is the wrap-around one.  Only with rc_mode EFLB.  0 otherwise. */
+                          failover schedule is the wrap-around one.  rc_mode EFLB or LFLB.  0 otherwise. */
   int32_t data_parallel; /* 1: pure data parallelism (Section 5.2, "Support for Pure Data Parallelism"): the
                           node holds the whole model (P == 1, stage_id == 0) and its replica layers are a
                           copy of ANOTHER node's model (n_shadow == n_own).  There is no bubble: eager FRC

@@ -292,7 +292,7 @@ def wrap_victim_progress(P, M, k_fail, tick_F=1, tick_B=2):
     return nf, nb
 
 
-def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2):
+def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2, rc=EFLB):
     """Failover schedule of the last stage (s = P-1) after the first stage, whose replica it holds,
     is lost.  The last stage notices right after FWD(k_fail) and its FRC, as a middle stage does.
 
@@ -310,8 +310,13 @@ def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2):
             their outputs go to the second stage unless the victim had delivered them already.
     Communication is emitted as in the normal program: the send of what the previous computation
     of a stage produced, then the receive the next one needs, right before it.
+
+    rc = LFLB (Section 7.4's lazy variant on this stage): nothing redundant has run, so step (ii)
+    runs FRC before every BRC, and the forwards the victim had done but not yet back-propagated
+    (all delivered to the second stage already: the last stage cannot be at micro-batch k_fail
+    before the first has forwarded it) are run again right after, for their intermediates.
     """
-    assert P >= 2 and 0 <= k_fail < M
+    assert P >= 2 and 0 <= k_fail < M and rc in (LFLB, EFLB)
     s = P - 1
     C = own_slots(P, s, M)
     start, end, _ = timeline(P, M, tick_F, tick_B)
@@ -321,7 +326,11 @@ def wrap_failover_program(P, M, k_fail, tick_F=1, tick_B=2):
     for k in range(nb):
         if far:
             prog.append((RECV_GRAD, 0, k, 1))
+        if rc == LFLB:
+            prog.append((FRC, 0, k, k))
         prog.append((BRC, 0, k, k))
+    if rc == LFLB:
+        prog += [(FRC, 0, k, k) for k in range(nb, k_fail + 1)]
     own = compute_order(P, s, M)
     j0 = own.index(("F", k_fail)) + 1
     items = []                                # (start time, 0 backward / 1 forward, 0 victim / 1 own, kind, k)

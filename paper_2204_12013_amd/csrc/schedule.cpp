@@ -280,10 +280,16 @@ static std::vector<bamboo_instr_t> wrap_merge(const bamboo_cfg_t& c, int k_fail)
   if (k_fail >= 0) {
     wrap_victim_progress(c, k_fail, &n_fwd, &n_bwd);
     out.push_back(ins(BAMBOO_JOIN, 0, -1, k_fail));
+    // lazy FRC (Section 7.4): nothing redundant has run yet, so FRC precedes every replayed BRC, and the
+    // victim's forwards that were done but not yet back-propagated are run again for their intermediates
+    const bool lazy = c.rc_mode == BAMBOO_RC_LFLB;
     for (int k = 0; k < n_bwd; ++k) {
       if (far) out.push_back(ins(BAMBOO_RECV_GRAD, 0, k, 1));
+      if (lazy) out.push_back(ins(BAMBOO_FRC, 0, k, k));
       out.push_back(ins(BAMBOO_BRC, 0, k, k));
     }
+    if (lazy)
+      for (int k = n_bwd; k <= k_fail; ++k) out.push_back(ins(BAMBOO_FRC, 0, k, k));
     // what is left: own sequence behind FWD(k_fail); victim forwards beyond k_fail, victim backwards from n_bwd
     while (!(!own[io].backward && own[io].mb == k_fail)) ++io;
     ++io;

@@ -135,8 +135,12 @@ int validate(const bamboo_cfg_t* c) {
   if ((uint64_t)c->seq * c->micro_batch > (1u << 24)) return BAMBOO_E_BADCFG;
   if (c->swap_slots < 0 || c->swap_slots > c->M || (c->swap_slots > 0 && c->n_shadow <= 0)) return BAMBOO_E_BADCFG;
   if (c->wrap != 0 && c->wrap != 1) return BAMBOO_E_BADCFG;
-  // the wrap-around failover schedule exists for the paper's own variant only (eager FRC, lazy BRC)
-  if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode != BAMBOO_RC_EFLB))
+  // The wrap-around stage runs the paper's own variant (eager FRC, lazy BRC) and the lazy one.  Eager BRC is
+  // not offered there: the gradient it needs leaves the second stage a whole pipeline traversal after the
+  // last stage's own backward, so "as soon as the upstream gradient exists" has no anchor in the last
+  // stage's own instruction order -- it would have to be placed by simulated time, a scheduling policy
+  // the paper (which measures the variants on middle stages, Section 7.4) does not describe.
+  if (c->wrap && (c->P < 2 || c->stage_id != c->P - 1 || c->n_shadow <= 0 || c->rc_mode == BAMBOO_RC_EFEB))
     return BAMBOO_E_BADCFG;
   if (c->data_parallel != 0 && c->data_parallel != 1) return BAMBOO_E_BADCFG;
   // pure data parallelism: the whole model on one node, the replica is another node's model; the paper

@@ -171,9 +171,12 @@ def test_wrap_around_failover_program_equals_oracle_bit_exact():
             for k_fail in range(M):
                 assert B.stage_wrap_victim_progress(cfg, k_fail) == S.wrap_victim_progress(P, M, k_fail, tf, tb)
                 assert B.stage_failover_program(cfg, k_fail) == S.wrap_failover_program(P, M, k_fail, tf, tb), (P, M, k_fail)
+                lazy = _cfg(P, P - 1, M, S.LFLB, tick_F=tf, tick_B=tb)
+                lazy.wrap = 1
+                assert B.stage_failover_program(lazy, k_fail) == S.wrap_failover_program(P, M, k_fail, tf, tb, rc=S.LFLB)
                 n += 1
     assert n > 300
-    for bad in (dict(stage_id=1), dict(n_shadow=0), dict(rc_mode=2), dict(rc_mode=0), dict(wrap=2)):
+    for bad in (dict(stage_id=1), dict(n_shadow=0), dict(rc_mode=2), dict(wrap=2)):
         cfg = _cfg(4, 3, 4)
         cfg.wrap = 1
         for k, v in bad.items():

@@ -34,11 +34,11 @@ def _ids(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
 
 
-def _build(B, sc, V, swap_slots=0):
+def _build(B, sc, V, swap_slots=0, rc_mode=None):
     from paper_2204_12013_amd.harness import WrapHarness
     inp = synth.make_stage_inputs(sc)
     ein = synth.make_ends_inputs(sc, V)
-    cfg = B.make_cfg(sc, wrap=1, swap_slots=swap_slots)
+    cfg = B.make_cfg(sc, wrap=1, swap_slots=swap_slots, rc_mode=rc_mode)
     st = B.Stage(cfg, B.to_device(inp["own_w"].reshape(-1), sc.dtype), B.to_device(inp["shadow_w"].reshape(-1), sc.dtype))
     en = B.Ends(cfg, V, B.to_device(ein["front_w"], sc.dtype), B.to_device(ein["back_w"], sc.dtype))
     x = [B.to_device(inp["x"][k], sc.dtype) for k in range(sc.M)]
@@ -256,3 +256,47 @@ def test_ends_at_the_bert_large_size(B):
     want_gf = E.front_bwd(sc.arch, front, cf, dx0.astype(np.float64))
     _check_named(en.front_g, want_gf, lambda a: E.unpack_front(a, sc.arch, V, sc.seq, sc.hidden), tol, "front")
     en.ends_destroy()
+
+
+@pytest.mark.parametrize("name,k_fail", [("fp32_encoder", 2), ("bf16_decoder", 1), ("bf16_encoder", 3)])
+def test_lazy_frc_variant_and_the_iteration_after_the_failover(B, name, k_fail):
+    """The wrap-around stage under the lazy variant of Section 7.4 (nothing redundant runs until the first stage
+    is lost; the failover schedule then runs FRC before every BRC), and, for both variants, the iteration
+    AFTER the failover, in which the last stage executes all of the first stage's instructions (Section 5.2):
+    program equal to the oracle's, gradients bitwise those of the failure-free pair of stages."""
+    from paper_2204_12013_amd.harness import split_at_failure
+    sc, V = WRAP[name]
+    inp, ein, st0, en0, hz0 = _build(B, sc, V)            # failure-free run, eager FRC
+    hz0.begin_iteration()
+    hz0.run(st0.stage_schedule())
+    hz0.sync()
+    zs, first_g, first_front_g = _first_stage(B, sc, V, inp, ein)
+    _, _, st, en, hz = _build(B, sc, V, rc_mode=B.RC_LFLB)
+    prog = st.stage_schedule()
+    assert prog == S.stage_program(sc.P, sc.P - 1, sc.M, rc=S.LFLB) and not any(i[0] == B.FRC for i in prog)
+    hz.begin_iteration()
+    hz.run(split_at_failure(prog, k_fail))
+    merged = st.failover_merge(k_fail)
+    assert merged == S.wrap_failover_program(sc.P, sc.M, k_fail, rc=S.LFLB)
+    hz.run(merged)
+    hz.sync()
+
+    def same_as_failure_free():
+        assert torch.equal(st.own_g, st0.own_g) and torch.equal(en.back_g, en0.back_g)
+        assert torch.equal(hz.loss, hz0.loss)
+        assert torch.equal(st.shadow_g, first_g) and torch.equal(en.front_g, first_front_g)
+        for k in range(sc.M):
+            assert torch.equal(hz.gx[k], hz0.gx[k])
+            assert torch.equal(hz.z_frc[k], zs[k])
+    same_as_failure_free()
+    # the next iteration: the whole-iteration program of the merged ends of the pipeline
+    hz.begin_iteration()
+    prog2 = st.stage_schedule()
+    assert prog2 == S.wrap_merged_program(sc.P, sc.M) == B.stage_merged_program(st.cfg)
+    hz.run(prog2)
+    hz.sync()
+    same_as_failure_free()
+    for o in (st0, st):
+        o.stage_destroy()
+    for o in (en0, en):
+        o.ends_destroy()

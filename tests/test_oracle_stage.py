@@ -159,11 +159,14 @@ def test_wrap_around_failover_rebuilds_the_first_stage_gradients():
     Gv, Gfv, zv = St.wrap_first_stage_reference(arch, shadow, front, Bsz, S_len, n_h, M, ids, g1)
     for k in range(M):
         np.testing.assert_array_equal(ref.z_frc[k], zv[k])          # FRC is the first stage's forward
-    for k_fail in range(M):
+    for k_fail, rc in itertools.product(range(M), (S.EFLB, S.LFLB)):
         sim = St.WrapStageSim(*args)
-        sim.run(S.prefix_until_failure(P, P - 1, M, k_fail))
-        sim.run(S.wrap_failover_program(P, M, k_fail))
+        sim.run(S.prefix_until_failure(P, P - 1, M, k_fail, rc=rc))
+        assert rc == S.EFLB or not sim.shadow_stash              # the lazy variant has run nothing redundant
+        sim.run(S.wrap_failover_program(P, M, k_fail, rc=rc))
         assert not sim.own_stash and not sim.shadow_stash
+        for k in range(M):
+            np.testing.assert_array_equal(sim.z_frc[k], zv[k])
         for a, b in zip(sim.G_own, ref.G_own):
             for n in L.PARAM_NAMES:
                 np.testing.assert_allclose(a[n], b[n], rtol=0, atol=1e-12)
@@ -266,3 +269,34 @@ def test_data_parallel_failover_rebuilds_the_lost_nodes_gradient(rc):
         for k in range(M):
             assert np.array_equal(sim.z_frc[k], z_neigh[k])
             assert np.array_equal(sim.gx[k], ref.gx[k])
+
+
+def test_wrap_merged_iteration_equals_the_two_failure_free_stages():
+    """A whole iteration of the last stage after it has taken over the first (Section 5.2: the shadow executes
+    all of the victim's instructions): own side as in the failure-free program, replica side what the first
+    stage itself would accumulate."""
+    from oracle import ends as E
+    rng = np.random.default_rng(22)
+    arch, H, F, n_h, Bsz, S_len, V, P, M = 0, 8, 16, 2, 1, 4, 11, 4, 5
+    T = Bsz * S_len
+    mk = lambda: L.unpack_layer(rng.normal(0, 0.3, L.layer_param_count(H, F)), H, F)
+    own, shadow = [mk(), mk()], [mk()]
+    front = E.unpack_front(rng.normal(0, 0.3, E.front_param_count(arch, V, S_len, H)), arch, V, S_len, H)
+    back = E.unpack_back(rng.normal(0, 0.3, E.back_param_count(arch, V, H)), arch, V, H)
+    x = {k: rng.normal(size=(T, H)) for k in range(M)}
+    g1 = {k: rng.normal(size=(T, H)) for k in range(M)}
+    ids = {k: rng.integers(0, V, T) for k in range(M)}
+    labels = {k: rng.integers(0, V, T) for k in range(M)}
+    args = (arch, own, back, shadow, front, Bsz, S_len, n_h, P, M, x, labels, ids, g1)
+    ref = St.WrapStageSim(*args).run(S.stage_program(P, P - 1, M))
+    Gv, Gfv, zv = St.wrap_first_stage_reference(arch, shadow, front, Bsz, S_len, n_h, M, ids, g1)
+    sim = St.WrapStageSim(*args).run(S.wrap_merged_program(P, M))
+    assert not sim.own_stash and not sim.shadow_stash and sim.loss == ref.loss
+    for a, b in zip(sim.G_own, ref.G_own):
+        for n in L.PARAM_NAMES:
+            np.testing.assert_array_equal(a[n], b[n])
+    for a, b in zip(sim.G_shadow, Gv):
+        for n in L.PARAM_NAMES:
+            np.testing.assert_allclose(a[n], b[n], rtol=0, atol=1e-12)
+    for n in Gfv:
+        np.testing.assert_allclose(sim.G_front[n], Gfv[n], rtol=0, atol=1e-12)
