@@ -211,7 +211,7 @@ def _kernel_table(sites, k_p):
     return out
 
 
-def measure_core(B, synth, torch, sc, steps, warmup, two_lanes=False, cpu_baseline=True):
+def measure_core(B, synth, torch, sc, steps, warmup, two_lanes=False, cpu_baseline=True, roofline_only=False):
     """Modes A, B, C, the per-site timing and the roofline of one workload; returns (record, live objects)."""
     from paper_2204_12013_amd.harness import StageHarness
     dev = torch.device("cuda:0")
@@ -224,6 +224,15 @@ def measure_core(B, synth, torch, sc, steps, warmup, two_lanes=False, cpu_baseli
     hz = StageHarness(st, x, gz=gy, gy_table=gy)
     prog_on = st.stage_schedule()
     prog_off = [i for i in prog_on if i[0] != B.FRC]
+    if roofline_only:
+        # profiler aid: nothing but warm-up and the per-site pass, so that a kernel trace of this run averages
+        # exactly the launches the roofline block is computed from
+        prog = prog_on if two_lanes else prog_off
+        _time_iters(torch, hz, prog, warmup)
+        sites = _site_profile(B, st, torch, hz, prog, steps)
+        rec = {"config": {"workload": sc.name}, "roofline": _roofline(sc, sites, steps, two_lanes),
+               "kernel_sites": _kernel_table(sites, steps)}
+        return rec, {"st": st, "hz": hz, "x": x, "gy": gy}
     _time_iters(torch, hz, prog_on, warmup)
     ms_on = _time_iters(torch, hz, prog_on, steps)                       # mode B: the headline
     rec = {"value": M * sc.micro_batch / (ms_on * 1e-3), "unit": "samples/s", "steps": steps, "warmup": warmup,
@@ -272,6 +281,9 @@ def main():
     ap.add_argument("--profile-two-lanes", action="store_true",
                     help="run the per-site pass with FRC on (two lanes: a kernel's event time then "
                          "includes the time it shares the GPU with the other lane's kernels)")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="profiler aid: warm-up, then --steps iterations with an event pair around every launch, "
+                         "nothing else; prints the roofline block and the per-site table of the workload")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 256 MiB device copy (yardstick for the HBM byte counters)")
     args = ap.parse_args()
@@ -288,6 +300,18 @@ def main():
         return 3
     sc = synth.CONFIGS[args.workload]
     dev = torch.device("cuda:0")
+    if args.roofline_only:
+        rec, live = measure_core(B, synth, torch, sc, args.steps, args.warmup, args.profile_two_lanes, roofline_only=True)
+        if args.calibration_copy:
+            a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+            b = torch.empty_like(a)
+            a.fill_(1)
+            torch.cuda.synchronize()
+            B.bk_copy(a, b)
+            torch.cuda.synchronize()
+        live["st"].stage_destroy()
+        print(json.dumps(rec))
+        return 0
     rec, live = measure_core(B, synth, torch, sc, args.steps, args.warmup, args.profile_two_lanes)
     st, hz, x, gy, gen, act = (live[k] for k in ("st", "hz", "x", "gy", "gen", "act"))
     cfg, ms_on, ms_off, ms_c_on, us_per_tick, k_c = (live[k] for k in ("cfg", "ms_on", "ms_off", "ms_c_on", "us_per_tick", "k_c"))

@@ -34,7 +34,7 @@ def stats(path, top=24):
 
 
 def pmc(paths, copy_bytes=256 << 20):
-    gemm_bytes = {}
+    gemm_bytes, group_bytes = {}, {}
     acc = collections.defaultdict(lambda: collections.defaultdict(list))
     for path in paths:
         for r in csv.DictReader(open(path)):
@@ -52,6 +52,9 @@ def pmc(paths, copy_bytes=256 << 20):
             g = [(len(v), sum(v)) for k, v in per_kernel.items() if k.startswith("gemm_mfma")]
             if g:
                 gemm_bytes[counter] = sum(t for _, t in g) / sum(n for n, _ in g) * factor * 1024.0
+            w = [(len(v), sum(v)) for k, v in per_kernel.items() if k.startswith("gemm_mfma_pl_group_kernel")]
+            if w:
+                group_bytes[counter] = sum(t for _, t in w) / sum(n for n, _ in w) * factor * 1024.0
         items = sorted(per_kernel.items(), key=lambda kv: -sum(kv[1]))
         for k, vals in items[:20]:
             mean = sum(vals) / len(vals)
@@ -63,6 +66,10 @@ def pmc(paths, copy_bytes=256 << 20):
         print("call-weighted mean over the stage GEMM kernels (gemm_mfma*), scaled: fetch %.2f MiB + write %.2f MiB"
               % (gemm_bytes["FETCH_SIZE"] / 2 ** 20, gemm_bytes["WRITE_SIZE"] / 2 ** 20))
         print("stage_gemm_traffic_bytes_per_launch=%d" % round(sum(gemm_bytes.values())))
+    if len(group_bytes) == 2:
+        print("grouped weight-gradient launch (gemm_mfma_pl_group_kernel), scaled: fetch %.2f MiB + write %.2f MiB"
+              % (group_bytes["FETCH_SIZE"] / 2 ** 20, group_bytes["WRITE_SIZE"] / 2 ** 20))
+        print("wgrad_group_traffic_bytes_per_launch=%d" % round(sum(group_bytes.values())))
 
 
 if __name__ == "__main__":
