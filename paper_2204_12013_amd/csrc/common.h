@@ -114,6 +114,7 @@ struct GemmGroup {
   GemmDesc d[MAX];
   int first[MAX + 1];
   int n;
+  int whole_launch_ranges;   // 1: the XCD ranges are cut from the concatenated tile sequences of all problems
   GradReduceBatch tail;
 };
 
