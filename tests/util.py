@@ -43,8 +43,9 @@ def rel_l2(got, want):
     return float(np.linalg.norm((got - want).ravel()) / (denom if denom > 0 else 1.0))
 
 
-def closeness(got, want, tol):
-    """(tensor, row, element) errors, each as a fraction of its bound (<= 1 passes)."""
+def closeness(got, want, tol, elem_tol=None):
+    """(tensor, row, element) errors, each as a fraction of its bound (<= 1 passes).  elem_tol: a tolerance
+    of its own for the element bound (default: tol)."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (got.shape, want.shape)
@@ -58,7 +59,7 @@ def closeness(got, want, tol):
         row = np.sqrt(np.mean(want * want, axis=1, keepdims=True))
         col = np.sqrt(np.mean(want * want, axis=0, keepdims=True))
         scale = np.maximum(rms, row * col / rms)
-    bound = C_ELEM * tol * (scale + np.abs(want))
+    bound = C_ELEM * (tol if elem_tol is None else elem_tol) * (scale + np.abs(want))
     with np.errstate(divide="ignore", invalid="ignore"):
         frac = np.where(bound > 0, np.abs(err) / bound, np.where(err == 0, 0.0, np.inf))
     e = float(frac.max()) if frac.size else 0.0
@@ -75,9 +76,9 @@ def closeness(got, want, tol):
     return t, r, e
 
 
-def assert_close(got, want, tol, label=""):
+def assert_close(got, want, tol, label="", elem_tol=None):
     """The three bounds of the module docstring; returns the tensor-level relative L2 error."""
-    t, r, e = closeness(got, want, tol)
+    t, r, e = closeness(got, want, tol, elem_tol)
     key = str(label).split(":")[0] if label else "unlabelled"
     w = WORST.setdefault(key, [0.0, 0.0, 0.0])
     w[0], w[1], w[2] = max(w[0], t), max(w[1], r), max(w[2], e)
@@ -88,7 +89,8 @@ def assert_close(got, want, tol, label=""):
         g, w_ = np.asarray(got, dtype=np.float64)[i], np.asarray(want, dtype=np.float64)[i]
         rms = float(np.sqrt(np.mean(np.asarray(want, dtype=np.float64) ** 2)))
         raise AssertionError("%s: worst element error is %.2f of its bound (%.1f x %.1e x (scale + |value|)): element %s got %.6g "
-                             "want %.6g, tensor rms %.4g" % (label, e, C_ELEM, tol, tuple(int(v) for v in i), g, w_, rms))
+                             "want %.6g, tensor rms %.4g" % (label, e, C_ELEM, tol if elem_tol is None else elem_tol,
+                                                              tuple(int(v) for v in i), g, w_, rms))
     return t * tol
 
 
