@@ -245,6 +245,14 @@ def test_rc_variants_recover_the_failure_free_gradients(B, name, k_fail, rc):
     for k in range(sc.M):
         assert torch.equal(hz2.gx[k], hz0.gx[k])
         assert torch.equal(hz2.z_frc[k], hz0.z_succ[k])
+    # the iteration after the failover is the same merged program whatever ran eagerly before
+    hz2.begin_iteration()
+    assert st2.stage_schedule() == S.merged_program(sc.P, sc.stage_id, sc.M)
+    hz2.run(st2.stage_schedule())
+    hz2.sync()
+    assert torch.equal(st2.own_g, st0.own_g) and torch.equal(st2.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz2.gx[k], hz0.gx[k]) and torch.equal(hz2.z_frc[k], hz0.z_succ[k])
     for s_ in (st0, hz0.succ, st1, hz1.succ, st2, hz2.succ):
         s_.stage_destroy()
 

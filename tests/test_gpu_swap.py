@@ -86,6 +86,14 @@ def test_failover_from_the_host_copy_recovers_the_failure_free_gradients(B, name
     assert torch.equal(st.shadow_g, hz0.succ.own_g)
     for k in range(sc.M):
         assert torch.equal(hz.gx[k], hz0.gx[k])
+    # the next iteration runs the merged stage's whole program, its FRC results swapped out and back in as before
+    hz.begin_iteration()
+    assert st.stage_schedule() == S.merged_program(sc.P, sc.stage_id, sc.M)
+    hz.run(st.stage_schedule())
+    hz.sync()
+    assert torch.equal(st.own_g, st0.own_g) and torch.equal(st.shadow_g, hz0.succ.own_g)
+    for k in range(sc.M):
+        assert torch.equal(hz.gx[k], hz0.gx[k])
     if rc == "EFLB" and name != "ragged_fp32_causal":    # and against the oracle, at the stated tolerance
         ref = _oracle(sc, inp, k_fail)
         check_grads(st.own_g.cpu().numpy(), ref.G_own, sc.hidden, sc.ffn, TOL[sc.dtype], "own")
