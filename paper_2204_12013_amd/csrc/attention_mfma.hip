@@ -15,12 +15,18 @@
 // Backward recomputes the probabilities from the log-sum-exp and uses no
 // atomics: one kernel owns query rows (dQ), one owns key rows (dK, dV), so the
 // result is bitwise reproducible.
+#include <type_traits>
+
 #include "common.h"
 
 namespace bamboo {
 
+#define BAMBOO_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) unsigned uint4_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -42,27 +48,58 @@ __device__ __forceinline__ void block_of(int nblk, int nbh, int* blk, int* bh) {
   *blk = (CAUSAL && HEAVY_LAST) ? nblk - 1 - i : i;
 }
 
+// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): loop indices the callee can use as constants
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>());
+    static_for<B + 1, E>(f);
+  }
+}
+
 // ---- cooperative copy of 64 rows x D (bf16) global -> registers -> LDS -------------
+// Rows at or beyond row_lim are read from row row_lim - 1 (finite values that the consumers' masks turn
+// into exact zeros): no load sits behind a branch, so a wavefront's loads retire in a known order and an
+// older tile can be waited for while a younger one is still in flight.  A thread's byte offsets inside a
+// tile and their upper limits (the same chunk in the last valid row) are computed once; per tile and chunk
+// an add and a min remain.  Offsets are 32-bit: the launcher checks that a sequence stays below 4 GiB.
 template <int D>
-struct RowTile {
+struct TileAddr {
   static constexpr int N = TILE * D / 8 / 256;   // 16-byte chunks per thread
-  bf16x8 v[N];
-  __device__ __forceinline__ void fetch(const bf16_t* g, long row_stride, int row0, int row_lim) {
+  unsigned ofs[N], last[N];
+  unsigned tile_bytes;                           // 64 rows
+  __device__ __forceinline__ void init(long row_stride, int row_lim) {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const int c = threadIdx.x + i * 256;
-      const int row = c / (D / 8), ch = (c % (D / 8)) * 8;
-      bf16x8 t = {};
-      if (row0 + row < row_lim) t = *(const bf16x8*)(g + (long)(row0 + row) * row_stride + ch);
-      v[i] = t;
+      const unsigned col = (unsigned)((c % (D / 8)) * 8) * 2u;
+      ofs[i] = (unsigned)(c / (D / 8)) * (unsigned)row_stride * 2u + col;
+      last[i] = (unsigned)(row_lim - 1) * (unsigned)row_stride * 2u + col;
     }
+    tile_bytes = (unsigned)TILE * (unsigned)row_stride * 2u;
+  }
+};
+template <int D>
+struct RowTile {
+  static constexpr int N = TileAddr<D>::N;
+  bf16x8 v[N];
+  // tile: index of the 64-row tile counted from g (uniform)
+  __device__ __forceinline__ void fetch(const bf16_t* g, const TileAddr<D>& ta, int tile) {
+    const unsigned t0 = (unsigned)tile * ta.tile_bytes;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = *(const bf16x8*)((const char*)g + min(t0 + ta.ofs[i], ta.last[i]));
   }
   __device__ __forceinline__ void stash(bf16_t* s, int ld) const {
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-      const int c = threadIdx.x + i * 256;
-      *(bf16x8*)(s + (c / (D / 8)) * ld + (c % (D / 8)) * 8) = v[i];
-    }
+    for (int i = 0; i < N; ++i) stash_one(i, s, ld);
+  }
+  // one chunk at a time, for callers that spread a tile's loads and LDS writes over their schedule
+  __device__ __forceinline__ void fetch_one(int i, const bf16_t* g, const TileAddr<D>& ta, int tile) {
+    v[i] = *(const bf16x8*)((const char*)g + min((unsigned)tile * ta.tile_bytes + ta.ofs[i], ta.last[i]));
+  }
+  __device__ __forceinline__ void stash_one(int i, bf16_t* s, int ld) const {
+    const int c = threadIdx.x + i * 256;
+    *(bf16x8*)(s + (c / (D / 8)) * ld + (c % (D / 8)) * 8) = v[i];
   }
 };
 
@@ -91,6 +128,14 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& t, int half) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = (bf16_t)t[8 * half + j];
   return o;
+}
+// the value the lane 32 places away holds (v_permlane32_swap: no trip through LDS)
+__device__ __forceinline__ float other_half(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // r[0]: lanes 0..31 keep theirs, lanes 32..63 receive the lower half's; r[1]: the other way round
+  const unsigned lo = r[0], hi = r[1];
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? lo : hi);
 }
 // row index inside a 32x32 accumulator tile of register r for this lane
 __device__ __forceinline__ int acc_row(int r) { return 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3); }
@@ -213,8 +258,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
   const int kend = CAUSAL ? min(S, q0 + 128) : S;
   const int nt = (kend + TILE - 1) / TILE;
   RowTile<D> kt_regs, vt_regs;
-  kt_regs.fetch(base + H, rs, 0, S);
-  vt_regs.fetch(base + 2 * H, rs, 0, S);
+  TileAddr<D> ta;
+  ta.init(rs, S);
+  kt_regs.fetch(base + H, ta, 0);
+  vt_regs.fetch(base + 2 * H, ta, 0);
   kt_regs.stash(Ks, LDK);
   vt_regs.stash(Vs, LDV);
   __syncthreads();
@@ -223,8 +270,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
     const bf16_t* vs_ = Vs + (t & 1) * TILE * LDV;
     const int k0 = t * TILE;
     if (t + 1 < nt) {
-      kt_regs.fetch(base + H, rs, k0 + TILE, S);
-      vt_regs.fetch(base + 2 * H, rs, k0 + TILE, S);
+      kt_regs.fetch(base + H, ta, t + 1);
+      vt_regs.fetch(base + 2 * H, ta, t + 1);
     }
     if (!CAUSAL || k0 <= qw0 + 31) {              // wave-uniform: tile not entirely above the diagonal
       f32x16 s[2];
@@ -261,7 +308,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[u][r]);
         mx *= c;
       }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = fmaxf(mx, other_half(mx));
       const bool grow = mx > m_i + 8.f;
       if (__builtin_amdgcn_ballot_w64(grow) != 0) {
         const float m_new = grow ? mx : m_i;
@@ -273,30 +320,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnDesc a) {
 #pragma unroll
           for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
       }
-      float ls = 0.f;
       if (need_mask) {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(s[u][r] - m_i);
-            s[u][r] = p;
-            ls += p;
-          }
+          for (int r = 0; r < 16; ++r) s[u][r] = __builtin_amdgcn_exp2f(s[u][r] - m_i);
       } else {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -m_i));
-            s[u][r] = p;
-            ls += p;
-          }
+          for (int r = 0; r < 16; ++r) s[u][r] = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -m_i));
       }
-      l_i += ls;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const bf16x8 pb = pack8(s[u >> 1], u & 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) l_i += s[u >> 1][8 * (u & 1) + j];
 #pragma unroll
         for (int dt = 0; dt < D / 32; ++dt)
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(vs_, LDV, dt * 32, 16 * u), pb, o[dt], 0, 0, 0);
@@ -359,12 +398,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[dt][r] = 0.f;
+  // the dP MFMAs start from -delta (a per-lane constant here: a lane owns a query), so their accumulator
+  // comes out as dP - delta
+  f32x16 neg_delta, zero16;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    neg_delta[r] = -delta;
+    zero16[r] = 0.f;
+  }
 
   const int kend = CAUSAL ? min(S, q0 + 128) : S;
   const int nt = (kend + TILE - 1) / TILE;
   RowTile<D> kt_regs, vt_regs;
-  kt_regs.fetch(base + H, rs, 0, S);
-  vt_regs.fetch(base + 2 * H, rs, 0, S);
+  TileAddr<D> ta;
+  ta.init(rs, S);
+  kt_regs.fetch(base + H, ta, 0);
+  vt_regs.fetch(base + 2 * H, ta, 0);
   kt_regs.stash(Ks, LD);
   vt_regs.stash(Vs, LD);
   __syncthreads();
@@ -373,21 +422,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
     const bf16_t* vs_ = Vs + (t & 1) * TILE * LD;
     const int k0 = t * TILE;
     if (t + 1 < nt) {
-      kt_regs.fetch(base + H, rs, k0 + TILE, S);
-      vt_regs.fetch(base + 2 * H, rs, k0 + TILE, S);
+      kt_regs.fetch(base + H, ta, t + 1);
+      vt_regs.fetch(base + 2 * H, ta, t + 1);
     }
     if (!CAUSAL || k0 <= qw0 + 31) {
       f32x16 s[2], dp[2];
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[u][r] = 0.f; dp[u][r] = 0.f; }
-#pragma unroll
       for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(ks_, LD, u * 32, ks), qf[ks], s[u], 0, 0, 0);
-          dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(vs_, LD, u * 32, ks), dof[ks], dp[u], 0, 0, 0);
+          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(ks_, LD, u * 32, ks), qf[ks], ks == 0 ? zero16 : s[u], 0, 0, 0);
+          dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(vs_, LD, u * 32, ks), dof[ks], ks == 0 ? neg_delta : dp[u], 0,
+                                                          0, 0);
         }
       const bool need_mask = (k0 + TILE > S) || (CAUSAL && k0 + TILE - 1 > qw0);
       if (need_mask) {                            // uniform over the wavefront
@@ -398,14 +444,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnDesc a) {
             float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -lse2));
             const int key = k0 + u * 32 + acc_row(r);
             if (key >= S || (CAUSAL && key > query)) p = 0.f;
-            s[u][r] = p * (dp[u][r] - delta);     // dS^T
+            s[u][r] = p * dp[u][r];               // dS^T
           }
       } else {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-          for (int r = 0; r < 16; ++r)
-            s[u][r] = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -lse2)) * (dp[u][r] - delta);
+          for (int r = 0; r < 16; ++r) s[u][r] = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -lse2)) * dp[u][r];
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
@@ -473,7 +518,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
     if (threadIdx.x < TILE) {
       const int q = q0t + threadIdx.x;
       lse_r = q < S ? lse_g[q] * kLog2e : 0.f;
-      del_r = q < S ? del_g[q] : 0.f;
+      del_r = q < S ? -del_g[q] : 0.f;             // negated: the dP accumulators start from it
     }
   };
   auto stash_stats = [&](int buf) {
@@ -482,8 +527,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
       del_s[buf * TILE + threadIdx.x] = del_r;
     }
   };
-  q_regs.fetch(base, rs, qbeg, S);
-  do_regs.fetch(dbase, H, qbeg, S);
+  TileAddr<D> ta_q, ta_do;
+  ta_q.init(rs, S);
+  ta_do.init(H, S);
+  q_regs.fetch(base, ta_q, qbeg / TILE);
+  do_regs.fetch(dbase, ta_do, qbeg / TILE);
   fetch_stats(qbeg);
   q_regs.stash(Qs, LD);
   do_regs.stash(dOs, LD);
@@ -495,21 +543,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
     const bf16_t* dos_ = dOs + buf * TILE * LD;
     const int q0t = qbeg + t * TILE;
     if (t + 1 < nt) {
-      q_regs.fetch(base, rs, q0t + TILE, S);
-      do_regs.fetch(dbase, H, q0t + TILE, S);
+      q_regs.fetch(base, ta_q, qbeg / TILE + t + 1);
+      do_regs.fetch(dbase, ta_do, qbeg / TILE + t + 1);
       fetch_stats(q0t + TILE);
     }
     if (!CAUSAL || q0t + TILE - 1 >= kw0) {       // wave-uniform: some query at or after the wave's first key
+      // the queries' -delta runs along the accumulator registers here and comes from LDS with the tile: the
+      // dP accumulators start from it and come out as dP - delta
       f32x16 s[2], dp[2];
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) { s[u][r] = 0.f; dp[u][r] = 0.f; }
+        for (int a4 = 0; a4 < 4; ++a4) {
+          const f32x4 d4 = *(const f32x4*)(del_s + buf * TILE + u * 32 + 8 * a4 + 4 * g);
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) dp[u][4 * a4 + cc] = d4[cc];
+        }
+      const f32x16 zero16 = {};
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(qs_, LD, u * 32, ks), kf[ks], s[u], 0, 0, 0);
+          s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(qs_, LD, u * 32, ks), kf[ks], ks == 0 ? zero16 : s[u], 0, 0, 0);
           dp[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_k(dos_, LD, u * 32, ks), vf[ks], dp[u], 0, 0, 0);
         }
       const bool need_mask = (q0t + TILE > S) || (kw0 + 32 > S) || (CAUSAL && q0t < kw0 + 31);
@@ -519,7 +574,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
         for (int a4 = 0; a4 < 4; ++a4) {
           const int row = u * 32 + 8 * a4 + 4 * g;   // first of 4 consecutive query rows of this lane
           const f32x4 l4 = *(const f32x4*)(lse_s + buf * TILE + row);
-          const f32x4 d4 = *(const f32x4*)(del_s + buf * TILE + row);
           if (need_mask) {                        // uniform over the wavefront
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) {
@@ -528,7 +582,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
               const int query = q0t + row + cc;
               if (query >= S || key >= S || (CAUSAL && key > query)) p = 0.f;
               s[u][r] = p;
-              dp[u][r] = p * (dp[u][r] - d4[cc]);    // dS
+              dp[u][r] *= p;                      // dS
             }
           } else {
 #pragma unroll
@@ -536,7 +590,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
               const int r = 4 * a4 + cc;
               const float p = __builtin_amdgcn_exp2f(fmaf(s[u][r], c, -l4[cc]));
               s[u][r] = p;
-              dp[u][r] = p * (dp[u][r] - d4[cc]);    // dS
+              dp[u][r] *= p;                      // dS
             }
           }
         }
@@ -578,6 +632,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
 // ------------------------------------------------------------------ launchers
 static bool covered(const AttnDesc& a) {
   if (a.d != 64 && a.d != 128) return false;
+  if ((long)a.S * 3 * a.heads * a.d * 2 >= (1L << 32)) return false;   // 32-bit byte offsets inside one sequence
   auto misaligned = [](const void* p) { return p != nullptr && ((uintptr_t)p & 15) != 0; };
   return !(misaligned(a.qkv) || misaligned(a.ctx) || misaligned(a.dctx) || misaligned(a.dqkv));
 }

@@ -262,5 +262,8 @@ def test_attention_forward_backward(B, dtype, impl, causal, batch, seq, heads, d
     dqkv = _empty((T, 3 * H), dtype)
     B.bk_attention_bwd(dq, ctx, lse, _dev(B, dctx, dtype), dqkv, batch, seq, heads, causal, impl=impl)
     got = B.to_host(dqkv)
+    # a one-token sequence has dq = dk = 0 by cancellation (dP = delta): the three slices share the scale of
+    # the terms they sum, that of the whole gradient
+    floor = float(np.sqrt(np.mean(dqkv_ref ** 2))) if seq == 1 else 0.0
     for name, sl in (("dq", slice(0, H)), ("dk", slice(H, 2 * H)), ("dv", slice(2 * H, 3 * H))):
-        assert_close(got[:, sl], dqkv_ref[:, sl], TOL[dtype], "kernels got[:, sl] %s" % (name,))
+        assert_close(got[:, sl], dqkv_ref[:, sl], TOL[dtype], "kernels got[:, sl] %s" % (name,), floor=floor)

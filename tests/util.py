@@ -43,22 +43,28 @@ def rel_l2(got, want):
     return float(np.linalg.norm((got - want).ravel()) / (denom if denom > 0 else 1.0))
 
 
-def closeness(got, want, tol, elem_tol=None):
+def closeness(got, want, tol, elem_tol=None, floor=0.0):
     """(tensor, row, element) errors, each as a fraction of its bound (<= 1 passes).  elem_tol: a tolerance
-    of its own for the element bound (default: tol)."""
+    of its own for the element bound (default: tol).  floor: the size of the terms the elements sum, where the
+    expected values themselves say nothing about it (a slice that is exactly zero by cancellation: the query
+    gradient of a one-token sequence is P (dP - delta) with dP = delta); the scales of the row and element
+    bounds are then at least this."""
     got = np.asarray(got, dtype=np.float64)
     want = np.asarray(want, dtype=np.float64)
     assert got.shape == want.shape, (got.shape, want.shape)
     err = got - want
     if not np.all(np.isfinite(err)):
         return float("inf"), float("inf"), float("inf")
-    t = rel_l2(got, want) / tol
+    if floor > 0:
+        t = float(np.linalg.norm(err.ravel()) / max(np.linalg.norm(want.ravel()), floor * np.sqrt(want.size))) / tol
+    else:
+        t = rel_l2(got, want) / tol
     rms = float(np.sqrt(np.mean(want * want))) if want.size else 0.0
-    scale = rms
+    scale = max(rms, floor)
     if want.ndim == 2 and rms > 0:
         row = np.sqrt(np.mean(want * want, axis=1, keepdims=True))
         col = np.sqrt(np.mean(want * want, axis=0, keepdims=True))
-        scale = np.maximum(rms, row * col / rms)
+        scale = np.maximum(max(rms, floor), row * col / rms)
     bound = C_ELEM * (tol if elem_tol is None else elem_tol) * (scale + np.abs(want))
     with np.errstate(divide="ignore", invalid="ignore"):
         frac = np.where(bound > 0, np.abs(err) / bound, np.where(err == 0, 0.0, np.inf))
@@ -67,8 +73,8 @@ def closeness(got, want, tol, elem_tol=None):
     r = 0.0
     if want.ndim == 2 and want.shape[0] > 1:
         wn = np.linalg.norm(want, axis=1)
-        floor = float(np.sqrt(np.mean(wn * wn)))
-        den = C_ROW * tol * np.maximum(wn, floor)
+        row_floor = max(float(np.sqrt(np.mean(wn * wn))), floor * np.sqrt(want.shape[1]))
+        den = C_ROW * tol * np.maximum(wn, row_floor)
         en = np.linalg.norm(err, axis=1)
         with np.errstate(divide="ignore", invalid="ignore"):
             rf = np.where(den > 0, en / den, np.where(en == 0, 0.0, np.inf))
@@ -76,9 +82,9 @@ def closeness(got, want, tol, elem_tol=None):
     return t, r, e
 
 
-def assert_close(got, want, tol, label="", elem_tol=None):
+def assert_close(got, want, tol, label="", elem_tol=None, floor=0.0):
     """The three bounds of the module docstring; returns the tensor-level relative L2 error."""
-    t, r, e = closeness(got, want, tol, elem_tol)
+    t, r, e = closeness(got, want, tol, elem_tol, floor)
     key = str(label).split(":")[0] if label else "unlabelled"
     w = WORST.setdefault(key, [0.0, 0.0, 0.0])
     w[0], w[1], w[2] = max(w[0], t), max(w[1], r), max(w[2], e)
