@@ -15,18 +15,12 @@
 // Backward recomputes the probabilities from the log-sum-exp and uses no
 // atomics: one kernel owns query rows (dQ), one owns key rows (dK, dV), so the
 // result is bitwise reproducible.
-#include <type_traits>
-
 #include "common.h"
 
 namespace bamboo {
 
-#define BAMBOO_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(4))) unsigned uint4_t;
 typedef __attribute__((ext_vector_type(4))) short short4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -48,21 +42,11 @@ __device__ __forceinline__ void block_of(int nblk, int nbh, int* blk, int* bh) {
   *blk = (CAUSAL && HEAVY_LAST) ? nblk - 1 - i : i;
 }
 
-// f(integral_constant<int, B>), ..., f(integral_constant<int, E - 1>): loop indices the callee can use as constants
-template <int B, int E, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(std::integral_constant<int, B>());
-    static_for<B + 1, E>(f);
-  }
-}
-
 // ---- cooperative copy of 64 rows x D (bf16) global -> registers -> LDS -------------
 // Rows at or beyond row_lim are read from row row_lim - 1 (finite values that the consumers' masks turn
-// into exact zeros): no load sits behind a branch, so a wavefront's loads retire in a known order and an
-// older tile can be waited for while a younger one is still in flight.  A thread's byte offsets inside a
-// tile and their upper limits (the same chunk in the last valid row) are computed once; per tile and chunk
-// an add and a min remain.  Offsets are 32-bit: the launcher checks that a sequence stays below 4 GiB.
+// into exact zeros), so no load sits behind a branch.  A thread's byte offsets inside a tile and their
+// upper limits (the same chunk in the last valid row) are computed once; per tile and chunk an add and a
+// min remain.  Offsets are 32-bit: the launcher checks that a sequence stays below 4 GiB.
 template <int D>
 struct TileAddr {
   static constexpr int N = TILE * D / 8 / 256;   // 16-byte chunks per thread
@@ -91,15 +75,10 @@ struct RowTile {
   }
   __device__ __forceinline__ void stash(bf16_t* s, int ld) const {
 #pragma unroll
-    for (int i = 0; i < N; ++i) stash_one(i, s, ld);
-  }
-  // one chunk at a time, for callers that spread a tile's loads and LDS writes over their schedule
-  __device__ __forceinline__ void fetch_one(int i, const bf16_t* g, const TileAddr<D>& ta, int tile) {
-    v[i] = *(const bf16x8*)((const char*)g + min((unsigned)tile * ta.tile_bytes + ta.ofs[i], ta.last[i]));
-  }
-  __device__ __forceinline__ void stash_one(int i, bf16_t* s, int ld) const {
-    const int c = threadIdx.x + i * 256;
-    *(bf16x8*)(s + (c / (D / 8)) * ld + (c % (D / 8)) * 8) = v[i];
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      *(bf16x8*)(s + (c / (D / 8)) * ld + (c % (D / 8)) * 8) = v[i];
+    }
   }
 };
 
