@@ -214,6 +214,21 @@ def test_layernorm_forward_backward(B, dtype, T, H):
     assert_close(dg.cpu().numpy(), 2 * dg_ref, 1e-4, "kernels dg.cpu().numpy()")
 
 
+def test_mfma_attention_refuses_sequences_beyond_its_32_bit_tile_offsets(B):
+    # the MFMA kernels address a (batch, head) slice of qkv with 32-bit byte offsets: a sequence whose rows span
+    # 4 GiB or more is refused when the kernels are forced, nothing is launched
+    heads, d = 96, 128
+    seq = (1 << 32) // (3 * heads * d * 2) + 1
+    qkv = torch.empty((seq, 3 * heads * d), dtype=torch.bfloat16, device=DEV)
+    ctx = torch.empty((seq, heads * d), dtype=torch.bfloat16, device=DEV)
+    lse = torch.empty(heads * seq, dtype=torch.float32, device=DEV)
+    with pytest.raises(B.BambooError) as e:
+        B.bk_attention_fwd(qkv, ctx, lse, 1, seq, heads, 1, impl=2)
+    assert e.value.status == B.E_STATE
+    del qkv, ctx, lse
+    torch.cuda.empty_cache()
+
+
 ATTN_CASES = [(2, 16, 2, 32), (1, 100, 3, 64), (2, 200, 2, 128), (3, 77, 2, 40), (1, 512, 2, 64), (1, 300, 1, 128),
               (1, 1, 1, 64), (1, 129, 2, 64), (1, 8, 1, 128)]
 
