@@ -611,7 +611,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma_kernel(AttnDesc a) {
 // ------------------------------------------------------------------ launchers
 static bool covered(const AttnDesc& a) {
   if (a.d != 64 && a.d != 128) return false;
-  if ((long)a.S * 3 * a.heads * a.d * 2 >= (1L << 32)) return false;   // 32-bit byte offsets inside one sequence
+  // 32-bit byte offsets inside one sequence, the rows of a last, partial tile included (they are clamped after the add)
+  if ((long)(a.S + TILE) * 3 * a.heads * a.d * 2 >= (1L << 32)) return false;
   auto misaligned = [](const void* p) { return p != nullptr && ((uintptr_t)p & 15) != 0; };
   return !(misaligned(a.qkv) || misaligned(a.ctx) || misaligned(a.dctx) || misaligned(a.dqkv));
 }
