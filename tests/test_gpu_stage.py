@@ -534,3 +534,47 @@ def test_pure_data_parallel_node_matches_oracle_and_recovers_the_peers_gradient(
         st.stage_destroy()
     for s_ in (st0, peer):
         s_.stage_destroy()
+
+
+def test_two_stages_driven_from_two_threads_give_the_results_of_sequential_runs(B):
+    """The header allows one thread per stage, any number of stages per process: the launch state the library
+    keeps per process (tile and ring choices, the activation table, the LDS size attributes of its kernels) must
+    not care which thread gets there first.  Two different stages run three iterations each, concurrently, and
+    must reproduce bitwise what each gives when it runs alone."""
+    import threading
+    names = ["bf16_post_ln", "bf16_causal_d128"]
+
+    def run_one(name, out):
+        try:
+            sc = SMALL[name]
+            inp, st, hz = _build(B, sc)
+            prog = st.stage_schedule()
+            for _ in range(3):
+                hz.begin_iteration()
+                hz.run(prog)
+            hz.sync()
+            torch.cuda.synchronize()
+            out[name] = ([t.clone() for t in hz.y] + [t.clone() for t in hz.z_frc] + [t.clone() for t in hz.gx],
+                         st.own_g.clone(), hz.succ.own_g.clone())
+            st.stage_destroy()
+            hz.succ.stage_destroy()
+        except Exception as e:          # surfaces in the main thread below
+            out[name] = e
+
+    alone, together = {}, {}
+    # the threads go first: in a fresh process they also race for the one-time set-up
+    threads = [threading.Thread(target=run_one, args=(n, together)) for n in names]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+        assert not t.is_alive()
+    for n in names:
+        run_one(n, alone)
+    for n in names:
+        for res in (alone[n], together[n]):
+            if isinstance(res, Exception):
+                raise res
+        (acts_a, g_a, gs_a), (acts_t, g_t, gs_t) = alone[n], together[n]
+        assert all(torch.equal(a, b) for a, b in zip(acts_a, acts_t)), n
+        assert torch.equal(g_a, g_t) and torch.equal(gs_a, gs_t), n
