@@ -100,6 +100,10 @@ struct GemmDesc {
   // column-sum launch behind them).
   float* tile_colsum;
   int* tile_colsum_parts;
+  // Launch hint (does not change the result): the launch shares the chip with another stream's kernels, which
+  // take whatever CUs it leaves idle, so the tile that costs the least CU time is the best one, not the
+  // one that finishes first on an empty chip.
+  int shared_chip;
 };
 
 // Ordered final sums of partial rows (see launch_grad_reduce below): out0[c] += sum_y p0[y][c] over `parts`

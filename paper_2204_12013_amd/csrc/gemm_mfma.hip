@@ -918,6 +918,7 @@ static const TileCost kCostAcc[] = {       // fp32 read-modify-write output (wei
     {42, 2, 0.f, 1.102f, 11.56f}, {42, 3, 0.f, 0.997f, 4.55f}, {44, 2, 0.f, 1.737f, 0.f}};
 
 static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* code, int* ns, bool offer_43 = false) {
+  const bool by_work = d.shared_chip != 0;
   const int nk = d.K / BK;
   const TileCost* tab = acc_form ? kCostAcc : kCostStore;
   const int ntab = acc_form ? (int)(sizeof(kCostAcc) / sizeof(kCostAcc[0])) : (int)(sizeof(kCostStore) / sizeof(kCostStore[0]));
@@ -936,7 +937,10 @@ static void choose_tile(const GemmDesc& d, bool acc_form, long extra_lds, int* c
     if (lds > 160 * 1024) continue;
     const long slots = 256 * (2 * lds <= 160 * 1024 ? 2 : 1);
     const long rounds = (tiles + slots - 1) / slots;
-    const float cost = rounds * (t.a + t.b * nk) + t.c;
+    // alone on the chip: rounds of tiles.  Beside another stream's kernels: CU time summed over the tiles, but
+    // no shape that leaves fewer than 128 tiles where another offers more -- the launch still has to finish
+    // (measured: with 64-tile launches on the second lane that lane becomes the critical path).
+    const float cost = by_work ? (float)(tiles < 128 ? 4 * 256 : tiles) * (t.a + t.b * nk) : rounds * (t.a + t.b * nk) + t.c;
     if (!found || cost < best) {
       found = true;
       best = cost;

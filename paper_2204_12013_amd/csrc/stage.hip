@@ -268,7 +268,13 @@ enum KernelClass {
 };
 
 // site: which GEMM of the layer pass this is (for the per-site timing)
-int p_gemm(bamboo_stage* st, hipStream_t s, int site, const GemmDesc& d) {
+int p_gemm(bamboo_stage* st, hipStream_t s, int site, const GemmDesc& d0) {
+  GemmDesc d = d0;
+  // Lane 1 runs beside lane 0, which is rarely idle: what its launches leave unused, lane 0 takes, so its forward
+  // GEMMs are shaped for the least CU time.  Every tile shape gives the same output bits, so FRC still equals the
+  // successor's forward; the input-gradient launches keep the one choice, because the column sums that ride in
+  // their epilogue are partitioned by the tile rows.
+  d.shared_chip = s == st->lane[1] && s != st->lane[0] && site <= K_GEMM_FFN2 ? 1 : 0;
   ProfScope ps(st, site, s, gemm_flops(d));
   HIPCHK(launch_gemm(s, st->cfg.dtype, d));
   return BAMBOO_OK;
